@@ -1,0 +1,223 @@
+/*
+ * deeprebirth.h - C ABI of the MI355X (gfx950) forward-pass library for CNN blocks in the two
+ * forms of the DeepRebirth paper: the original form (convolution followed by the non-tensor
+ * layers ReLU / LRN / max-pool / concat / BatchNorm) and the slim form (one strided conv + ReLU per
+ * streamline block, two tensor branches per inception module, BatchNorm folded into the conv).
+ *
+ * Conventions common to every entry point
+ *   - Tensors: activations are dense NCHW, weights are dense KCRS (output channel, input channel,
+ *     filter row, filter column), biases and per-channel vectors are dense K.  DR_F32 tensors hold
+ *     IEEE binary32; DR_BF16 tensors hold bfloat16 (upper half of a binary32) and are computed with
+ *     fp32 accumulation and round-to-nearest-even on store.  Biases and BatchNorm vectors are
+ *     always fp32.
+ *   - Pointers named x, y, w, bias, ws, params[i] are DEVICE pointers owned by the caller; the
+ *     library never allocates, frees or retains them.  Descriptor structs are HOST memory, read
+ *     during the call only.  x and y must not overlap unless an entry point says otherwise.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every entry point
+ *     validates its arguments on the host first, then enqueues its kernels on `stream` and
+ *     returns without synchronising.
+ *   - Return value: DR_OK or a dr_status error; on error nothing has been enqueued (except
+ *     DR_ERR_HIP, which reports a failed launch) and dr_last_error() holds a message for the
+ *     calling thread.  No C++ exception crosses this boundary.
+ */
+#ifndef DEEPREBIRTH_H
+#define DEEPREBIRTH_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DR_OK = 0,
+    DR_ERR_NULL = 1,        /* a required pointer is NULL */
+    DR_ERR_SHAPE = 2,       /* inconsistent dimensions, or the output descriptor is not the layer's output shape */
+    DR_ERR_UNSUPPORTED = 3, /* dtype / parameter combination the library has no kernel for */
+    DR_ERR_WORKSPACE = 4,   /* workspace missing or too small */
+    DR_ERR_HIP = 5          /* the HIP runtime reported an error */
+} dr_status;
+
+typedef enum { DR_F32 = 0, DR_BF16 = 1 } dr_dtype;
+
+/* Feature map X^i / Y (Sec. 3.1): batch n of c channels of h x w, NCHW. */
+typedef struct { int n, c, h, w; int dtype; } dr_tensor;
+
+/* Convolution layer f_conv(W, b) (Sec. 3.1 Eq. (3), Eq. (7)): k filters over c channels, r x s taps.
+ * relu != 0 fuses max(.,0) into the store. */
+typedef struct { int k, c, r, s, stride_h, stride_w, pad_h, pad_w, relu; } dr_conv;
+
+/* LRN layer f_LRN (Sec. 3.1 Eq. (3)): across-channel window of local_size channels. */
+typedef struct { int local_size; float alpha, beta, k; } dr_lrn;
+
+/* Pooling layer f_pooling(p) (Sec. 3.1 Eq. (3)): kh x kw window. */
+typedef struct { int kh, kw, stride_h, stride_w, pad_h, pad_w; } dr_pool;
+
+/* ---- shape rules (host only, no GPU needed) ------------------------------------------------- */
+
+/* Convolution output size along one axis: floor((in + 2 pad - filt) / stride) + 1 (0 if the
+ * filter does not fit). */
+int dr_conv_out_size(int in, int filt, int stride, int pad);
+
+/* Pooling output size along one axis: ceil((in + 2 pad - win) / stride) + 1, minus one if the
+ * last window would start beyond the input and its left padding. */
+int dr_pool_out_size(int in, int win, int stride, int pad);
+
+/* ---- single layers ------------------------------------------------------------------------------ */
+
+/* Convolution, Eq. (7): y[n, y_c_offset + j, p, q] = bias[j] + sum_{c,r,s} w[j,c,r,s] *
+ * x[n, c, p*stride_h + r - pad_h, q*stride_w + s - pad_w], zero outside the input; then ReLU if
+ * cd->relu.  Writes channels [y_c_offset, y_c_offset + cd->k) of y, which has yd->c >= that many
+ * channels (other channels untouched): this is how a branch writes its part of a concatenated
+ * tensor.  bias may be NULL (zero).  xd->c == cd->c, yd->n == xd->n, yd->h/w == dr_conv_out_size.
+ * x, w, y share one dtype.  Uses no workspace. */
+int dr_conv2d_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
+                  const dr_tensor* yd, void* y, int y_c_offset, void* stream);
+
+/* Slim layer of streamline slimming (Sec. 3.1 "Pooling Layer" / "Non-Pooling Layer"): the
+ * convolution cd with its stride multiplied by the absorbed pooling layer's stride, LRN/BatchNorm
+ * dropped and ReLU kept (forced on whatever cd->relu says).  yd must carry the output size of the
+ * convolution at the product stride.  Otherwise as dr_conv2d_fwd. */
+int dr_slim_conv_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, int pool_stride_h, int pool_stride_w,
+                     const void* w, const float* bias, const dr_tensor* yd, void* y, int y_c_offset, void* stream);
+
+/* ReLU (non-tensor layer, Fig. 2; retained by slimming, Sec. 3.1 Example): y = max(x, 0).
+ * x == y (in place) is allowed. */
+int dr_relu(const dr_tensor* d, const void* x, void* y, void* stream);
+
+/* Across-channel LRN: y[n,c,h,w] = x[n,c,h,w] / (k + alpha/local_size * sum x[n,c',h,w]^2)^beta, c'
+ * over the local_size channels centred on c (from c - local_size/2), clipped to the tensor. */
+int dr_lrn_fwd(const dr_tensor* d, const void* x, const dr_lrn* p, void* y, void* stream);
+
+/* Max-pooling: maximum over the window's intersection with the input (padding never wins).
+ * yd->h/w must equal dr_pool_out_size; yd->n/c == xd->n/c. */
+int dr_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream);
+
+/* Concatenation along channels, Eq. (11): y = [x_0; x_1; ...; x_{nb-1}].  xds/xs are host arrays
+ * of nb descriptors / device pointers; all inputs share n, h, w and dtype; yd->c = sum of x_i c.
+ * nb <= DR_MAX_BRANCHES. */
+#define DR_MAX_BRANCHES 8
+int dr_concat(int nb, const dr_tensor* xds, const void* const* xs, const dr_tensor* yd, void* y, void* stream);
+
+/* BatchNorm + Scale at inference, Eq. (8) with m = 1 and eps under the root:
+ * y = gamma_c (x - mean_c) / sqrt(var_c + eps) + beta_c, then ReLU if relu != 0.  In place allowed.
+ * gamma, beta, mean, var: fp32 device vectors of d->c entries. */
+int dr_bn_fwd(const dr_tensor* d, const void* x, const float* gamma, const float* beta, const float* mean,
+              const float* var, float eps, int relu, void* y, void* stream);
+
+/* Residual merge of a ResNet bottleneck (Sec. 4.2): y = max(a + b, 0).  y may alias a or b. */
+int dr_add_relu(const dr_tensor* d, const void* a, const void* b, void* y, void* stream);
+
+/* Lemma 2, Eq. (6) with m = 1: folds BatchNorm + Scale into the preceding convolution.
+ * HOST arrays, fp32: eta_j = gamma_j / sqrt(var_j + eps), w_out[j,:] = eta_j w[j,:],
+ * b_out[j] = eta_j b[j] + beta_j - eta_j mean_j.  crs = weights per output channel; b may be NULL.
+ * w_out may alias w, b_out may alias b.  Runs on the CPU (it is an offline model transform). */
+int dr_fold_bn(int k, size_t crs, const float* w, const float* b, const float* gamma, const float* beta,
+               const float* mean, const float* var, float eps, float* w_out, float* b_out);
+
+/* Average pooling over a kh x kw window (floor sizes, no padding); the 7x7 pool of GoogLeNet's
+ * classifier (Table 4, row loss3).  p->pad_* must be 0. */
+int dr_avgpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream);
+
+/* Inner-product layer (a tensor layer, Sec. 1): y[n,o] = bias[o] + sum_i w[o,i] x[n,i], with
+ * i running over c*h*w of xd.  yd = {n, out, 1, 1}.  w: out x (c*h*w), dtype of x. */
+int dr_fc_fwd(const dr_tensor* xd, const void* x, const void* w, const float* bias, const dr_tensor* yd, void* y,
+              void* stream);
+
+/* Softmax over the channel axis of an {n, c, 1, 1} tensor; the output y is always fp32. */
+int dr_softmax_fwd(const dr_tensor* xd, const void* x, float* y, void* stream);
+
+/* ---- inception module (Sec. 3.2, Fig. 4) ---------------------------------------------------- */
+
+#define DR_MAX_STEPS 4
+typedef enum { DR_STEP_CONV = 0, DR_STEP_MAXPOOL = 1 } dr_step_kind;
+/* One step of a branch; conv.relu != 0 means a ReLU layer follows the convolution. */
+typedef struct { int kind; dr_conv conv; dr_pool pool; } dr_step;
+typedef struct { int n_steps; dr_step steps[DR_MAX_STEPS]; } dr_branch;
+
+/* How the module is executed.  0 = the layer-by-layer form the paper times: every ReLU is its own
+ * kernel and the branch outputs are gathered by a concat kernel.  Flags remove passes without
+ * changing the function computed: */
+#define DR_FUSE_RELU   1   /* ReLU in the convolution's store */
+#define DR_FUSE_CONCAT 2   /* a branch ending in a convolution writes its channel range of y directly
+                              (that convolution then also applies its ReLU in the store) */
+#define DR_FUSE_STACK  4   /* Eq. (12): first-step 1x1 convolutions that read the module input run as
+                              one convolution with stacked filters (needs DR_FUSE_RELU) */
+typedef struct { int n_branches; dr_branch branches[DR_MAX_BRANCHES]; int mode; } dr_inception;
+
+/* Bytes of workspace dr_inception_fwd needs for input xd. */
+int dr_inception_workspace_bytes(const dr_tensor* xd, const dr_inception* desc, size_t* bytes);
+
+/* Every branch is a chain of steps applied to the module input x; y = concat of the branch
+ * outputs in branch order.  The original module has four branches (1x1 | 1x1,3x3 | 1x1,5x5 |
+ * pool,1x1), the branch-slimmed one has two.  weights[i] / biases[i]: parameters of the i-th
+ * convolution step counted branch by branch, step by step.  ws: device scratch of at least
+ * dr_inception_workspace_bytes, 256-byte aligned. */
+int dr_inception_fwd(const dr_tensor* xd, const void* x, const dr_inception* desc, const void* const* weights,
+                     const float* const* biases, const dr_tensor* yd, void* y, void* ws, size_t ws_bytes,
+                     void* stream);
+
+/* ---- whole networks --------------------------------------------------------------------------- */
+
+typedef enum {
+    DR_LAYER_CONV = 0, DR_LAYER_RELU, DR_LAYER_LRN, DR_LAYER_MAXPOOL, DR_LAYER_INCEPTION,
+    DR_LAYER_BOTTLENECK, DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX
+} dr_layer_kind;
+
+/* ResNet bottleneck (Sec. 4.2): 1x1 (mid) - 3x3 (mid) - 1x1 (out), each followed by BatchNorm
+ * (+ReLU after the first two), shortcut = identity or (project != 0) a 1x1 convolution + BatchNorm;
+ * output = ReLU(sum).  folded != 0 is the slim form: no BatchNorm layers, the convolutions carry
+ * folded weights (dr_fold_bn), ReLU and the residual sum run in the convolutions' stores. */
+typedef struct { int mid, out, project, folded; float eps; } dr_bottleneck;
+
+typedef struct {
+    int kind;
+    dr_conv conv;            /* DR_LAYER_CONV */
+    dr_lrn lrn;              /* DR_LAYER_LRN */
+    dr_pool pool;            /* DR_LAYER_MAXPOOL, DR_LAYER_AVGPOOL */
+    dr_inception inception;  /* DR_LAYER_INCEPTION */
+    dr_bottleneck bottleneck;/* DR_LAYER_BOTTLENECK */
+    int fc_out;              /* DR_LAYER_FC */
+} dr_layer_desc;
+
+typedef struct dr_net dr_net;   /* host-side object: a validated copy of the layer list */
+
+/* Builds a network from n_layers descriptors (copied).  Parameter order expected by dr_net_fwd:
+ * forward order; conv: w, bias; inception: per branch, per conv step: w, bias; bottleneck:
+ * conv a, [bn a], conv b, [bn b], conv c, [bn c], then projection conv, [bn] if present, where a
+ * conv is (w, bias) and a bn is (gamma, beta, mean, var) and the bn entries are absent when
+ * folded; fc: w, bias. */
+int dr_net_create(const dr_layer_desc* layers, int n_layers, dr_net** out);
+void dr_net_destroy(dr_net* net);
+
+/* Number of parameter pointers dr_net_fwd expects. */
+int dr_net_num_params(const dr_net* net, int* count);
+
+/* Output descriptor and workspace need of the network for input xd. */
+int dr_net_output_desc(const dr_net* net, const dr_tensor* xd, dr_tensor* yd);
+int dr_net_workspace_bytes(const dr_net* net, const dr_tensor* xd, size_t* bytes);
+
+/* Runs the layer list on x.  params: host array of dr_net_num_params device pointers.  The output
+ * has the dtype of the input except after a softmax layer (fp32).  ws: at least
+ * dr_net_workspace_bytes, 256-byte aligned. */
+int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params,
+               const dr_tensor* yd, void* y, void* ws, size_t ws_bytes, void* stream);
+
+/* Per-layer timing: when enabled, dr_net_fwd brackets every top-level layer with events on
+ * `stream`; dr_net_layer_times synchronises with the last run and writes n_layers durations in
+ * milliseconds (used to report the paper's "% Latency" of non-tensor layers, Eq. (1)). */
+int dr_net_set_timing(dr_net* net, int enabled);
+int dr_net_layer_times(dr_net* net, float* ms_per_layer, int n);
+
+/* ---- misc ------------------------------------------------------------------------------------------ */
+
+/* Message of the last error raised on the calling thread ("" if none). */
+const char* dr_last_error(void);
+
+/* Library version string. */
+const char* dr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEEPREBIRTH_H */

@@ -1,0 +1,744 @@
+// C ABI of the library: argument validation (host only, before anything is enqueued), shape rules,
+// and the orchestration of inception modules, bottlenecks and whole networks out of the kernels.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "dr_internal.h"
+
+namespace dr {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_launch(const char* what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(DR_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return DR_OK;
+}
+
+namespace {
+
+#define DR_TRY(expr) do { const int dr_rc_ = (expr); if (dr_rc_ != DR_OK) return dr_rc_; } while (0)
+
+int check_tensor(const char* who, const char* name, const dr_tensor* t)
+{
+    if (!t) return fail(DR_ERR_NULL, "%s: descriptor %s is NULL", who, name);
+    if (t->n < 0 || t->c < 0 || t->h < 0 || t->w < 0)
+        return fail(DR_ERR_SHAPE, "%s: %s has a negative dimension (%d,%d,%d,%d)", who, name, t->n, t->c, t->h, t->w);
+    if (t->dtype != DR_F32 && t->dtype != DR_BF16) return fail(DR_ERR_UNSUPPORTED, "%s: %s has unknown dtype %d", who, name, t->dtype);
+    if ((double)t->n * t->c * t->h * t->w >= 2147483648.0)
+        return fail(DR_ERR_UNSUPPORTED, "%s: %s has more than 2^31-1 elements", who, name);
+    return DR_OK;
+}
+
+int check_conv_desc(const char* who, const dr_conv* c)
+{
+    if (!c) return fail(DR_ERR_NULL, "%s: convolution descriptor is NULL", who);
+    if (c->k < 1 || c->c < 1 || c->r < 1 || c->s < 1 || c->stride_h < 1 || c->stride_w < 1 || c->pad_h < 0 || c->pad_w < 0)
+        return fail(DR_ERR_SHAPE, "%s: bad convolution k=%d c=%d r=%d s=%d stride=%d,%d pad=%d,%d", who, c->k, c->c, c->r, c->s,
+                    c->stride_h, c->stride_w, c->pad_h, c->pad_w);
+    return DR_OK;
+}
+
+int check_pool_desc(const char* who, const dr_pool* p)
+{
+    if (!p) return fail(DR_ERR_NULL, "%s: pooling descriptor is NULL", who);
+    if (p->kh < 1 || p->kw < 1 || p->stride_h < 1 || p->stride_w < 1 || p->pad_h < 0 || p->pad_w < 0 || p->pad_h >= p->kh ||
+        p->pad_w >= p->kw)
+        return fail(DR_ERR_SHAPE, "%s: bad pooling window %dx%d stride %d,%d pad %d,%d", who, p->kh, p->kw, p->stride_h,
+                    p->stride_w, p->pad_h, p->pad_w);
+    return DR_OK;
+}
+
+// Output descriptors (shape rules live here and nowhere else in the library).
+dr_tensor conv_out(const dr_tensor& x, const dr_conv& c)
+{
+    return dr_tensor{x.n, c.k, dr_conv_out_size(x.h, c.r, c.stride_h, c.pad_h), dr_conv_out_size(x.w, c.s, c.stride_w, c.pad_w),
+                     x.dtype};
+}
+dr_tensor pool_out(const dr_tensor& x, const dr_pool& p)
+{
+    return dr_tensor{x.n, x.c, dr_pool_out_size(x.h, p.kh, p.stride_h, p.pad_h), dr_pool_out_size(x.w, p.kw, p.stride_w, p.pad_w),
+                     x.dtype};
+}
+dr_tensor avgpool_out(const dr_tensor& x, const dr_pool& p)
+{
+    return dr_tensor{x.n, x.c, dr_conv_out_size(x.h, p.kh, p.stride_h, 0), dr_conv_out_size(x.w, p.kw, p.stride_w, 0), x.dtype};
+}
+bool same_shape(const dr_tensor& a, const dr_tensor& b) { return a.n == b.n && a.c == b.c && a.h == b.h && a.w == b.w; }
+
+// Validated convolution launch (shared by the single-layer entry points and the composite ones).
+int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias,
+             const void* residual, int res_ctot, const dr_tensor& yd, void* y, int y_c_offset, hipStream_t st)
+{
+    if (xd.c != cd.c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd.c, cd.c);
+    const dr_tensor o = conv_out(xd, cd);
+    if (yd.n != o.n || yd.h != o.h || yd.w != o.w)
+        return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%d per channel, the layer produces %dx%dx%d", who, yd.n, yd.h, yd.w, o.n, o.h, o.w);
+    if (y_c_offset < 0 || y_c_offset + cd.k > yd.c)
+        return fail(DR_ERR_SHAPE, "%s: channels [%d,%d) do not fit an output of %d channels", who, y_c_offset, y_c_offset + cd.k, yd.c);
+    if (yd.dtype != xd.dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
+    if ((double)cd.c * cd.r * cd.s >= 2147483648.0 || (double)o.n * o.h * o.w >= 2147483648.0)
+        return fail(DR_ERR_UNSUPPORTED, "%s: problem too large", who);
+    if (tensor_elems(o) == 0) return DR_OK;
+    if (o.h == 0 || o.w == 0) return DR_OK;
+    ConvGeom g;
+    g.N = xd.n; g.C = xd.c; g.H = xd.h; g.W = xd.w;
+    g.K = cd.k; g.R = cd.r; g.S = cd.s;
+    g.sh = cd.stride_h; g.sw = cd.stride_w; g.ph = cd.pad_h; g.pw = cd.pad_w;
+    g.P = o.h; g.Q = o.w;
+    g.Kg = cd.c * cd.r * cd.s;
+    g.Ng = o.n * o.h * o.w;
+    g.y_ctot = yd.c; g.y_coff = y_c_offset;
+    g.relu = cd.relu != 0;
+    g.res_ctot = residual ? res_ctot : 0;
+    if (xd.dtype == DR_F32)
+        return launch_conv_f32(g, (const float*)x, (const float*)w, bias, (const float*)residual, (float*)y, st);
+    return launch_conv_bf16(g, (const uint16_t*)x, (const uint16_t*)w, bias, (const uint16_t*)residual, (uint16_t*)y, st);
+}
+
+// ---- bump allocator over the caller's workspace (also used in "measure" mode with base = NULL)
+struct Arena {
+    char* base;
+    size_t size, used, peak;
+    bool measure;
+    Arena(void* b, size_t s, bool m) : base((char*)b), size(s), used(0), peak(0), measure(m) {}
+    void* take(size_t bytes)
+    {
+        const size_t off = used;
+        used = align_up(used + bytes, 256);
+        if (used > peak) peak = used;
+        if (measure) return (void*)(uintptr_t)(256 + off);   // never dereferenced
+        return used <= size ? base + off : nullptr;
+    }
+};
+
+// ---- inception ---------------------------------------------------------------------------------------
+struct ParamCursor {
+    const void* const* p;
+    int i;
+    const void* next() { return p ? p[i++] : (++i, nullptr); }
+};
+
+int inception_validate(const dr_tensor& xd, const dr_inception& d, dr_tensor* out)
+{
+    const char* who = "dr_inception_fwd";
+    if (d.n_branches < 1 || d.n_branches > DR_MAX_BRANCHES) return fail(DR_ERR_SHAPE, "%s: %d branches", who, d.n_branches);
+    if ((d.mode & DR_FUSE_STACK) && !(d.mode & DR_FUSE_RELU)) return fail(DR_ERR_UNSUPPORTED, "%s: DR_FUSE_STACK needs DR_FUSE_RELU", who);
+    int ctot = 0, oh = -1, ow = -1;
+    for (int b = 0; b < d.n_branches; ++b) {
+        const dr_branch& br = d.branches[b];
+        if (br.n_steps < 1 || br.n_steps > DR_MAX_STEPS) return fail(DR_ERR_SHAPE, "%s: branch %d has %d steps", who, b, br.n_steps);
+        dr_tensor t = xd;
+        for (int s = 0; s < br.n_steps; ++s) {
+            const dr_step& stp = br.steps[s];
+            if (stp.kind == DR_STEP_CONV) {
+                DR_TRY(check_conv_desc(who, &stp.conv));
+                if (stp.conv.c != t.c) return fail(DR_ERR_SHAPE, "%s: branch %d step %d expects %d channels, gets %d", who, b, s, stp.conv.c, t.c);
+                t = conv_out(t, stp.conv);
+            } else if (stp.kind == DR_STEP_MAXPOOL) {
+                DR_TRY(check_pool_desc(who, &stp.pool));
+                t = pool_out(t, stp.pool);
+            } else {
+                return fail(DR_ERR_UNSUPPORTED, "%s: unknown step kind %d", who, stp.kind);
+            }
+        }
+        if (b == 0) { oh = t.h; ow = t.w; }
+        else if (t.h != oh || t.w != ow) return fail(DR_ERR_SHAPE, "%s: branch %d ends at %dx%d, branch 0 at %dx%d", who, b, t.h, t.w, oh, ow);
+        ctot += t.c;
+    }
+    *out = dr_tensor{xd.n, ctot, oh, ow, xd.dtype};
+    return DR_OK;
+}
+
+// Runs (or, with a measuring arena, only plans) one module.  y may be NULL when measuring.
+int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, ParamCursor& wts, ParamCursor& bss,
+                  const dr_tensor& yd, void* y, Arena& ar, hipStream_t st)
+{
+    const char* who = "dr_inception_fwd";
+    const bool fuse_relu = d.mode & DR_FUSE_RELU, fuse_cat = d.mode & DR_FUSE_CONCAT;
+    ConcatSeg segs[DR_MAX_BRANCHES];
+    int nseg = 0, c_off = 0;
+    for (int b = 0; b < d.n_branches; ++b) {
+        const dr_branch& br = d.branches[b];
+        dr_tensor t = xd;
+        const void* cur = x;
+        for (int s = 0; s < br.n_steps; ++s) {
+            const dr_step& stp = br.steps[s];
+            const bool last = s == br.n_steps - 1;
+            if (stp.kind == DR_STEP_CONV) {
+                dr_conv cd = stp.conv;
+                const bool relu_after = cd.relu != 0;
+                cd.relu = relu_after && fuse_relu;
+                const dr_tensor o = conv_out(t, cd);
+                const void* w = wts.next();
+                const float* bias = (const float*)bss.next();
+                const bool direct = last && fuse_cat;   // writes its channel range of y, ReLU in the store
+                if (direct) cd.relu = relu_after;
+                void* dst = direct ? y : ar.take(tensor_bytes(o));
+                if (!dst && !ar.measure) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
+                if (!ar.measure) {
+                    if (!w) return fail(DR_ERR_NULL, "%s: missing weights of branch %d step %d", who, b, s);
+                    DR_TRY(conv_run(who, t, cur, cd, w, bias, nullptr, 0, direct ? yd : o, dst, direct ? c_off : 0, st));
+                    if (relu_after && !cd.relu) DR_TRY(launch_relu(o.dtype, dst, dst, tensor_elems(o), st));
+                }
+                if (last && !direct) segs[nseg++] = ConcatSeg{dst, o.c, c_off};
+                cur = dst;
+                t = o;
+            } else {
+                const dr_tensor o = pool_out(t, stp.pool);
+                void* dst = ar.take(tensor_bytes(o));
+                if (!dst && !ar.measure) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
+                if (!ar.measure) DR_TRY(launch_maxpool(t.dtype, cur, dst, t.n * t.c, t.h, t.w, o.h, o.w, stp.pool, st));
+                if (last) segs[nseg++] = ConcatSeg{dst, o.c, c_off};
+                cur = dst;
+                t = o;
+            }
+        }
+        c_off += t.c;
+    }
+    if (nseg && !ar.measure) DR_TRY(launch_concat(yd.dtype, nseg, segs, y, yd.n, yd.c, yd.h * yd.w, st));
+    return DR_OK;
+}
+
+
+// ---- whole networks ------------------------------------------------------------------------------------
+int param_count(const dr_layer_desc& L)
+{
+    switch (L.kind) {
+    case DR_LAYER_CONV: return 2;
+    case DR_LAYER_FC: return 2;
+    case DR_LAYER_INCEPTION: {
+        int n = 0;
+        for (int b = 0; b < L.inception.n_branches; ++b)
+            for (int s = 0; s < L.inception.branches[b].n_steps; ++s)
+                if (L.inception.branches[b].steps[s].kind == DR_STEP_CONV) n += 2;
+        return n;
+    }
+    case DR_LAYER_BOTTLENECK: return (L.bottleneck.project ? 4 : 3) * (L.bottleneck.folded ? 2 : 6);
+    default: return 0;
+    }
+}
+
+// ResNet bottleneck.  Original form: conv, BatchNorm(+Scale) and ReLU are separate passes and the
+// residual sum is its own kernel; folded (slim) form: three or four convolutions with folded
+// parameters, ReLU and the residual sum applied in the convolutions' stores.
+int bottleneck_run(const dr_tensor& xd, const void* x, const dr_bottleneck& bd, const void* const* prm, const dr_tensor& yd,
+                   void* y, Arena& ar, hipStream_t st)
+{
+    const char* who = "dr_net_fwd(bottleneck)";
+    const bool run = !ar.measure;
+    const int per = bd.folded ? 2 : 6;   // pointers per conv(+bn) group
+    auto conv_of = [&](int k, int c, int r, int pad, int relu) { return dr_conv{k, c, r, r, 1, 1, pad, pad, relu}; };
+    const dr_conv ca = conv_of(bd.mid, xd.c, 1, 0, bd.folded), cb = conv_of(bd.mid, bd.mid, 3, 1, bd.folded),
+                  cc = conv_of(bd.out, bd.mid, 1, 0, bd.folded), cp = conv_of(bd.out, xd.c, 1, 0, 0);
+    const dr_tensor ta = conv_out(xd, ca), tb = conv_out(ta, cb), tc = conv_out(tb, cc);
+    if (!bd.project && xd.c != bd.out) return fail(DR_ERR_SHAPE, "%s: identity shortcut needs %d input channels, got %d", who, bd.out, xd.c);
+    void* sa = ar.take(tensor_bytes(ta));
+    void* sb = ar.take(tensor_bytes(tb));
+    void* sp = bd.project ? ar.take(tensor_bytes(tc)) : nullptr;
+    void* sc = bd.folded ? nullptr : ar.take(tensor_bytes(tc));
+    if (!run) return DR_OK;
+    if (!sa || !sb || (bd.project && !sp) || (!bd.folded && !sc)) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
+    for (int i = 0; i < (bd.project ? 4 : 3) * per; ++i)
+        if (!prm[i] && (i % per) != 1) return fail(DR_ERR_NULL, "%s: parameter %d is NULL", who, i);
+    auto P = [&](int group, int j) { return prm[group * per + j]; };
+    auto F = [&](int group, int j) { return (const float*)prm[group * per + j]; };
+    if (bd.folded) {
+        DR_TRY(conv_run(who, xd, x, ca, P(0, 0), F(0, 1), nullptr, 0, ta, sa, 0, st));
+        DR_TRY(conv_run(who, ta, sa, cb, P(1, 0), F(1, 1), nullptr, 0, tb, sb, 0, st));
+        const void* shortcut = x;
+        if (bd.project) {
+            DR_TRY(conv_run(who, xd, x, cp, P(3, 0), F(3, 1), nullptr, 0, tc, sp, 0, st));
+            shortcut = sp;
+        }
+        return conv_run(who, tb, sb, cc, P(2, 0), F(2, 1), shortcut, tc.c, yd, y, 0, st);
+    }
+    auto conv_bn = [&](const dr_tensor& in, const void* src, const dr_conv& c, int grp, const dr_tensor& o, void* dst, bool relu) -> int {
+        DR_TRY(conv_run(who, in, src, c, P(grp, 0), F(grp, 1), nullptr, 0, o, dst, 0, st));
+        DR_TRY(launch_bn(o.dtype, dst, dst, o.n, o.c, o.h * o.w, F(grp, 2), F(grp, 3), F(grp, 4), F(grp, 5), bd.eps, 0, st));
+        if (relu) DR_TRY(launch_relu(o.dtype, dst, dst, tensor_elems(o), st));
+        return DR_OK;
+    };
+    DR_TRY(conv_bn(xd, x, ca, 0, ta, sa, true));
+    DR_TRY(conv_bn(ta, sa, cb, 1, tb, sb, true));
+    DR_TRY(conv_bn(tb, sb, cc, 2, tc, sc, false));
+    const void* shortcut = x;
+    if (bd.project) {
+        DR_TRY(conv_bn(xd, x, cp, 3, tc, sp, false));
+        shortcut = sp;
+    }
+    return launch_add_relu(tc.dtype, sc, shortcut, y, tensor_elems(tc), st);
+}
+
+}  // namespace
+}  // namespace dr
+
+struct dr_net {
+    std::vector<dr_layer_desc> layers;
+    int n_params = 0;
+    bool timing = false;
+    std::vector<hipEvent_t> events;
+    hipStream_t timed_stream = nullptr;
+    bool timed_valid = false;
+};
+
+namespace dr {
+namespace {
+
+// Output descriptor of one layer for input t (validates the layer against its input).
+int layer_out(const dr_layer_desc& L, const dr_tensor& t, dr_tensor* o)
+{
+    const char* who = "dr_net";
+    switch (L.kind) {
+    case DR_LAYER_CONV:
+        DR_TRY(check_conv_desc(who, &L.conv));
+        if (L.conv.c != t.c) return fail(DR_ERR_SHAPE, "%s: convolution expects %d channels, gets %d", who, L.conv.c, t.c);
+        *o = conv_out(t, L.conv);
+        return DR_OK;
+    case DR_LAYER_RELU: *o = t; return DR_OK;
+    case DR_LAYER_LRN:
+        if (L.lrn.local_size < 1) return fail(DR_ERR_SHAPE, "%s: LRN local_size %d", who, L.lrn.local_size);
+        *o = t;
+        return DR_OK;
+    case DR_LAYER_MAXPOOL: DR_TRY(check_pool_desc(who, &L.pool)); *o = pool_out(t, L.pool); return DR_OK;
+    case DR_LAYER_AVGPOOL:
+        DR_TRY(check_pool_desc(who, &L.pool));
+        if (L.pool.pad_h || L.pool.pad_w) return fail(DR_ERR_UNSUPPORTED, "%s: padded average pooling", who);
+        *o = avgpool_out(t, L.pool);
+        return DR_OK;
+    case DR_LAYER_INCEPTION: return inception_validate(t, L.inception, o);
+    case DR_LAYER_BOTTLENECK:
+        if (L.bottleneck.mid < 1 || L.bottleneck.out < 1) return fail(DR_ERR_SHAPE, "%s: bad bottleneck widths", who);
+        if (!L.bottleneck.project && t.c != L.bottleneck.out) return fail(DR_ERR_SHAPE, "%s: identity shortcut needs %d channels, gets %d", who, L.bottleneck.out, t.c);
+        *o = dr_tensor{t.n, L.bottleneck.out, t.h, t.w, t.dtype};
+        return DR_OK;
+    case DR_LAYER_FC:
+        if (L.fc_out < 1) return fail(DR_ERR_SHAPE, "%s: fc_out %d", who, L.fc_out);
+        *o = dr_tensor{t.n, L.fc_out, 1, 1, t.dtype};
+        return DR_OK;
+    case DR_LAYER_SOFTMAX:
+        if (t.h != 1 || t.w != 1) return fail(DR_ERR_SHAPE, "%s: softmax needs an {n, c, 1, 1} input", who);
+        *o = dr_tensor{t.n, t.c, 1, 1, DR_F32};
+        return DR_OK;
+    default: return fail(DR_ERR_UNSUPPORTED, "%s: unknown layer kind %d", who, L.kind);
+    }
+}
+
+struct NetPlan {
+    std::vector<dr_tensor> outs;   // output descriptor of every layer
+    size_t act_bytes = 0;          // largest intermediate activation
+    size_t scratch_bytes = 0;      // largest per-layer scratch (inception / bottleneck internals)
+};
+
+int net_plan(const dr_net& net, const dr_tensor& xd, NetPlan* plan)
+{
+    dr_tensor t = xd;
+    plan->outs.clear();
+    for (size_t i = 0; i < net.layers.size(); ++i) {
+        const dr_layer_desc& L = net.layers[i];
+        dr_tensor o;
+        DR_TRY(layer_out(L, t, &o));
+        if (L.kind == DR_LAYER_SOFTMAX && i + 1 != net.layers.size())
+            return fail(DR_ERR_UNSUPPORTED, "dr_net: softmax must be the last layer");
+        Arena ar(nullptr, 0, true);
+        if (L.kind == DR_LAYER_INCEPTION) {
+            ParamCursor w{nullptr, 0}, b{nullptr, 0};
+            DR_TRY(inception_run(t, nullptr, L.inception, w, b, o, nullptr, ar, nullptr));
+        } else if (L.kind == DR_LAYER_BOTTLENECK) {
+            DR_TRY(bottleneck_run(t, nullptr, L.bottleneck, nullptr, o, nullptr, ar, nullptr));
+        }
+        if (ar.peak > plan->scratch_bytes) plan->scratch_bytes = ar.peak;
+        if (i + 1 != net.layers.size()) {
+            const size_t b = align_up(tensor_bytes(o), 256);
+            if (b > plan->act_bytes) plan->act_bytes = b;
+        }
+        plan->outs.push_back(o);
+        t = o;
+    }
+    return DR_OK;
+}
+
+}  // namespace
+}  // namespace dr
+
+using namespace dr;
+
+// =====================================================================================================
+// C ABI
+// =====================================================================================================
+extern "C" {
+
+const char* dr_last_error(void) { return g_err; }
+const char* dr_version(void) { return "deeprebirth-gfx950 0.1"; }
+
+int dr_conv_out_size(int in, int filt, int stride, int pad)
+{
+    if (stride < 1 || filt < 1 || pad < 0 || in + 2 * pad < filt) return 0;
+    return (in + 2 * pad - filt) / stride + 1;
+}
+
+int dr_pool_out_size(int in, int win, int stride, int pad)
+{
+    if (stride < 1 || win < 1 || pad < 0 || in + 2 * pad < win) return 0;
+    int out = (in + 2 * pad - win + stride - 1) / stride + 1;
+    if (pad > 0 && (out - 1) * stride >= in + pad) --out;
+    return out;
+}
+
+int dr_conv2d_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
+                  const dr_tensor* yd, void* y, int y_c_offset, void* stream)
+{
+    const char* who = "dr_conv2d_fwd";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    DR_TRY(check_conv_desc(who, cd));
+    if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
+    return conv_run(who, *xd, x, *cd, w, bias, nullptr, 0, *yd, y, y_c_offset, (hipStream_t)stream);
+}
+
+int dr_slim_conv_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, int pool_stride_h, int pool_stride_w,
+                     const void* w, const float* bias, const dr_tensor* yd, void* y, int y_c_offset, void* stream)
+{
+    const char* who = "dr_slim_conv_fwd";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    DR_TRY(check_conv_desc(who, cd));
+    if (pool_stride_h < 1 || pool_stride_w < 1) return fail(DR_ERR_SHAPE, "%s: pooling stride %d,%d", who, pool_stride_h, pool_stride_w);
+    if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
+    dr_conv slim = *cd;
+    slim.stride_h = cd->stride_h * pool_stride_h;   // stride of the slim layer = product of both strides
+    slim.stride_w = cd->stride_w * pool_stride_w;
+    slim.relu = 1;                                  // the ReLU is retained
+    return conv_run(who, *xd, x, slim, w, bias, nullptr, 0, *yd, y, y_c_offset, (hipStream_t)stream);
+}
+
+int dr_relu(const dr_tensor* d, const void* x, void* y, void* stream)
+{
+    DR_TRY(check_tensor("dr_relu", "d", d));
+    if (!x || !y) return fail(DR_ERR_NULL, "dr_relu: x or y is NULL");
+    return launch_relu(d->dtype, x, y, tensor_elems(*d), (hipStream_t)stream);
+}
+
+int dr_lrn_fwd(const dr_tensor* d, const void* x, const dr_lrn* p, void* y, void* stream)
+{
+    const char* who = "dr_lrn_fwd";
+    DR_TRY(check_tensor(who, "d", d));
+    if (!p) return fail(DR_ERR_NULL, "%s: parameters are NULL", who);
+    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
+    if (x == y) return fail(DR_ERR_UNSUPPORTED, "%s: in-place operation is not supported", who);
+    if (p->local_size < 1) return fail(DR_ERR_SHAPE, "%s: local_size %d", who, p->local_size);
+    return launch_lrn(d->dtype, x, y, d->n, d->c, d->h * d->w, *p, (hipStream_t)stream);
+}
+
+int dr_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream)
+{
+    const char* who = "dr_maxpool_fwd";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    DR_TRY(check_pool_desc(who, p));
+    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
+    const dr_tensor o = pool_out(*xd, *p);
+    if (!same_shape(o, *yd)) return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%dx%d, the layer produces %dx%dx%dx%d", who, yd->n, yd->c, yd->h, yd->w, o.n, o.c, o.h, o.w);
+    if (yd->dtype != xd->dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
+    return launch_maxpool(xd->dtype, x, y, xd->n * xd->c, xd->h, xd->w, o.h, o.w, *p, (hipStream_t)stream);
+}
+
+int dr_avgpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream)
+{
+    const char* who = "dr_avgpool_fwd";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    DR_TRY(check_pool_desc(who, p));
+    if (p->pad_h || p->pad_w) return fail(DR_ERR_UNSUPPORTED, "%s: padding is not supported", who);
+    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
+    const dr_tensor o = avgpool_out(*xd, *p);
+    if (!same_shape(o, *yd)) return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%dx%d, the layer produces %dx%dx%dx%d", who, yd->n, yd->c, yd->h, yd->w, o.n, o.c, o.h, o.w);
+    if (yd->dtype != xd->dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
+    return launch_avgpool(xd->dtype, x, y, xd->n * xd->c, xd->h, xd->w, o.h, o.w, *p, (hipStream_t)stream);
+}
+
+int dr_concat(int nb, const dr_tensor* xds, const void* const* xs, const dr_tensor* yd, void* y, void* stream)
+{
+    const char* who = "dr_concat";
+    if (nb < 1 || nb > DR_MAX_BRANCHES) return fail(DR_ERR_SHAPE, "%s: %d inputs (1..%d supported)", who, nb, DR_MAX_BRANCHES);
+    if (!xds || !xs) return fail(DR_ERR_NULL, "%s: input arrays are NULL", who);
+    DR_TRY(check_tensor(who, "yd", yd));
+    if (!y) return fail(DR_ERR_NULL, "%s: y is NULL", who);
+    ConcatSeg segs[DR_MAX_BRANCHES];
+    int c = 0;
+    for (int i = 0; i < nb; ++i) {
+        DR_TRY(check_tensor(who, "xds[i]", &xds[i]));
+        if (!xs[i]) return fail(DR_ERR_NULL, "%s: xs[%d] is NULL", who, i);
+        if (xds[i].n != yd->n || xds[i].h != yd->h || xds[i].w != yd->w || xds[i].dtype != yd->dtype)
+            return fail(DR_ERR_SHAPE, "%s: input %d does not match the output's n, h, w or dtype", who, i);
+        segs[i] = ConcatSeg{xs[i], xds[i].c, c};
+        c += xds[i].c;
+    }
+    if (c != yd->c) return fail(DR_ERR_SHAPE, "%s: inputs have %d channels in total, output has %d", who, c, yd->c);
+    return launch_concat(yd->dtype, nb, segs, y, yd->n, yd->c, yd->h * yd->w, (hipStream_t)stream);
+}
+
+int dr_bn_fwd(const dr_tensor* d, const void* x, const float* gamma, const float* beta, const float* mean,
+              const float* var, float eps, int relu, void* y, void* stream)
+{
+    const char* who = "dr_bn_fwd";
+    DR_TRY(check_tensor(who, "d", d));
+    if (!x || !y || !gamma || !beta || !mean || !var) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
+    if (!(eps >= 0.f)) return fail(DR_ERR_SHAPE, "%s: eps must be >= 0", who);
+    return launch_bn(d->dtype, x, y, d->n, d->c, d->h * d->w, gamma, beta, mean, var, eps, relu, (hipStream_t)stream);
+}
+
+int dr_add_relu(const dr_tensor* d, const void* a, const void* b, void* y, void* stream)
+{
+    DR_TRY(check_tensor("dr_add_relu", "d", d));
+    if (!a || !b || !y) return fail(DR_ERR_NULL, "dr_add_relu: a pointer is NULL");
+    return launch_add_relu(d->dtype, a, b, y, tensor_elems(*d), (hipStream_t)stream);
+}
+
+int dr_fold_bn(int k, size_t crs, const float* w, const float* b, const float* gamma, const float* beta,
+               const float* mean, const float* var, float eps, float* w_out, float* b_out)
+{
+    const char* who = "dr_fold_bn";
+    if (k < 0) return fail(DR_ERR_SHAPE, "%s: k = %d", who, k);
+    if (!w || !gamma || !beta || !mean || !var || !w_out || !b_out) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
+    if (!(eps >= 0.f)) return fail(DR_ERR_SHAPE, "%s: eps must be >= 0", who);
+    for (int j = 0; j < k; ++j) {
+        // evaluated in double so that the folded fp32 parameters are the correctly rounded ones
+        const double eta = (double)gamma[j] / sqrt((double)var[j] + (double)eps);
+        for (size_t i = 0; i < crs; ++i) w_out[(size_t)j * crs + i] = (float)(eta * (double)w[(size_t)j * crs + i]);
+        b_out[j] = (float)(eta * (b ? (double)b[j] : 0.0) + (double)beta[j] - eta * (double)mean[j]);
+    }
+    return DR_OK;
+}
+
+int dr_fc_fwd(const dr_tensor* xd, const void* x, const void* w, const float* bias, const dr_tensor* yd, void* y,
+              void* stream)
+{
+    const char* who = "dr_fc_fwd";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
+    if (yd->n != xd->n || yd->h != 1 || yd->w != 1) return fail(DR_ERR_SHAPE, "%s: output must be {n, out, 1, 1}", who);
+    if (yd->dtype != xd->dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
+    return launch_fc(xd->dtype, x, w, bias, y, xd->n, xd->c * xd->h * xd->w, yd->c, (hipStream_t)stream);
+}
+
+int dr_softmax_fwd(const dr_tensor* xd, const void* x, float* y, void* stream)
+{
+    const char* who = "dr_softmax_fwd";
+    DR_TRY(check_tensor(who, "xd", xd));
+    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
+    if (xd->h != 1 || xd->w != 1) return fail(DR_ERR_SHAPE, "%s: input must be {n, c, 1, 1}", who);
+    return launch_softmax(xd->dtype, x, y, xd->n, xd->c, (hipStream_t)stream);
+}
+
+int dr_inception_workspace_bytes(const dr_tensor* xd, const dr_inception* desc, size_t* bytes)
+{
+    const char* who = "dr_inception_workspace_bytes";
+    DR_TRY(check_tensor(who, "xd", xd));
+    if (!desc || !bytes) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
+    dr_tensor yd;
+    DR_TRY(inception_validate(*xd, *desc, &yd));
+    Arena ar(nullptr, 0, true);
+    ParamCursor w{nullptr, 0}, b{nullptr, 0};
+    DR_TRY(inception_run(*xd, nullptr, *desc, w, b, yd, nullptr, ar, nullptr));
+    *bytes = ar.peak;
+    return DR_OK;
+}
+
+int dr_inception_fwd(const dr_tensor* xd, const void* x, const dr_inception* desc, const void* const* weights,
+                     const float* const* biases, const dr_tensor* yd, void* y, void* ws, size_t ws_bytes, void* stream)
+{
+    const char* who = "dr_inception_fwd";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    if (!desc || !x || !y || !weights || !biases) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
+    dr_tensor o;
+    DR_TRY(inception_validate(*xd, *desc, &o));
+    if (!same_shape(o, *yd) || yd->dtype != xd->dtype)
+        return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%dx%d, the module produces %dx%dx%dx%d", who, yd->n, yd->c, yd->h, yd->w, o.n, o.c, o.h, o.w);
+    size_t need = 0;
+    DR_TRY(dr_inception_workspace_bytes(xd, desc, &need));
+    if (need > 0 && (!ws || ws_bytes < need)) return fail(DR_ERR_WORKSPACE, "%s: needs %zu bytes of workspace, got %zu", who, need, ws ? ws_bytes : (size_t)0);
+    if (((uintptr_t)ws & 255) != 0) return fail(DR_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned", who);
+    Arena ar(ws, ws_bytes, false);
+    ParamCursor w{weights, 0}, b{(const void* const*)biases, 0};
+    return inception_run(*xd, x, *desc, w, b, *yd, y, ar, (hipStream_t)stream);
+}
+
+}  // extern "C"
+
+extern "C" {
+
+int dr_net_create(const dr_layer_desc* layers, int n_layers, dr_net** out)
+{
+    const char* who = "dr_net_create";
+    if (!layers || !out) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
+    if (n_layers < 1) return fail(DR_ERR_SHAPE, "%s: %d layers", who, n_layers);
+    dr_net* net = new (std::nothrow) dr_net;
+    if (!net) return fail(DR_ERR_HIP, "%s: out of host memory", who);
+    net->layers.assign(layers, layers + n_layers);
+    for (const dr_layer_desc& L : net->layers) {
+        if (L.kind < DR_LAYER_CONV || L.kind > DR_LAYER_SOFTMAX) {
+            delete net;
+            return fail(DR_ERR_UNSUPPORTED, "%s: unknown layer kind %d", who, L.kind);
+        }
+        net->n_params += param_count(L);
+    }
+    *out = net;
+    return DR_OK;
+}
+
+void dr_net_destroy(dr_net* net)
+{
+    if (!net) return;
+    for (hipEvent_t e : net->events) (void)hipEventDestroy(e);
+    delete net;
+}
+
+int dr_net_num_params(const dr_net* net, int* count)
+{
+    if (!net || !count) return fail(DR_ERR_NULL, "dr_net_num_params: a pointer is NULL");
+    *count = net->n_params;
+    return DR_OK;
+}
+
+int dr_net_output_desc(const dr_net* net, const dr_tensor* xd, dr_tensor* yd)
+{
+    if (!net || !yd) return fail(DR_ERR_NULL, "dr_net_output_desc: a pointer is NULL");
+    DR_TRY(check_tensor("dr_net_output_desc", "xd", xd));
+    NetPlan plan;
+    DR_TRY(net_plan(*net, *xd, &plan));
+    *yd = plan.outs.back();
+    return DR_OK;
+}
+
+int dr_net_workspace_bytes(const dr_net* net, const dr_tensor* xd, size_t* bytes)
+{
+    if (!net || !bytes) return fail(DR_ERR_NULL, "dr_net_workspace_bytes: a pointer is NULL");
+    DR_TRY(check_tensor("dr_net_workspace_bytes", "xd", xd));
+    NetPlan plan;
+    DR_TRY(net_plan(*net, *xd, &plan));
+    *bytes = 2 * plan.act_bytes + plan.scratch_bytes;
+    return DR_OK;
+}
+
+int dr_net_set_timing(dr_net* net, int enabled)
+{
+    if (!net) return fail(DR_ERR_NULL, "dr_net_set_timing: net is NULL");
+    net->timing = enabled != 0;
+    net->timed_valid = false;
+    if (net->timing && net->events.empty()) {
+        net->events.resize(net->layers.size() + 1);
+        for (hipEvent_t& e : net->events)
+            if (hipEventCreate(&e) != hipSuccess) {
+                net->events.clear();
+                net->timing = false;
+                return fail(DR_ERR_HIP, "dr_net_set_timing: hipEventCreate failed");
+            }
+    }
+    return DR_OK;
+}
+
+int dr_net_layer_times(dr_net* net, float* ms_per_layer, int n)
+{
+    const char* who = "dr_net_layer_times";
+    if (!net || !ms_per_layer) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
+    if (n != (int)net->layers.size()) return fail(DR_ERR_SHAPE, "%s: the network has %zu layers", who, net->layers.size());
+    if (!net->timing || !net->timed_valid) return fail(DR_ERR_UNSUPPORTED, "%s: no timed run recorded", who);
+    if (hipEventSynchronize(net->events.back()) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipEventSynchronize failed", who);
+    for (int i = 0; i < n; ++i)
+        if (hipEventElapsedTime(&ms_per_layer[i], net->events[i], net->events[i + 1]) != hipSuccess)
+            return fail(DR_ERR_HIP, "%s: hipEventElapsedTime failed", who);
+    return DR_OK;
+}
+
+int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params, const dr_tensor* yd, void* y,
+               void* ws, size_t ws_bytes, void* stream)
+{
+    const char* who = "dr_net_fwd";
+    if (!net) return fail(DR_ERR_NULL, "%s: net is NULL", who);
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    if (!x || !y || (net->n_params && !params)) return fail(DR_ERR_NULL, "%s: x, y or params is NULL", who);
+    NetPlan plan;
+    DR_TRY(net_plan(*net, *xd, &plan));
+    const dr_tensor& o = plan.outs.back();
+    if (!same_shape(o, *yd) || o.dtype != yd->dtype)
+        return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%dx%d dtype %d, the network produces %dx%dx%dx%d dtype %d", who, yd->n, yd->c,
+                    yd->h, yd->w, yd->dtype, o.n, o.c, o.h, o.w, o.dtype);
+    const size_t need = 2 * plan.act_bytes + plan.scratch_bytes;
+    if (need > 0 && (!ws || ws_bytes < need)) return fail(DR_ERR_WORKSPACE, "%s: needs %zu bytes of workspace, got %zu", who, need, ws ? ws_bytes : (size_t)0);
+    if (((uintptr_t)ws & 255) != 0) return fail(DR_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned", who);
+    for (int i = 0; i < net->n_params; ++i)
+        if (!params[i]) return fail(DR_ERR_NULL, "%s: params[%d] is NULL", who, i);
+
+    hipStream_t st = (hipStream_t)stream;
+    char* buf[2] = {(char*)ws, (char*)ws + plan.act_bytes};
+    char* scratch = (char*)ws + 2 * plan.act_bytes;
+    const void* cur = x;
+    int cur_buf = -1;   // -1: the caller's input (read only)
+    dr_tensor t = *xd;
+    int pi = 0;
+    const size_t nl = net->layers.size();
+    net->timed_valid = false;
+    if (net->timing && hipEventRecord(net->events[0], st) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipEventRecord failed", who);
+    for (size_t i = 0; i < nl; ++i) {
+        const dr_layer_desc& L = net->layers[i];
+        const dr_tensor& od = plan.outs[i];
+        const bool last = i + 1 == nl;
+        // ReLU runs in place unless it would overwrite the caller's input or is the last layer
+        const bool inplace = L.kind == DR_LAYER_RELU && cur_buf >= 0 && !last;
+        const int dst_buf = inplace ? cur_buf : (cur_buf == 0 ? 1 : 0);
+        void* dst = last ? y : (void*)buf[dst_buf];
+        Arena ar(scratch, plan.scratch_bytes, false);
+        switch (L.kind) {
+        case DR_LAYER_CONV:
+            DR_TRY(conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], nullptr, 0, od, dst, 0, st));
+            break;
+        case DR_LAYER_RELU: DR_TRY(launch_relu(t.dtype, cur, dst, tensor_elems(t), st)); break;
+        case DR_LAYER_LRN: DR_TRY(launch_lrn(t.dtype, cur, dst, t.n, t.c, t.h * t.w, L.lrn, st)); break;
+        case DR_LAYER_MAXPOOL: DR_TRY(launch_maxpool(t.dtype, cur, dst, t.n * t.c, t.h, t.w, od.h, od.w, L.pool, st)); break;
+        case DR_LAYER_AVGPOOL: DR_TRY(launch_avgpool(t.dtype, cur, dst, t.n * t.c, t.h, t.w, od.h, od.w, L.pool, st)); break;
+        case DR_LAYER_INCEPTION: {
+            const int np = param_count(L) / 2;
+            std::vector<const void*> w(np);
+            std::vector<const void*> b(np);
+            for (int j = 0; j < np; ++j) { w[j] = params[pi + 2 * j]; b[j] = params[pi + 2 * j + 1]; }
+            ParamCursor wc{w.data(), 0}, bc{b.data(), 0};
+            DR_TRY(inception_run(t, cur, L.inception, wc, bc, od, dst, ar, st));
+            break;
+        }
+        case DR_LAYER_BOTTLENECK: DR_TRY(bottleneck_run(t, cur, L.bottleneck, params + pi, od, dst, ar, st)); break;
+        case DR_LAYER_FC:
+            DR_TRY(launch_fc(t.dtype, cur, params[pi], (const float*)params[pi + 1], dst, t.n, t.c * t.h * t.w, od.c, st));
+            break;
+        case DR_LAYER_SOFTMAX: DR_TRY(launch_softmax(t.dtype, cur, (float*)dst, t.n, t.c, st)); break;
+        default: return fail(DR_ERR_UNSUPPORTED, "%s: unknown layer kind %d", who, L.kind);
+        }
+        pi += param_count(L);
+        cur = dst;
+        cur_buf = last ? -1 : dst_buf;
+        t = od;
+        if (net->timing && hipEventRecord(net->events[i + 1], st) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipEventRecord failed", who);
+    }
+    net->timed_valid = net->timing;
+    return DR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/deeprebirth.h"
+
+namespace dr {
+
+// Records a message for dr_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+// Checks the launch status of the kernels just enqueued.
+int check_launch(const char* what);
+
+inline size_t elem_size(int dtype) { return dtype == DR_BF16 ? 2 : 4; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t tensor_elems(const dr_tensor& t) { return (size_t)t.n * t.c * t.h * t.w; }
+inline size_t tensor_bytes(const dr_tensor& t) { return tensor_elems(t) * elem_size(t.dtype); }
+
+// Geometry of one convolution launch, filled by the host after validation.
+struct ConvGeom {
+    int N, C, H, W;      // input
+    int K, R, S;         // filters
+    int sh, sw, ph, pw;  // stride, padding
+    int P, Q;            // output spatial size
+    int Kg;              // GEMM K = C*R*S
+    int Ng;              // GEMM N = N*P*Q
+    int y_ctot, y_coff;  // channels of the output tensor, first channel written
+    int relu;            // fused max(.,0)
+    int res_ctot;        // channels of the residual tensor (0 = no residual add)
+};
+
+// conv_f32.hip / conv_bf16.hip: y = conv(x, w) + bias [+ residual] [ReLU].
+// `residual` (may be NULL) has the output's n, P, Q and res_ctot channels, read at channel j.
+int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const float* bias, const float* residual,
+                    float* y, hipStream_t st);
+int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
+                     const uint16_t* residual, uint16_t* y, hipStream_t st);
+
+// pointwise.hip
+int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st);
+int launch_lrn(int dtype, const void* x, void* y, int N, int C, int HW, const dr_lrn& p, hipStream_t st);
+int launch_maxpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p,
+                   hipStream_t st);
+int launch_avgpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p,
+                   hipStream_t st);
+struct ConcatSeg { const void* src; int c; int c_off; };
+int launch_concat(int dtype, int nb, const ConcatSeg* segs, void* y, int N, int Cy, int HW, hipStream_t st);
+int launch_bn(int dtype, const void* x, void* y, int N, int C, int HW, const float* gamma, const float* beta,
+              const float* mean, const float* var, float eps, int relu, hipStream_t st);
+int launch_add_relu(int dtype, const void* a, const void* b, void* y, size_t count, hipStream_t st);
+int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* y, int N, int I, int O, hipStream_t st);
+int launch_softmax(int dtype, const void* x, float* y, int N, int O, hipStream_t st);
+
+}  // namespace dr

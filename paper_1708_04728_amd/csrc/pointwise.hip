@@ -1,0 +1,453 @@
+// Bandwidth-bound layers: ReLU, across-channel LRN, max/avg pooling, concat, BatchNorm(+Scale),
+// residual add, plus the small classifier tail (inner product, softmax).  NCHW; fp32 or bf16 storage,
+// fp32 arithmetic.  Every kernel reads each input element once from HBM (neighbouring windows are
+// served by the caches) and writes each output once, with 16-byte accesses where the shape allows.
+#include "dr_internal.h"
+
+namespace dr {
+namespace {
+
+// ---- storage helpers -------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float((uint32_t)u << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;   // NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);                      // round to nearest, ties to even
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Store;
+template <> struct Store<float> {
+    static constexpr int VN = 4;   // elements per 16 bytes
+    static __device__ __forceinline__ float ld(const float* p) { return *p; }
+    static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+    static __device__ __forceinline__ void ldv(const float* p, float* v)
+    {
+        const float4 t = *reinterpret_cast<const float4*>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+    static __device__ __forceinline__ void stv(float* p, const float* v)
+    {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct Store<uint16_t> {
+    static constexpr int VN = 8;
+    static __device__ __forceinline__ float ld(const uint16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void st(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+    static __device__ __forceinline__ void ldv(const uint16_t* p, float* v)
+    {
+        const uint4 t = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+    static __device__ __forceinline__ void stv(uint16_t* p, const float* v)
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+inline unsigned blocks_for(size_t items, int per_block, size_t cap = 1u << 20)
+{
+    size_t b = (items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    return (unsigned)(b > cap ? cap : b);
+}
+
+// ---- ReLU / add+ReLU -----------------------------------------------------------------------------
+// ADD = false: y = max(a, 0);  ADD = true: y = max(a + b, 0).
+template <typename T, bool ADD>
+__global__ __launch_bounds__(256) void relu_kernel(const T* a, const T* b, T* y,
+                                                   size_t nvec, size_t count)
+{
+    constexpr int VN = Store<T>::VN;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+        float v[VN], u[VN];
+        Store<T>::ldv(a + i * VN, v);
+        if constexpr (ADD) Store<T>::ldv(b + i * VN, u);
+#pragma unroll
+        for (int j = 0; j < VN; ++j) v[j] = fmaxf(ADD ? v[j] + u[j] : v[j], 0.f);
+        Store<T>::stv(y + i * VN, v);
+    }
+    // scalar tail (and the whole tensor when the pointers are not 16-byte aligned: nvec = 0)
+    for (size_t i = nvec * VN + (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+        float v = Store<T>::ld(a + i);
+        if (ADD) v += Store<T>::ld(b + i);
+        Store<T>::st(y + i, fmaxf(v, 0.f));
+    }
+}
+
+template <typename T, bool ADD>
+int relu_launch(const void* a, const void* b, void* y, size_t count, hipStream_t st)
+{
+    if (count == 0) return DR_OK;
+    constexpr int VN = Store<T>::VN;
+    const bool vec = aligned16(a) && aligned16(y) && (!ADD || aligned16(b));
+    const size_t nvec = vec ? count / VN : 0;
+    const unsigned grid = blocks_for(nvec ? nvec : count, 256, 256 * 16);
+    hipLaunchKernelGGL((relu_kernel<T, ADD>), dim3(grid), dim3(256), 0, st, (const T*)a, (const T*)b, (T*)y, nvec, count);
+    return check_launch(ADD ? "add_relu" : "relu");
+}
+
+// ---- LRN ---------------------------------------------------------------------------------------------
+// s^(-beta); beta = 0.75 (the value every workload uses) needs no transcendental:
+// s^-0.75 = rsqrt(s) * sqrt(rsqrt(s)).
+__device__ __forceinline__ float pow_neg_beta(float s, float beta, bool b075)
+{
+    if (b075) {
+        const float r = 1.0f / sqrtf(s);
+        return r * sqrtf(r);
+    }
+    return powf(s, -beta);
+}
+
+// One thread owns V adjacent pixels (one 16-byte vector, or one element when V == 1) of one image and a
+// run of channels [c0, c1); it slides a window of NL channels held in registers down the channel
+// axis, so every input element is loaded once per run (plus NL-1 halo loads per run).
+template <typename T, int V, int NL>
+__global__ __launch_bounds__(256) void lrn_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int HW, int HWv,
+                                                  int chunk, int nchunks, float a_over_n, float beta, float k, int b075)
+{
+    const int pv = blockIdx.x * blockDim.x + threadIdx.x;
+    if (pv >= HWv) return;
+    const int n = blockIdx.y / nchunks, ch = blockIdx.y - n * nchunks;
+    const int c0 = ch * chunk, c1 = min(C, c0 + chunk);
+    constexpr int LO = NL / 2;                    // window of channel c = [c - LO, c - LO + NL)
+    const T* xb = x + (size_t)n * C * HW + (size_t)pv * V;
+    T* yb = y + (size_t)n * C * HW + (size_t)pv * V;
+
+    float win[NL][V];
+    auto fetch = [&](int c, float* v) {
+        if (c >= 0 && c < C) {
+            if constexpr (V == 1) v[0] = Store<T>::ld(xb + (size_t)c * HW);
+            else Store<T>::ldv(xb + (size_t)c * HW, v);
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) v[j] = 0.f;
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < NL - 1; ++i) fetch(c0 - LO + i, win[i + 1]);   // slots 1..NL-1; slot 0 is dropped first
+    for (int c = c0; c < c1; ++c) {
+#pragma unroll
+        for (int i = 0; i < NL - 1; ++i)
+#pragma unroll
+            for (int j = 0; j < V; ++j) win[i][j] = win[i + 1][j];
+        fetch(c - LO + NL - 1, win[NL - 1]);
+        float o[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float ss = 0.f;
+#pragma unroll
+            for (int i = 0; i < NL; ++i) ss = fmaf(win[i][j], win[i][j], ss);
+            o[j] = win[LO][j] * pow_neg_beta(fmaf(a_over_n, ss, k), beta, b075);
+        }
+        if constexpr (V == 1) Store<T>::st(yb + (size_t)c * HW, o[0]);
+        else Store<T>::stv(yb + (size_t)c * HW, o);
+    }
+}
+
+// Any window length: every output re-reads its window (served by the caches).
+template <typename T>
+__global__ __launch_bounds__(256) void lrn_generic_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int HW,
+                                                          size_t total, int nl, float a_over_n, float beta, float k)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int pix = (int)(i % HW);
+        const size_t nc = i / HW;
+        const int c = (int)(nc % C);
+        const size_t n = nc / C;
+        float ss = 0.f;
+        for (int cc = c - nl / 2; cc < c - nl / 2 + nl; ++cc)
+            if (cc >= 0 && cc < C) {
+                const float v = Store<T>::ld(x + (n * C + cc) * HW + pix);
+                ss = fmaf(v, v, ss);
+            }
+        Store<T>::st(y + i, Store<T>::ld(x + i) * powf(fmaf(a_over_n, ss, k), -beta));
+    }
+}
+
+template <typename T>
+int lrn_launch(const void* x, void* y, int N, int C, int HW, const dr_lrn& p, hipStream_t st)
+{
+    const float a_over_n = p.alpha / (float)p.local_size;
+    if (p.local_size != 5) {
+        const size_t total = (size_t)N * C * HW;
+        hipLaunchKernelGGL((lrn_generic_kernel<T>), dim3(blocks_for(total, 256, 256 * 32)), dim3(256), 0, st, (const T*)x,
+                           (T*)y, C, HW, total, p.local_size, a_over_n, p.beta, p.k);
+        return check_launch("lrn");
+    }
+    constexpr int VN = Store<T>::VN;
+    const bool vec = (HW % VN == 0) && aligned16(x) && aligned16(y);
+    const int HWv = vec ? HW / VN : HW;
+    if (N > 8192) return fail(DR_ERR_UNSUPPORTED, "lrn: batch %d exceeds 8192", N);
+    // split the channel axis into runs until the launch has enough threads to fill the device
+    const long want = 256L * 2048;
+    int nchunks = (int)((want + (long)N * HWv - 1) / ((long)N * HWv));
+    if (nchunks > C / 16) nchunks = C / 16;   // runs of >= 16 channels keep the halo re-reads <= 25%
+    if (nchunks < 1) nchunks = 1;
+    const int chunk = (C + nchunks - 1) / nchunks;
+    nchunks = (C + chunk - 1) / chunk;
+    const dim3 grid((HWv + 255) / 256, (unsigned)(N * nchunks));
+    const int b075 = p.beta == 0.75f;
+    if (vec)
+        hipLaunchKernelGGL((lrn_kernel<T, VN, 5>), grid, dim3(256), 0, st, (const T*)x, (T*)y, C, HW, HWv, chunk, nchunks,
+                           a_over_n, p.beta, p.k, b075);
+    else
+        hipLaunchKernelGGL((lrn_kernel<T, 1, 5>), grid, dim3(256), 0, st, (const T*)x, (T*)y, C, HW, HWv, chunk, nchunks,
+                           a_over_n, p.beta, p.k, b075);
+    return check_launch("lrn");
+}
+
+// ---- pooling --------------------------------------------------------------------------------------------
+// One output element per thread, lanes along q.  AVG = false: maximum over the window clipped to the
+// input;  AVG = true: mean over the full window (no padding allowed).
+template <typename T, bool AVG>
+__global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ x, T* __restrict__ y, int H, int W, int P, int Q,
+                                                   size_t total, dr_pool p)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int q = (int)(i % Q);
+        const size_t t = i / Q;
+        const int pp = (int)(t % P);
+        const size_t nc = t / P;
+        const int h0 = pp * p.stride_h - p.pad_h, w0 = q * p.stride_w - p.pad_w;
+        const int ha = max(h0, 0), hb = min(h0 + p.kh, H);
+        const int wa = max(w0, 0), wb = min(w0 + p.kw, W);
+        const T* xb = x + nc * H * W;
+        float m = AVG ? 0.f : -INFINITY;
+        for (int h = ha; h < hb; ++h)
+            for (int w = wa; w < wb; ++w) {
+                const float v = Store<T>::ld(xb + h * W + w);
+                m = AVG ? m + v : fmaxf(m, v);
+            }
+        if (AVG) m /= (float)(p.kh * p.kw);
+        Store<T>::st(y + i, m);
+    }
+}
+
+template <typename T, bool AVG>
+int pool_launch(const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p, hipStream_t st)
+{
+    const size_t total = (size_t)NC * P * Q;
+    if (total == 0) return DR_OK;
+    hipLaunchKernelGGL((pool_kernel<T, AVG>), dim3(blocks_for(total, 256, 256 * 64)), dim3(256), 0, st, (const T*)x, (T*)y,
+                       H, W, P, Q, total, p);
+    return check_launch(AVG ? "avgpool" : "maxpool");
+}
+
+// ---- concat ----------------------------------------------------------------------------------------------
+struct ConcatArgs {
+    const void* src[DR_MAX_BRANCHES];
+    int c[DR_MAX_BRANCHES];
+    int c_off[DR_MAX_BRANCHES];
+};
+
+// blockIdx.z = branch, blockIdx.y = image; within an image a branch is one contiguous run of c*HW
+// elements in both the source and the destination.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void concat_kernel(ConcatArgs a, T* __restrict__ y, int Cy, int HW)
+{
+    const int b = blockIdx.z, n = blockIdx.y;
+    const size_t run = (size_t)a.c[b] * HW;
+    const T* src = (const T*)a.src[b] + (size_t)n * run;
+    T* dst = y + ((size_t)n * Cy + a.c_off[b]) * HW;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i * V < run; i += stride) {
+        if constexpr (V == 1) dst[i] = src[i];
+        else *reinterpret_cast<uint4*>(dst + i * V) = *reinterpret_cast<const uint4*>(src + i * V);
+    }
+}
+
+template <typename T>
+int concat_launch(int nb, const ConcatSeg* segs, void* y, int N, int Cy, int HW, hipStream_t st)
+{
+    constexpr int VN = Store<T>::VN;
+    ConcatArgs a;
+    bool vec = aligned16(y) && ((size_t)Cy * HW % VN == 0);
+    int cmax = 0;
+    for (int i = 0; i < nb; ++i) {
+        a.src[i] = segs[i].src; a.c[i] = segs[i].c; a.c_off[i] = segs[i].c_off;
+        vec = vec && aligned16(segs[i].src) && ((size_t)segs[i].c * HW % VN == 0) && ((size_t)segs[i].c_off * HW % VN == 0);
+        if (segs[i].c > cmax) cmax = segs[i].c;
+    }
+    if (N == 0 || cmax == 0 || HW == 0) return DR_OK;
+    if (N > 65535) return fail(DR_ERR_UNSUPPORTED, "concat: batch %d exceeds 65535", N);
+    const size_t items = (size_t)cmax * HW / (vec ? VN : 1);
+    const dim3 grid(blocks_for(items, 256 * 4, 4096), (unsigned)N, (unsigned)nb);
+    if (vec) hipLaunchKernelGGL((concat_kernel<T, VN>), grid, dim3(256), 0, st, a, (T*)y, Cy, HW);
+    else hipLaunchKernelGGL((concat_kernel<T, 1>), grid, dim3(256), 0, st, a, (T*)y, Cy, HW);
+    return check_launch("concat");
+}
+
+// ---- BatchNorm + Scale ------------------------------------------------------------------------------
+// blockIdx.y walks the (n, c) planes, so the four per-channel parameters are wave-uniform.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void bn_kernel(const T* x, T* y, int NC, int C, int HW,
+                                                 const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                 const float* __restrict__ mean, const float* __restrict__ var, float eps,
+                                                 int relu)
+{
+    for (int plane = blockIdx.y; plane < NC; plane += gridDim.y) {
+        const int c = plane % C;
+        const float mu = mean[c];
+        const float inv = 1.0f / sqrtf(var[c] + eps);
+        const float ga = gamma[c], be = beta[c];
+        const T* xb = x + (size_t)plane * HW;
+        T* yb = y + (size_t)plane * HW;
+        for (int i = blockIdx.x * blockDim.x + threadIdx.x; i * V < HW; i += gridDim.x * blockDim.x) {
+            float v[V];
+            if constexpr (V == 1) v[0] = Store<T>::ld(xb + i);
+            else Store<T>::ldv(xb + (size_t)i * V, v);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                v[j] = ga * ((v[j] - mu) * inv) + be;
+                if (relu) v[j] = fmaxf(v[j], 0.f);
+            }
+            if constexpr (V == 1) Store<T>::st(yb + i, v[0]);
+            else Store<T>::stv(yb + (size_t)i * V, v);
+        }
+    }
+}
+
+template <typename T>
+int bn_launch(const void* x, void* y, int N, int C, int HW, const float* gamma, const float* beta, const float* mean,
+              const float* var, float eps, int relu, hipStream_t st)
+{
+    if ((size_t)N * C * HW == 0) return DR_OK;
+    constexpr int VN = Store<T>::VN;
+    const bool vec = (HW % VN == 0) && aligned16(x) && aligned16(y);
+    const int items = vec ? HW / VN : HW;
+    const dim3 grid(blocks_for(items, 256, 64), (unsigned)((size_t)N * C < 32768 ? N * C : 32768));
+    if (vec)
+        hipLaunchKernelGGL((bn_kernel<T, VN>), grid, dim3(256), 0, st, (const T*)x, (T*)y, N * C, C, HW, gamma, beta, mean, var, eps,
+                           relu);
+    else
+        hipLaunchKernelGGL((bn_kernel<T, 1>), grid, dim3(256), 0, st, (const T*)x, (T*)y, N * C, C, HW, gamma, beta, mean, var, eps,
+                           relu);
+    return check_launch("bn");
+}
+
+// ---- inner product ---------------------------------------------------------------------------------
+// One wave per output unit o and a slice of the batch: lanes stride over the inputs (coalesced
+// reads of the weight row and of the activation row), then a butterfly reduction.
+template <typename T>
+__global__ __launch_bounds__(64) void fc_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                const float* __restrict__ bias, T* __restrict__ y, int N, int I, int O)
+{
+    const int o = blockIdx.x, lane = threadIdx.x;
+    const float b = bias ? bias[o] : 0.f;
+    const T* wr = w + (size_t)o * I;
+    for (int n = blockIdx.y; n < N; n += gridDim.y) {
+        const T* xr = x + (size_t)n * I;
+        float acc = 0.f;
+        for (int i = lane; i < I; i += 64) acc = fmaf(Store<T>::ld(wr + i), Store<T>::ld(xr + i), acc);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+        if (lane == 0) Store<T>::st(y + (size_t)n * O + o, acc + b);
+    }
+}
+
+// ---- softmax ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_kernel(const T* __restrict__ x, float* __restrict__ y, int O)
+{
+    __shared__ float red[4];
+    const T* xb = x + (size_t)blockIdx.x * O;
+    float* yb = y + (size_t)blockIdx.x * O;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float m = -INFINITY;
+    for (int i = threadIdx.x; i < O; i += 256) m = fmaxf(m, Store<T>::ld(xb + i));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    float s = 0.f;
+    for (int i = threadIdx.x; i < O; i += 256) s += expf(Store<T>::ld(xb + i) - m);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    s = (red[0] + red[1]) + (red[2] + red[3]);
+    for (int i = threadIdx.x; i < O; i += 256) yb[i] = expf(Store<T>::ld(xb + i) - m) / s;
+}
+
+}  // namespace
+
+#define DR_BY_DTYPE(dtype, call_f32, call_bf16) ((dtype) == DR_BF16 ? (call_bf16) : (call_f32))
+
+int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st)
+{
+    return DR_BY_DTYPE(dtype, (relu_launch<float, false>(x, nullptr, y, count, st)),
+                       (relu_launch<uint16_t, false>(x, nullptr, y, count, st)));
+}
+
+int launch_add_relu(int dtype, const void* a, const void* b, void* y, size_t count, hipStream_t st)
+{
+    return DR_BY_DTYPE(dtype, (relu_launch<float, true>(a, b, y, count, st)), (relu_launch<uint16_t, true>(a, b, y, count, st)));
+}
+
+int launch_lrn(int dtype, const void* x, void* y, int N, int C, int HW, const dr_lrn& p, hipStream_t st)
+{
+    if ((size_t)N * C * HW == 0) return DR_OK;
+    return DR_BY_DTYPE(dtype, lrn_launch<float>(x, y, N, C, HW, p, st), lrn_launch<uint16_t>(x, y, N, C, HW, p, st));
+}
+
+int launch_maxpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p, hipStream_t st)
+{
+    return DR_BY_DTYPE(dtype, (pool_launch<float, false>(x, y, NC, H, W, P, Q, p, st)),
+                       (pool_launch<uint16_t, false>(x, y, NC, H, W, P, Q, p, st)));
+}
+
+int launch_avgpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p, hipStream_t st)
+{
+    return DR_BY_DTYPE(dtype, (pool_launch<float, true>(x, y, NC, H, W, P, Q, p, st)),
+                       (pool_launch<uint16_t, true>(x, y, NC, H, W, P, Q, p, st)));
+}
+
+int launch_concat(int dtype, int nb, const ConcatSeg* segs, void* y, int N, int Cy, int HW, hipStream_t st)
+{
+    return DR_BY_DTYPE(dtype, concat_launch<float>(nb, segs, y, N, Cy, HW, st), concat_launch<uint16_t>(nb, segs, y, N, Cy, HW, st));
+}
+
+int launch_bn(int dtype, const void* x, void* y, int N, int C, int HW, const float* gamma, const float* beta,
+              const float* mean, const float* var, float eps, int relu, hipStream_t st)
+{
+    return DR_BY_DTYPE(dtype, bn_launch<float>(x, y, N, C, HW, gamma, beta, mean, var, eps, relu, st),
+                       bn_launch<uint16_t>(x, y, N, C, HW, gamma, beta, mean, var, eps, relu, st));
+}
+
+int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* y, int N, int I, int O, hipStream_t st)
+{
+    if (N == 0 || O == 0) return DR_OK;
+    const dim3 grid((unsigned)O, (unsigned)(N < 8 ? N : 8));
+    if (dtype == DR_BF16)
+        hipLaunchKernelGGL((fc_kernel<uint16_t>), grid, dim3(64), 0, st, (const uint16_t*)x, (const uint16_t*)w, bias, (uint16_t*)y, N, I, O);
+    else
+        hipLaunchKernelGGL((fc_kernel<float>), grid, dim3(64), 0, st, (const float*)x, (const float*)w, bias, (float*)y, N, I, O);
+    return check_launch("fc");
+}
+
+int launch_softmax(int dtype, const void* x, float* y, int N, int O, hipStream_t st)
+{
+    if (N == 0 || O == 0) return DR_OK;
+    if (dtype == DR_BF16) hipLaunchKernelGGL((softmax_kernel<uint16_t>), dim3(N), dim3(256), 0, st, (const uint16_t*)x, y, O);
+    else hipLaunchKernelGGL((softmax_kernel<float>), dim3(N), dim3(256), 0, st, (const float*)x, y, O);
+    return check_launch("softmax");
+}
+
+}  // namespace dr

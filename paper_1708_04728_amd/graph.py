@@ -1,0 +1,121 @@
+"""Layer lists (vocabulary of ``workloads.py``) -> library descriptors and device parameters.
+
+Host-side marshalling only; every shape is computed by the library itself."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(dtype):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def to_device(a, dtype="f32", device="cuda"):
+    """numpy fp32 array -> device tensor; for bf16 the values must already be bf16-representable,
+    so the conversion is exact."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.to(device)
+
+
+def conv_desc(p, c_in, relu=False):
+    return B.conv_desc(p["k"], c_in, p["r"], p["s"], p["stride"], p["pad"], relu)
+
+
+def inception_desc(p, c_in, mode=0):
+    """dr_inception from an ("inception", {...}) layer; a conv directly followed by a relu gets
+    conv.relu = 1."""
+    d = B.dr_inception()
+    d.n_branches = len(p["branches"])
+    d.mode = mode
+    for bi, br in enumerate(p["branches"]):
+        c, si, i = c_in, 0, 0
+        while i < len(br):
+            kind, q = br[i]
+            step = d.branches[bi].steps[si]
+            if kind == "conv":
+                relu = i + 1 < len(br) and br[i + 1][0] == "relu"
+                step.kind, step.conv = B.DR_STEP_CONV, conv_desc(q, c, relu)
+                c = q["k"]
+                i += 2 if relu else 1
+            elif kind == "maxpool":
+                step.kind, step.pool = B.DR_STEP_MAXPOOL, B.pool_desc(q["k"], q["stride"], q["pad"])
+                i += 1
+            else:
+                raise ValueError("step %s not allowed in an inception branch" % kind)
+            si += 1
+        d.branches[bi].n_steps = si
+    return d
+
+
+def _out_channels(layers, c_in):
+    c = c_in
+    for kind, p in layers:
+        if kind == "conv":
+            c = p["k"]
+        elif kind == "inception":
+            c = sum(_out_channels(br, c) for br in p["branches"])
+        elif kind == "bottleneck":
+            c = p["out"]
+        elif kind == "fc":
+            c = p["out"]
+    return c
+
+
+def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False):
+    """List of dr_layer_desc for a layer list.
+
+    fuse_relu: a conv directly followed by a relu becomes one conv with the ReLU in its store
+               (the slim form always runs this way; for the original form it is the "fused"
+               variant reported next to the layer-by-layer one)."""
+    out, c, i = [], c_in, 0
+    while i < len(layers):
+        kind, p = layers[i]
+        L = B.dr_layer_desc()
+        if kind == "conv":
+            relu = fuse_relu and i + 1 < len(layers) and layers[i + 1][0] == "relu"
+            L.kind, L.conv = B.DR_LAYER_CONV, conv_desc(p, c, relu)
+            c = p["k"]
+            if relu:
+                i += 1
+        elif kind == "relu":
+            L.kind = B.DR_LAYER_RELU
+        elif kind == "lrn":
+            L.kind, L.lrn = B.DR_LAYER_LRN, B.dr_lrn(p["n"], p["alpha"], p["beta"], p["k"])
+        elif kind == "maxpool":
+            L.kind, L.pool = B.DR_LAYER_MAXPOOL, B.pool_desc(p["k"], p["stride"], p["pad"])
+        elif kind == "avgpool":
+            L.kind, L.pool = B.DR_LAYER_AVGPOOL, B.pool_desc(p["k"], 1, 0)
+        elif kind == "inception":
+            L.kind, L.inception = B.DR_LAYER_INCEPTION, inception_desc(p, c, inception_mode)
+            c = _out_channels([(kind, p)], c)
+        elif kind == "bottleneck":
+            L.kind = B.DR_LAYER_BOTTLENECK
+            L.bottleneck = B.dr_bottleneck(p["mid"], p["out"], int(p["project"]), int(folded), p["eps"])
+            c = p["out"]
+        elif kind == "fc":
+            L.kind, L.fc_out = B.DR_LAYER_FC, p["out"]
+            c = p["out"]
+        elif kind == "softmax":
+            L.kind = B.DR_LAYER_SOFTMAX
+        else:
+            raise ValueError(kind)
+        out.append(L)
+        i += 1
+    return out
+
+
+def flat_params(params, dtype="f32", device="cuda", folded_from=None):
+    """Device tensors in the order dr_net_fwd expects: conv/fc -> w, bias; bn -> gamma, beta,
+    mean, var (all fp32 except w)."""
+    out = []
+    for q in params:
+        if "w" in q:
+            out += [to_device(q["w"], dtype, device), to_device(q["b"], "f32", device)]
+        else:
+            out += [to_device(q[k], "f32", device) for k in ("gamma", "beta", "mean", "var")]
+    return out

@@ -1,0 +1,132 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header declares,
+rejects bad arguments before touching a GPU, and its host-only routines (shape rules, Lemma 2
+fold) agree with the oracle.  No GPU needed."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from paper_1708_04728_amd import binding as B, graph as G, slim
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(dr_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = C.CDLL(B.LIB_PATH)
+    syms = declared_symbols()
+    assert len(syms) >= 25
+    for name in syms:
+        assert hasattr(lib, name), name
+    assert set(B._SIGNATURES) == set(syms)
+    assert B.lib().dr_version().decode().startswith("deeprebirth")
+
+
+def test_shape_rules_match_oracle():
+    for n in range(1, 40):
+        for k in (1, 2, 3, 5, 7, 11):
+            for s in (1, 2, 3, 4, 8):
+                for pad in (0, 1, 2, 3):
+                    assert B.conv_out_size(n, k, s, pad) == oracle.conv_out_size(n, k, s, pad), (n, k, s, pad)
+                    if pad < k:
+                        assert B.pool_out_size(n, k, s, pad) == oracle.pool_out_size(n, k, s, pad), (n, k, s, pad)
+
+
+def _t(n, c, h, w, dt=B.DR_F32):
+    return B.dr_tensor(n, c, h, w, dt)
+
+
+def test_argument_validation_runs_before_any_launch():
+    L = B.lib()
+    xd, yd = _t(1, 4, 8, 8), _t(1, 6, 8, 8)
+    cd = B.conv_desc(6, 4, 3, pad=1)
+    fake = C.c_void_p(4096)   # never dereferenced: every call below must fail in validation
+    assert L.dr_conv2d_fwd(xd, None, cd, fake, None, yd, fake, 0, None) == B.DR_ERR_NULL
+    assert "NULL" in B.last_error()
+    assert L.dr_conv2d_fwd(xd, fake, cd, fake, None, _t(1, 6, 7, 8), fake, 0, None) == B.DR_ERR_SHAPE
+    assert L.dr_conv2d_fwd(xd, fake, cd, fake, None, yd, fake, 1, None) == B.DR_ERR_SHAPE        # channels overflow
+    assert L.dr_conv2d_fwd(_t(1, 5, 8, 8), fake, cd, fake, None, yd, fake, 0, None) == B.DR_ERR_SHAPE
+    assert L.dr_conv2d_fwd(xd, fake, B.conv_desc(6, 4, 3, stride=0), fake, None, yd, fake, 0, None) == B.DR_ERR_SHAPE
+    assert L.dr_conv2d_fwd(_t(1, 4, 8, 8, 7), fake, cd, fake, None, yd, fake, 0, None) == B.DR_ERR_UNSUPPORTED
+    assert L.dr_slim_conv_fwd(xd, fake, cd, 2, 2, fake, None, yd, fake, 0, None) == B.DR_ERR_SHAPE   # needs 4x4 output
+    assert L.dr_maxpool_fwd(xd, fake, B.pool_desc(3, 2), _t(1, 4, 3, 3), fake, None) == B.DR_ERR_SHAPE  # ceil rule: 4x4
+    assert L.dr_maxpool_fwd(xd, fake, B.pool_desc(3, 2, 3), _t(1, 4, 4, 4), fake, None) == B.DR_ERR_SHAPE  # pad >= window
+    assert L.dr_lrn_fwd(xd, fake, B.dr_lrn(0, 1e-4, 0.75, 1.0), fake, None) in (B.DR_ERR_SHAPE, B.DR_ERR_UNSUPPORTED)
+    assert L.dr_relu(None, fake, fake, None) == B.DR_ERR_NULL
+    xds = (B.dr_tensor * 2)(_t(1, 2, 4, 4), _t(1, 3, 4, 4))
+    ptrs = (C.c_void_p * 2)(4096, 8192)
+    assert L.dr_concat(2, xds, ptrs, _t(1, 6, 4, 4), fake, None) == B.DR_ERR_SHAPE
+    assert L.dr_concat(9, xds, ptrs, _t(1, 5, 4, 4), fake, None) == B.DR_ERR_SHAPE
+    assert L.dr_softmax_fwd(_t(2, 10, 2, 1), fake, fake, None) == B.DR_ERR_SHAPE
+
+
+def test_inception_and_net_planning_on_host():
+    layers = workloads.CONFIGS[2]["original"]
+    d = G.inception_desc(layers[0][1], 192, 0)
+    assert d.n_branches == 4 and [d.branches[i].n_steps for i in range(4)] == [1, 2, 2, 2]
+    n = C.c_size_t(0)
+    xd = _t(32, 192, 28, 28)
+    assert B.lib().dr_inception_workspace_bytes(xd, d, C.byref(n)) == B.DR_OK
+    # layer-by-layer form keeps every branch tensor: 64+96+128+16+32+192+32 channels of 32x28x28 fp32
+    assert n.value == (64 + 96 + 128 + 16 + 32 + 192 + 32) * 32 * 784 * 4
+    d2 = G.inception_desc(layers[0][1], 192, B.DR_FUSE_RELU | B.DR_FUSE_CONCAT)
+    assert B.lib().dr_inception_workspace_bytes(xd, d2, C.byref(n)) == B.DR_OK
+    assert n.value == (96 + 16 + 192) * 32 * 784 * 4
+    bad = G.inception_desc(layers[0][1], 100, 0)
+    assert B.lib().dr_inception_workspace_bytes(xd, bad, C.byref(n)) == B.DR_ERR_SHAPE
+
+    for form in ("original", "slim"):
+        net = B.Net(G.net_descs(workloads.CONFIGS[5][form], 3, fuse_relu=(form == "slim")))
+        assert net.num_params() == 2 * len(workloads.make_params(5, form))
+        yd = net.output_desc(_t(4, 3, 224, 224, B.DR_BF16))
+        assert (yd.n, yd.c, yd.h, yd.w, yd.dtype) == (4, 1000, 1, 1, B.DR_F32)
+        assert net.workspace_bytes(_t(4, 3, 224, 224, B.DR_BF16)) > 0
+    net = B.Net(G.net_descs(workloads.CONFIGS[4]["original"], 64))
+    assert net.num_params() == 6 * 4 + 6 * 3 + 6 * 3
+    yd = net.output_desc(_t(2, 64, 56, 56, B.DR_BF16))
+    assert (yd.n, yd.c, yd.h, yd.w) == (2, 256, 56, 56)
+    net = B.Net(G.net_descs(workloads.CONFIGS[1]["original"], 64))
+    with pytest.raises(B.DeepRebirthError):
+        net.output_desc(_t(2, 32, 56, 56))
+
+
+def test_fold_bn_host_matches_lemma2():
+    rng = np.random.default_rng(5)
+    w = rng.standard_normal((7, 3, 3, 3)).astype(np.float32)
+    b = rng.standard_normal(7).astype(np.float32)
+    g, be = rng.uniform(0.5, 1.5, 7).astype(np.float32), rng.standard_normal(7).astype(np.float32)
+    mu, var = rng.standard_normal(7).astype(np.float32), rng.uniform(0.5, 1.5, 7).astype(np.float32)
+    wf, bf = B.fold_bn(w, b, g, be, mu, var, 1e-5)
+    # fp32 eps is not exactly 1e-5: hand the oracle the value the library saw
+    wo, bo = oracle.fold_bn(w, b, g, be, mu, var, float(np.float32(1e-5)))
+    np.testing.assert_allclose(wf, wo, rtol=1e-7)
+    np.testing.assert_allclose(bf, bo, rtol=2e-7, atol=1e-7)
+    assert np.array_equal(wf, wo.astype(np.float32)) and np.array_equal(bf, bo.astype(np.float32))
+
+
+def test_slim_transforms_reproduce_the_configurations():
+    for cid in (1, 2, 3, 5):
+        assert slim.slim_network(workloads.CONFIGS[cid]["original"]) == workloads.CONFIGS[cid]["slim"], cid
+    # stride rule: new stride = conv stride x pool stride; LRN dropped; ReLU kept
+    s = slim.streamline_slim(workloads.CONFIGS[3]["original"])
+    assert [k for k, _ in s] == ["conv", "relu", "conv", "relu"]
+    assert s[0][1]["stride"] == 8 and s[2][1]["stride"] == 2
+    # branch slimming keeps the concatenated width
+    for name, wd in workloads.INCEPTION_WIDTHS.items():
+        br = slim.branch_slim(workloads.inception_original(name))[1]["branches"]
+        assert len(br) == 2
+        assert br[0][2][1]["k"] + br[1][2][1]["k"] == wd[1] + wd[3] + wd[5] + wd[6]
+        assert br[1][2][1]["r"] == 5

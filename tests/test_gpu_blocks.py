@@ -1,0 +1,101 @@
+"""GPU parity of the composite entry points (inception_fwd, net_fwd) against the oracle on the
+seeded workloads: original and slim forms, every execution mode of the module."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from paper_1708_04728_amd import binding as B, graph as G
+from util import TOL_BF16, TOL_F32, host, rel_err
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+MODES = [0, B.DR_FUSE_RELU, B.DR_FUSE_CONCAT, B.DR_FUSE_RELU | B.DR_FUSE_CONCAT,
+         B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK]
+
+
+def run_inception(layer, params, x, mode, dtype="f32"):
+    xg = G.to_device(x, dtype)
+    d = G.inception_desc(layer[1], x.shape[1], mode)
+    ws = torch.empty(max(B.inception_workspace_bytes(xg, d), 256), dtype=torch.uint8, device="cuda")
+    c_out = G._out_channels([layer], x.shape[1])
+    y = torch.full((x.shape[0], c_out, x.shape[2], x.shape[3]), float("nan"), dtype=G.torch_dtype(dtype), device="cuda")
+    flat = G.flat_params(params, dtype)
+    B.inception_fwd(xg, d, flat[0::2], flat[1::2], y, ws)
+    torch.cuda.synchronize()
+    return host(y)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("form", ["original", "slim"])
+def test_inception_3a(form, mode):
+    layer = workloads.CONFIGS[2][form][0]
+    params = workloads.make_params(2, form)
+    x = workloads.make_input(2, 3)
+    ref = oracle.forward([layer], params, x)
+    got = run_inception(layer, params, x, mode)
+    assert rel_err(got, ref) < TOL_F32
+
+
+def test_inception_3a_paper_variant_and_ragged_spatial():
+    layer = workloads.inception_3a_paper_variant()
+    params = workloads.make_params(2, "slim", layers=[layer])
+    x = workloads.make_input(2, 2)[:, :, :13, :11]
+    ref = oracle.forward([layer], params, x)
+    assert ref.shape == (2, 256, 13, 11)
+    for mode in (0, B.DR_FUSE_RELU | B.DR_FUSE_CONCAT):
+        assert rel_err(run_inception(layer, params, x, mode), ref) < TOL_F32
+
+
+def run_net(layers, params, x, dtype="f32", fuse_relu=False, inception_mode=0, folded=False, timing=False):
+    xg = G.to_device(x, dtype)
+    net = B.Net(G.net_descs(layers, x.shape[1], inception_mode=inception_mode, fuse_relu=fuse_relu, folded=folded))
+    yd = net.output_desc(B.desc(xg))
+    y = torch.full((yd.n, yd.c, yd.h, yd.w), float("nan"), dtype=torch.float32 if yd.dtype == B.DR_F32 else torch.bfloat16,
+                   device="cuda")
+    ws = torch.empty(max(net.workspace_bytes(B.desc(xg)), 256), dtype=torch.uint8, device="cuda")
+    if timing:
+        net.set_timing(True)
+    net.fwd(xg, G.flat_params(params, dtype), y, ws)
+    torch.cuda.synchronize()
+    out = host(y)
+    return (out, net.layer_times()) if timing else out
+
+
+@pytest.mark.parametrize("form,fuse", [("original", False), ("original", True), ("slim", True)])
+def test_config1_streamline_block(form, fuse):
+    layers = workloads.CONFIGS[1][form]
+    params = workloads.make_params(1, form)
+    x = workloads.make_input(1)
+    ref = oracle.forward(layers, params, x)
+    assert ref.shape == (1, 192, 28, 28)
+    assert rel_err(run_net(layers, params, x, fuse_relu=fuse), ref) < TOL_F32
+
+
+@pytest.mark.parametrize("form,fuse", [("original", False), ("slim", True)])
+def test_config3_alexnet_front(form, fuse):
+    layers = workloads.CONFIGS[3][form]
+    params = workloads.make_params(3, form)
+    x = workloads.make_input(3, 2)
+    ref = oracle.forward(layers, params, x)
+    assert ref.shape == ((2, 256, 13, 13) if form == "original" else (2, 256, 14, 14))
+    got, times = run_net(layers, params, x, fuse_relu=fuse, timing=True)
+    assert rel_err(got, ref) < TOL_F32
+    assert len(times) == len(G.net_descs(layers, 3, fuse_relu=fuse)) and all(t >= 0 for t in times)
+
+
+def test_config2_through_net_fwd_full_batch_sampled():
+    """Config 2 at its full batch in the launch configuration the benchmark times; the oracle
+    checks four of the 32 images (images are independent)."""
+    x = workloads.make_input(2)
+    assert x.shape == (32, 192, 28, 28)
+    pick = [0, 13, 30, 31]
+    for form, mode in (("original", 0), ("slim", B.DR_FUSE_RELU | B.DR_FUSE_CONCAT)):
+        layers = workloads.CONFIGS[2][form]
+        params = workloads.make_params(2, form)
+        got = run_net(layers, params, x, inception_mode=mode)
+        assert got.shape == (32, 256, 28, 28)
+        ref = oracle.forward(layers, params, x[pick])
+        assert rel_err(got[pick], ref) < TOL_F32
+        assert np.isfinite(got).all() and (got >= 0).all()

@@ -1,0 +1,30 @@
+"""Helpers shared by the tests (no arithmetic of the method)."""
+import numpy as np
+
+TOL_F32 = 1e-4    # max relative error, fp32 path
+TOL_BF16 = 2e-2   # max relative error, bf16 storage with fp32 accumulation
+
+
+def rel_err(got, ref):
+    """max_i |g_i - r_i| / max(|r_i|, rms(r)): relative error with an RMS floor, so that exact
+    zeros after a ReLU and softmax tails do not divide by ~0."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    rms = np.sqrt(np.mean(ref * ref))
+    den = np.maximum(np.abs(ref), max(rms, 1e-300))
+    return float(np.max(np.abs(got - ref) / den))
+
+
+def gpu(a, dtype="f32"):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.cuda()
+
+
+def host(t):
+    return t.float().cpu().numpy().astype(np.float64)
