@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the forward hot path on one MI355X: original form vs slim form.
+
+One "step" = one forward pass of the ORIGINAL block (layer by layer: conv, ReLU, LRN / max-pool /
+concat kernels as separate passes, the form the paper times) followed by one forward pass of the
+SLIM block (slimmed structure, ReLU in the conv store, branches written straight into the
+concatenated tensor), both over the same batch already resident in HBM.
+
+Prints ONE JSON line: whole-step throughput (`value`, images/s through both forms), the per-form
+times and the slim/original speed-up, the roofline of the dominant kernel (measured with HIP events
+around that kernel inside the timed region) and the CPU oracle timed on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MI355X_HBM_GBS = 8000.0
+MI355X_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+WORKLOAD_NAMES = {
+    1: "config 1: GoogLeNet conv2 streamline block, batch 1, fp32, 64x56x56 -> 192x28x28",
+    2: "config 2: GoogLeNet inception(3a), batch 32, fp32, 192x28x28 -> 256x28x28",
+    3: "config 3: AlexNet front end (conv1+conv2 blocks), batch 128, fp32, 3x227x227",
+}
+
+
+def conv_flops(rec):
+    label, k, c, r, s, items, ms = rec
+    return 2.0 * k * c * r * s * items
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOAD_NAMES))
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the path shards by batch with no communication, "
+              "so --gpus %d is not measured here" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import workloads
+    from paper_1708_04728_amd import binding as B, graph as G
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    B.lib()                                    # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = workloads.CONFIGS[args.config]
+    dtype = cfg["dtype"]
+    x_host = workloads.make_input(args.config)
+    batch, c_in = x_host.shape[0], x_host.shape[1]
+    x = G.to_device(x_host, dtype)
+    stream = torch.cuda.current_stream()
+
+    forms = {}
+    for form in ("original", "slim"):
+        layers = cfg[form]
+        params_host = workloads.make_params(args.config, form)
+        slim = form == "slim"
+        net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT) if slim else 0,
+                                fuse_relu=slim))
+        yd = net.output_desc(B.desc(x))
+        y = torch.empty((yd.n, yd.c, yd.h, yd.w), dtype=G.torch_dtype(dtype), device="cuda")
+        ws = torch.empty(max(net.workspace_bytes(B.desc(x)), 256), dtype=torch.uint8, device="cuda")
+        forms[form] = dict(net=net, y=y, ws=ws, params=G.flat_params(params_host, dtype), layers=layers,
+                           params_host=params_host)
+
+    def run(form):
+        f = forms[form]
+        f["net"].fwd(x, f["params"], f["y"], f["ws"], stream)
+
+    def step():
+        run("original")
+        run("slim")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- untimed traced pass: every kernel of one step, to find the dominant one and the per-kind split
+    B.trace_begin("", capacity=4096)
+    run("original")
+    n_orig = None
+    recs = B.trace_end()
+    n_orig = len(recs)
+    B.trace_begin("", capacity=4096)
+    run("slim")
+    recs_slim = B.trace_end()
+    all_recs = recs + recs_slim
+    dom = max(all_recs, key=lambda r: r[6])
+    dom_is_conv = dom[0].startswith("conv")
+
+    # ---- timed region: K steps, with one event pair around every launch of the dominant kernel
+    if dom_is_conv:
+        B.trace_begin(dom[0], dom[1], dom[2], dom[3], capacity=4 * args.steps + 16)
+    else:
+        B.trace_begin(dom[0], capacity=64 * args.steps + 16)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_recs = [r for r in B.trace_end(64 * args.steps + 16) if r[:6] == dom[:6]]
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    dom_ms = float(np.mean([r[6] for r in dom_recs]))
+
+    # ---- per-form times (events on the launch stream), best and median as the paper reports best runs
+    form_ms = {}
+    for form in ("original", "slim"):
+        ts = []
+        for _ in range(max(args.steps, 10)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            run(form)
+            e1.record(stream)
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        form_ms[form] = (float(np.min(ts)), float(np.median(ts)))
+
+    # ---- roofline of the dominant kernel
+    esz = 2 if dtype == "bf16" else 4
+    if dom_is_conv:
+        flops = conv_flops(dom)
+        achieved = flops / (dom_ms * 1e-3) / 1e12
+        peak = MI355X_MFMA_TFLOPS[dtype]
+        roofline = {"bound": "mfma", "kernel": "%s %dx%d %d->%d" % (dom[0], dom[3], dom[4], dom[2], dom[1]),
+                    "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                    "launch_ms": round(dom_ms, 5), "launches_timed": len(dom_recs), "traffic": None}
+    else:
+        nbytes = 2.0 * dom[5] * esz
+        achieved = nbytes / (dom_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": MI355X_HBM_GBS,
+                    "unit": "GB/s", "frac": round(achieved / MI355X_HBM_GBS, 4), "launch_ms": round(dom_ms, 5),
+                    "launches_timed": len(dom_recs), "traffic": None}
+
+    # ---- per-kind split of one step: time in tensor layers vs non-tensor layers (Eq. (1))
+    def split(rs):
+        conv = sum(r[6] for r in rs if r[0].startswith("conv") or r[0] == "fc")
+        other = sum(r[6] for r in rs if not (r[0].startswith("conv") or r[0] == "fc"))
+        fl = sum(conv_flops(r) for r in rs if r[0].startswith("conv"))
+        return conv, other, fl
+    co, oo, fo = split(recs)
+    cs, os_, fs = split(recs_slim)
+    nontensor_bytes = sum(2.0 * r[5] * esz for r in recs if not r[0].startswith("conv"))
+
+    out = {
+        "metric": "images/sec fwd (orig vs slim GoogLeNet), conv MFMA util %, non-tensor HBM GB/s",
+        "value": round(batch / (ms_per_step * 1e-3), 1),
+        "unit": "images/s (one original-form + one slim-form forward per image)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.config], "batch": batch,
+                   "original": "layer-by-layer (separate ReLU / pool / LRN / concat kernels)",
+                   "slim": "slimmed structure, ReLU and concat fused into the conv stores"},
+        "original_ms": {"best": round(form_ms["original"][0], 4), "median": round(form_ms["original"][1], 4)},
+        "slim_ms": {"best": round(form_ms["slim"][0], 4), "median": round(form_ms["slim"][1], 4)},
+        "original_images_per_s": round(batch / (form_ms["original"][0] * 1e-3), 1),
+        "slim_images_per_s": round(batch / (form_ms["slim"][0] * 1e-3), 1),
+        "slim_speedup": round(form_ms["original"][0] / form_ms["slim"][0], 3),
+        "kernel_split_ms": {"original_tensor": round(co, 4), "original_non_tensor": round(oo, 4),
+                            "slim_tensor": round(cs, 4), "slim_non_tensor": round(os_, 4)},
+        "pct_latency_non_tensor_original": round(100.0 * oo / max(co + oo, 1e-9), 1),
+        "conv_mfma_util_pct": {"original": round(100.0 * fo / max(co, 1e-9) / 1e9 / MI355X_MFMA_TFLOPS[dtype], 1),
+                               "slim": round(100.0 * fs / max(cs, 1e-9) / 1e9 / MI355X_MFMA_TFLOPS[dtype], 1)},
+        "non_tensor_hbm_gbs": round(nontensor_bytes / max(oo, 1e-9) / 1e6, 1) if oo > 0 else None,
+        "roofline": roofline,
+        "paper_context": "GoogLeNet 651.4 ms -> GoogLeNet-Slim 210.6 ms on Samsung Galaxy S5 CPU; 10.17 -> 6.57 ms on "
+                         "Titan X (batch 1, Table 4/5); inception_3a 55.23 -> 21.17 ms on S5",
+    }
+
+    # ---- CPU baseline: the fp64 oracle, as it stands, on the host cores (bounded sample)
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = {1: 1, 2: 32, 3: 4}[args.config]
+        xs = x_host[:sample]
+        oracle.forward(cfg["original"][:1], forms["original"]["params_host"], xs[:1])     # builds / warms the library
+        c0 = time.perf_counter()
+        for form in ("original", "slim"):
+            oracle.forward(forms[form]["layers"], forms[form]["params_host"], xs)
+        c1 = time.perf_counter()
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            cores = os.cpu_count()
+        omp = os.environ.get("OMP_NUM_THREADS")
+        cores = min(cores, int(omp)) if omp else cores
+        out["cpu_baseline"] = {"value": round(sample / (c1 - c0), 2), "unit": out["unit"], "cores": cores, "kind": "oracle",
+                               "sample": "%d of %d images, one original + one slim forward, fp64 nested loops, %.1f s"
+                                         % (sample, batch, c1 - c0)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

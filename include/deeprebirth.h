@@ -209,6 +209,25 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
 int dr_net_set_timing(dr_net* net, int enabled);
 int dr_net_layer_times(dr_net* net, float* ms_per_layer, int n);
 
+/* ---- measurement ---------------------------------------------------------------------------------- */
+
+/* One traced kernel launch.  label: kernel family ("conv_f32", "conv_bf16", "relu", "lrn", "maxpool",
+ * "concat", "bn", "add_relu", "avgpool", "fc", "softmax").  For convolutions k, c, r, s are the
+ * filter dimensions and items = N*P*Q (the GEMM n extent); otherwise items = elements written. */
+typedef struct { char label[24]; int k, c, r, s; long long items; float ms; } dr_trace_record;
+
+/* Starts recording one HIP event pair around every kernel launch the library makes (on the stream
+ * of that launch) whose label contains label_filter (NULL or "" = all) and, for convolutions, whose
+ * k / c / r equal conv_k / conv_c / conv_r (0 = any).  At most `capacity` launches are recorded,
+ * later ones run untraced.  Per-process state, not thread safe: meant for benchmarks, which use it
+ * to time the dominant kernel inside their timed region (the measure behind the paper's per-layer
+ * tables, Table 4).  Creates events (the only entry point besides dr_net_set_timing that does). */
+int dr_trace_begin(const char* label_filter, int conv_k, int conv_c, int conv_r, int capacity);
+
+/* Stops recording, waits for the recorded events, writes up to out_capacity records (launch order)
+ * and the number written to *count, and releases the events. */
+int dr_trace_end(dr_trace_record* out, int out_capacity, int* count);
+
 /* ---- misc ------------------------------------------------------------------------------------------ */
 
 /* Message of the last error raised on the calling thread ("" if none). */

@@ -62,6 +62,11 @@ class dr_layer_desc(C.Structure):
                 ("inception", dr_inception), ("bottleneck", dr_bottleneck), ("fc_out", C.c_int)]
 
 
+class dr_trace_record(C.Structure):
+    _fields_ = [("label", C.c_char * 24), ("k", C.c_int), ("c", C.c_int), ("r", C.c_int), ("s", C.c_int),
+                ("items", C.c_longlong), ("ms", C.c_float)]
+
+
 class DeepRebirthError(RuntimeError):
     def __init__(self, code, msg):
         super().__init__("deeprebirth error %d: %s" % (code, msg))
@@ -97,6 +102,8 @@ _SIGNATURES = {
     "dr_net_fwd": ([_vp, _P(dr_tensor), _vp, _P(_vp), _P(dr_tensor), _vp, _vp, _z, _vp], _i),
     "dr_net_set_timing": ([_vp, _i], _i),
     "dr_net_layer_times": ([_vp, _P(_f), _i], _i),
+    "dr_trace_begin": ([C.c_char_p, _i, _i, _i, _i], _i),
+    "dr_trace_end": ([_P(dr_trace_record), _i, _P(_i)], _i),
     "dr_last_error": ([], C.c_char_p),
     "dr_version": ([], C.c_char_p),
 }
@@ -264,6 +271,18 @@ def inception_fwd(x, idesc, weights, biases, y, ws, stream=None):
     _check(lib().dr_inception_fwd(desc(x), _ptr(x), idesc, wp, bp, desc(y), _ptr(y), _ptr(ws),
                                   0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
     return y
+
+
+def trace_begin(label_filter="", conv_k=0, conv_c=0, conv_r=0, capacity=4096):
+    _check(lib().dr_trace_begin(label_filter.encode(), conv_k, conv_c, conv_r, capacity))
+
+
+def trace_end(capacity=4096):
+    """List of (label, k, c, r, s, items, ms) in launch order."""
+    arr = (dr_trace_record * capacity)()
+    n = C.c_int(0)
+    _check(lib().dr_trace_end(arr, capacity, C.byref(n)))
+    return [(a.label.decode(), a.k, a.c, a.r, a.s, a.items, a.ms) for a in arr[:n.value]]
 
 
 class Net:

@@ -30,6 +30,36 @@ int check_launch(const char* what)
     return DR_OK;
 }
 
+// ---- kernel tracing -------------------------------------------------------------------------------
+static struct {
+    bool active = false;
+    char filter[24] = "";
+    int k = 0, c = 0, r = 0;
+    std::vector<hipEvent_t> ev;            // 2 per slot
+    std::vector<dr_trace_record> recs;
+    size_t capacity = 0;
+} g_trace;
+
+TraceScope::TraceScope(const char* label, const ConvGeom* g, long long items, hipStream_t s) : slot(-1), st(s)
+{
+    if (!g_trace.active || g_trace.recs.size() >= g_trace.capacity) return;
+    if (g_trace.filter[0] && !strstr(label, g_trace.filter)) return;
+    if (g && ((g_trace.k && g_trace.k != g->K) || (g_trace.c && g_trace.c != g->C) || (g_trace.r && g_trace.r != g->R))) return;
+    dr_trace_record rec;
+    memset(&rec, 0, sizeof rec);
+    snprintf(rec.label, sizeof rec.label, "%s", label);
+    if (g) { rec.k = g->K; rec.c = g->C; rec.r = g->R; rec.s = g->S; }
+    rec.items = items;
+    slot = (int)g_trace.recs.size();
+    g_trace.recs.push_back(rec);
+    (void)hipEventRecord(g_trace.ev[2 * slot], st);
+}
+
+TraceScope::~TraceScope()
+{
+    if (slot >= 0) (void)hipEventRecord(g_trace.ev[2 * slot + 1], st);
+}
+
 namespace {
 
 #define DR_TRY(expr) do { const int dr_rc_ = (expr); if (dr_rc_ != DR_OK) return dr_rc_; } while (0)
@@ -94,8 +124,8 @@ int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv&
     if (yd.dtype != xd.dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
     if ((double)cd.c * cd.r * cd.s >= 2147483648.0 || (double)o.n * o.h * o.w >= 2147483648.0)
         return fail(DR_ERR_UNSUPPORTED, "%s: problem too large", who);
-    if (tensor_elems(o) == 0) return DR_OK;
-    if (o.h == 0 || o.w == 0) return DR_OK;
+    if ((size_t)o.n * cd.k * o.h * o.w == 0) return DR_OK;   // nothing to compute: pointers may be NULL
+    if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
     ConvGeom g;
     g.N = xd.n; g.C = xd.c; g.H = xd.h; g.W = xd.w;
     g.K = cd.k; g.R = cd.r; g.S = cd.s;
@@ -384,6 +414,52 @@ using namespace dr;
 extern "C" {
 
 const char* dr_last_error(void) { return g_err; }
+
+int dr_trace_begin(const char* label_filter, int conv_k, int conv_c, int conv_r, int capacity)
+{
+    const char* who = "dr_trace_begin";
+    if (g_trace.active) return fail(DR_ERR_UNSUPPORTED, "%s: a trace is already running", who);
+    if (capacity < 1 || capacity > (1 << 20)) return fail(DR_ERR_SHAPE, "%s: capacity %d", who, capacity);
+    snprintf(g_trace.filter, sizeof g_trace.filter, "%s", label_filter ? label_filter : "");
+    g_trace.k = conv_k; g_trace.c = conv_c; g_trace.r = conv_r;
+    g_trace.recs.clear();
+    g_trace.recs.reserve(capacity);
+    g_trace.ev.resize(2 * (size_t)capacity);
+    for (size_t i = 0; i < g_trace.ev.size(); ++i)
+        if (hipEventCreate(&g_trace.ev[i]) != hipSuccess) {
+            for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(g_trace.ev[j]);
+            g_trace.ev.clear();
+            return fail(DR_ERR_HIP, "%s: hipEventCreate failed", who);
+        }
+    g_trace.capacity = capacity;
+    g_trace.active = true;
+    return DR_OK;
+}
+
+int dr_trace_end(dr_trace_record* out, int out_capacity, int* count)
+{
+    const char* who = "dr_trace_end";
+    if (!g_trace.active) return fail(DR_ERR_UNSUPPORTED, "%s: no trace is running", who);
+    g_trace.active = false;
+    int rc = DR_OK;
+    const int n = (int)g_trace.recs.size();
+    for (int i = 0; i < n && rc == DR_OK; ++i) {
+        if (hipEventSynchronize(g_trace.ev[2 * i + 1]) != hipSuccess ||
+            hipEventElapsedTime(&g_trace.recs[i].ms, g_trace.ev[2 * i], g_trace.ev[2 * i + 1]) != hipSuccess)
+            rc = fail(DR_ERR_HIP, "%s: reading event %d failed", who, i);
+    }
+    for (hipEvent_t e : g_trace.ev) (void)hipEventDestroy(e);
+    g_trace.ev.clear();
+    if (rc == DR_OK) {
+        if (!out || !count) rc = fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
+        else {
+            *count = n < out_capacity ? n : out_capacity;
+            for (int i = 0; i < *count; ++i) out[i] = g_trace.recs[i];
+        }
+    }
+    g_trace.recs.clear();
+    return rc;
+}
 const char* dr_version(void) { return "deeprebirth-gfx950 0.1"; }
 
 int dr_conv_out_size(int in, int filt, int stride, int pad)
@@ -407,7 +483,6 @@ int dr_conv2d_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const v
     DR_TRY(check_tensor(who, "xd", xd));
     DR_TRY(check_tensor(who, "yd", yd));
     DR_TRY(check_conv_desc(who, cd));
-    if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
     return conv_run(who, *xd, x, *cd, w, bias, nullptr, 0, *yd, y, y_c_offset, (hipStream_t)stream);
 }
 
@@ -419,7 +494,6 @@ int dr_slim_conv_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, int 
     DR_TRY(check_tensor(who, "yd", yd));
     DR_TRY(check_conv_desc(who, cd));
     if (pool_stride_h < 1 || pool_stride_w < 1) return fail(DR_ERR_SHAPE, "%s: pooling stride %d,%d", who, pool_stride_h, pool_stride_w);
-    if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
     dr_conv slim = *cd;
     slim.stride_h = cd->stride_h * pool_stride_h;   // stride of the slim layer = product of both strides
     slim.stride_w = cd->stride_w * pool_stride_w;
@@ -430,6 +504,7 @@ int dr_slim_conv_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, int 
 int dr_relu(const dr_tensor* d, const void* x, void* y, void* stream)
 {
     DR_TRY(check_tensor("dr_relu", "d", d));
+    if (tensor_elems(*d) == 0) return DR_OK;
     if (!x || !y) return fail(DR_ERR_NULL, "dr_relu: x or y is NULL");
     return launch_relu(d->dtype, x, y, tensor_elems(*d), (hipStream_t)stream);
 }
@@ -439,9 +514,10 @@ int dr_lrn_fwd(const dr_tensor* d, const void* x, const dr_lrn* p, void* y, void
     const char* who = "dr_lrn_fwd";
     DR_TRY(check_tensor(who, "d", d));
     if (!p) return fail(DR_ERR_NULL, "%s: parameters are NULL", who);
+    if (p->local_size < 1) return fail(DR_ERR_SHAPE, "%s: local_size %d", who, p->local_size);
+    if (tensor_elems(*d) == 0) return DR_OK;
     if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
     if (x == y) return fail(DR_ERR_UNSUPPORTED, "%s: in-place operation is not supported", who);
-    if (p->local_size < 1) return fail(DR_ERR_SHAPE, "%s: local_size %d", who, p->local_size);
     return launch_lrn(d->dtype, x, y, d->n, d->c, d->h * d->w, *p, (hipStream_t)stream);
 }
 
@@ -451,10 +527,11 @@ int dr_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const d
     DR_TRY(check_tensor(who, "xd", xd));
     DR_TRY(check_tensor(who, "yd", yd));
     DR_TRY(check_pool_desc(who, p));
-    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
     const dr_tensor o = pool_out(*xd, *p);
     if (!same_shape(o, *yd)) return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%dx%d, the layer produces %dx%dx%dx%d", who, yd->n, yd->c, yd->h, yd->w, o.n, o.c, o.h, o.w);
     if (yd->dtype != xd->dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
+    if (tensor_elems(o) == 0) return DR_OK;
+    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
     return launch_maxpool(xd->dtype, x, y, xd->n * xd->c, xd->h, xd->w, o.h, o.w, *p, (hipStream_t)stream);
 }
 
@@ -465,10 +542,11 @@ int dr_avgpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const d
     DR_TRY(check_tensor(who, "yd", yd));
     DR_TRY(check_pool_desc(who, p));
     if (p->pad_h || p->pad_w) return fail(DR_ERR_UNSUPPORTED, "%s: padding is not supported", who);
-    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
     const dr_tensor o = avgpool_out(*xd, *p);
     if (!same_shape(o, *yd)) return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%dx%d, the layer produces %dx%dx%dx%d", who, yd->n, yd->c, yd->h, yd->w, o.n, o.c, o.h, o.w);
     if (yd->dtype != xd->dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
+    if (tensor_elems(o) == 0) return DR_OK;
+    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
     return launch_avgpool(xd->dtype, x, y, xd->n * xd->c, xd->h, xd->w, o.h, o.w, *p, (hipStream_t)stream);
 }
 
@@ -498,6 +576,7 @@ int dr_bn_fwd(const dr_tensor* d, const void* x, const float* gamma, const float
 {
     const char* who = "dr_bn_fwd";
     DR_TRY(check_tensor(who, "d", d));
+    if (tensor_elems(*d) == 0) return DR_OK;
     if (!x || !y || !gamma || !beta || !mean || !var) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
     if (!(eps >= 0.f)) return fail(DR_ERR_SHAPE, "%s: eps must be >= 0", who);
     return launch_bn(d->dtype, x, y, d->n, d->c, d->h * d->w, gamma, beta, mean, var, eps, relu, (hipStream_t)stream);
@@ -506,6 +585,7 @@ int dr_bn_fwd(const dr_tensor* d, const void* x, const float* gamma, const float
 int dr_add_relu(const dr_tensor* d, const void* a, const void* b, void* y, void* stream)
 {
     DR_TRY(check_tensor("dr_add_relu", "d", d));
+    if (tensor_elems(*d) == 0) return DR_OK;
     if (!a || !b || !y) return fail(DR_ERR_NULL, "dr_add_relu: a pointer is NULL");
     return launch_add_relu(d->dtype, a, b, y, tensor_elems(*d), (hipStream_t)stream);
 }

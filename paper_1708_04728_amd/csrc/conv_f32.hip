@@ -233,6 +233,7 @@ int launch_tile(const KArgs& base, hipStream_t st)
 int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const float* bias, const float* residual,
                     float* y, hipStream_t st)
 {
+    TraceScope trace("conv_f32", &g, g.Ng, st);
     KArgs a;
     a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g;
     a.grid_m = a.grid_n = 0;

@@ -18,6 +18,15 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t tensor_elems(const dr_tensor& t) { return (size_t)t.n * t.c * t.h * t.w; }
 inline size_t tensor_bytes(const dr_tensor& t) { return tensor_elems(t) * elem_size(t.dtype); }
 
+struct ConvGeom;
+// Brackets one kernel launch with an event pair when tracing is on (see dr_trace_begin).
+struct TraceScope {
+    TraceScope(const char* label, const ConvGeom* g, long long items, hipStream_t st);
+    ~TraceScope();
+    int slot;
+    hipStream_t st;
+};
+
 // Geometry of one convolution launch, filled by the host after validation.
 struct ConvGeom {
     int N, C, H, W;      // input

@@ -392,47 +392,55 @@ __global__ __launch_bounds__(256) void softmax_kernel(const T* __restrict__ x, f
 
 int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st)
 {
+    TraceScope trace("relu", nullptr, (long long)(count), st);
     return DR_BY_DTYPE(dtype, (relu_launch<float, false>(x, nullptr, y, count, st)),
                        (relu_launch<uint16_t, false>(x, nullptr, y, count, st)));
 }
 
 int launch_add_relu(int dtype, const void* a, const void* b, void* y, size_t count, hipStream_t st)
 {
+    TraceScope trace("add_relu", nullptr, (long long)(count), st);
     return DR_BY_DTYPE(dtype, (relu_launch<float, true>(a, b, y, count, st)), (relu_launch<uint16_t, true>(a, b, y, count, st)));
 }
 
 int launch_lrn(int dtype, const void* x, void* y, int N, int C, int HW, const dr_lrn& p, hipStream_t st)
 {
+    TraceScope trace("lrn", nullptr, (long long)((size_t)N * C * HW), st);
     if ((size_t)N * C * HW == 0) return DR_OK;
     return DR_BY_DTYPE(dtype, lrn_launch<float>(x, y, N, C, HW, p, st), lrn_launch<uint16_t>(x, y, N, C, HW, p, st));
 }
 
 int launch_maxpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p, hipStream_t st)
 {
+    TraceScope trace("maxpool", nullptr, (long long)((size_t)NC * P * Q), st);
     return DR_BY_DTYPE(dtype, (pool_launch<float, false>(x, y, NC, H, W, P, Q, p, st)),
                        (pool_launch<uint16_t, false>(x, y, NC, H, W, P, Q, p, st)));
 }
 
 int launch_avgpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p, hipStream_t st)
 {
+    TraceScope trace("avgpool", nullptr, (long long)((size_t)NC * P * Q), st);
     return DR_BY_DTYPE(dtype, (pool_launch<float, true>(x, y, NC, H, W, P, Q, p, st)),
                        (pool_launch<uint16_t, true>(x, y, NC, H, W, P, Q, p, st)));
 }
 
 int launch_concat(int dtype, int nb, const ConcatSeg* segs, void* y, int N, int Cy, int HW, hipStream_t st)
 {
+    TraceScope trace("concat", nullptr, (long long)((size_t)N * Cy * HW), st);
     return DR_BY_DTYPE(dtype, concat_launch<float>(nb, segs, y, N, Cy, HW, st), concat_launch<uint16_t>(nb, segs, y, N, Cy, HW, st));
 }
 
 int launch_bn(int dtype, const void* x, void* y, int N, int C, int HW, const float* gamma, const float* beta,
               const float* mean, const float* var, float eps, int relu, hipStream_t st)
 {
+    TraceScope trace("bn", nullptr, (long long)((size_t)N * C * HW), st);
     return DR_BY_DTYPE(dtype, bn_launch<float>(x, y, N, C, HW, gamma, beta, mean, var, eps, relu, st),
                        bn_launch<uint16_t>(x, y, N, C, HW, gamma, beta, mean, var, eps, relu, st));
 }
 
 int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* y, int N, int I, int O, hipStream_t st)
 {
+    TraceScope trace("fc", nullptr, (long long)((size_t)N * O), st);
     if (N == 0 || O == 0) return DR_OK;
     const dim3 grid((unsigned)O, (unsigned)(N < 8 ? N : 8));
     if (dtype == DR_BF16)
@@ -444,6 +452,7 @@ int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* 
 
 int launch_softmax(int dtype, const void* x, float* y, int N, int O, hipStream_t st)
 {
+    TraceScope trace("softmax", nullptr, (long long)((size_t)N * O), st);
     if (N == 0 || O == 0) return DR_OK;
     if (dtype == DR_BF16) hipLaunchKernelGGL((softmax_kernel<uint16_t>), dim3(N), dim3(256), 0, st, (const uint16_t*)x, y, O);
     else hipLaunchKernelGGL((softmax_kernel<float>), dim3(N), dim3(256), 0, st, (const float*)x, y, O);
