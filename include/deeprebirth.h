@@ -43,9 +43,15 @@ typedef enum { DR_F32 = 0, DR_BF16 = 1 } dr_dtype;
 /* Feature map X^i / Y (Sec. 3.1): batch n of c channels of h x w, NCHW. */
 typedef struct { int n, c, h, w; int dtype; } dr_tensor;
 
+/* Filter tensor orders.  DR_KCRS is the order the filters are defined in (output channel, input
+ * channel, row, column).  DR_KRSC (input channel innermost) is the order the fast kernels read:
+ * dr_pack_filters produces it once, offline, like any other model preparation step. */
+typedef enum { DR_KCRS = 0, DR_KRSC = 1 } dr_filter_layout;
+
 /* Convolution layer f_conv(W, b) (Sec. 3.1 Eq. (3), Eq. (7)): k filters over c channels, r x s taps.
- * relu != 0 fuses max(.,0) into the store. */
-typedef struct { int k, c, r, s, stride_h, stride_w, pad_h, pad_w, relu; } dr_conv;
+ * relu != 0 fuses max(.,0) into the store.  filter_layout says how the w passed with this
+ * descriptor is ordered; DR_KRSC requires c to be a multiple of 16. */
+typedef struct { int k, c, r, s, stride_h, stride_w, pad_h, pad_w, relu, filter_layout; } dr_conv;
 
 /* LRN layer f_LRN (Sec. 3.1 Eq. (3)): across-channel window of local_size channels. */
 typedef struct { int local_size; float alpha, beta, k; } dr_lrn;
@@ -70,9 +76,15 @@ int dr_pool_out_size(int in, int win, int stride, int pad);
  * cd->relu.  Writes channels [y_c_offset, y_c_offset + cd->k) of y, which has yd->c >= that many
  * channels (other channels untouched): this is how a branch writes its part of a concatenated
  * tensor.  bias may be NULL (zero).  xd->c == cd->c, yd->n == xd->n, yd->h/w == dr_conv_out_size.
- * x, w, y share one dtype.  Uses no workspace. */
+ * x, w, y share one dtype; w is ordered as cd->filter_layout says.  x and w must each be smaller
+ * than 2 GiB.  Uses no workspace. */
 int dr_conv2d_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
                   const dr_tensor* yd, void* y, int y_c_offset, void* stream);
+
+/* Reorders a filter tensor from KCRS to KRSC on the device: w_krsc[j][r][s][c] = w_kcrs[j][c][r][s]
+ * (cd->k, c, r, s give the shape; dtype DR_F32 or DR_BF16; the two buffers must not overlap).
+ * Returns DR_ERR_UNSUPPORTED when cd->c is not a multiple of 16: such filters stay in KCRS. */
+int dr_pack_filters(const dr_conv* cd, int dtype, const void* w_kcrs, void* w_krsc, void* stream);
 
 /* Slim layer of streamline slimming (Sec. 3.1 "Pooling Layer" / "Non-Pooling Layer"): the
  * convolution cd with its stride multiplied by the absorbed pooling layer's stride, LRN/BatchNorm
@@ -168,7 +180,7 @@ typedef enum {
  * (+ReLU after the first two), shortcut = identity or (project != 0) a 1x1 convolution + BatchNorm;
  * output = ReLU(sum).  folded != 0 is the slim form: no BatchNorm layers, the convolutions carry
  * folded weights (dr_fold_bn), ReLU and the residual sum run in the convolutions' stores. */
-typedef struct { int mid, out, project, folded; float eps; } dr_bottleneck;
+typedef struct { int mid, out, project, folded; float eps; int filter_layout; /* of all its convolutions */ } dr_bottleneck;
 
 typedef struct {
     int kind;

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdeeprebirth.so")
 DR_OK = 0
 DR_ERR_NULL, DR_ERR_SHAPE, DR_ERR_UNSUPPORTED, DR_ERR_WORKSPACE, DR_ERR_HIP = 1, 2, 3, 4, 5
 DR_F32, DR_BF16 = 0, 1
+DR_KCRS, DR_KRSC = 0, 1
 DR_MAX_BRANCHES, DR_MAX_STEPS = 8, 4
 DR_STEP_CONV, DR_STEP_MAXPOOL = 0, 1
 DR_FUSE_RELU, DR_FUSE_CONCAT, DR_FUSE_STACK = 1, 2, 4
@@ -30,7 +31,8 @@ class dr_tensor(C.Structure):
 
 
 class dr_conv(C.Structure):
-    _fields_ = [(f, C.c_int) for f in ("k", "c", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w", "relu")]
+    _fields_ = [(f, C.c_int) for f in ("k", "c", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w", "relu",
+                                       "filter_layout")]
 
 
 class dr_lrn(C.Structure):
@@ -54,7 +56,8 @@ class dr_inception(C.Structure):
 
 
 class dr_bottleneck(C.Structure):
-    _fields_ = [("mid", C.c_int), ("out", C.c_int), ("project", C.c_int), ("folded", C.c_int), ("eps", C.c_float)]
+    _fields_ = [("mid", C.c_int), ("out", C.c_int), ("project", C.c_int), ("folded", C.c_int), ("eps", C.c_float),
+                ("filter_layout", C.c_int)]
 
 
 class dr_layer_desc(C.Structure):
@@ -81,6 +84,7 @@ _SIGNATURES = {
     "dr_conv_out_size": ([_i, _i, _i, _i], _i),
     "dr_pool_out_size": ([_i, _i, _i, _i], _i),
     "dr_conv2d_fwd": ([_P(dr_tensor), _vp, _P(dr_conv), _vp, _vp, _P(dr_tensor), _vp, _i, _vp], _i),
+    "dr_pack_filters": ([_P(dr_conv), _i, _vp, _vp, _vp], _i),
     "dr_slim_conv_fwd": ([_P(dr_tensor), _vp, _P(dr_conv), _i, _i, _vp, _vp, _P(dr_tensor), _vp, _i, _vp], _i),
     "dr_relu": ([_P(dr_tensor), _vp, _vp, _vp], _i),
     "dr_lrn_fwd": ([_P(dr_tensor), _vp, _P(dr_lrn), _vp, _vp], _i),
@@ -159,11 +163,16 @@ def _stream(stream=None):
     return C.c_void_p(s.cuda_stream)
 
 
-def conv_desc(k, c, r, s=None, stride=1, pad=0, relu=False):
+def conv_desc(k, c, r, s=None, stride=1, pad=0, relu=False, layout=DR_KCRS):
     s = r if s is None else s
     sh, sw = (stride, stride) if isinstance(stride, int) else stride
     ph, pw = (pad, pad) if isinstance(pad, int) else pad
-    return dr_conv(k, c, r, s, sh, sw, ph, pw, int(relu))
+    return dr_conv(k, c, r, s, sh, sw, ph, pw, int(relu), layout)
+
+
+def can_pack(c):
+    """Filters over c input channels have a KRSC form the fast kernels accept."""
+    return c % 16 == 0
 
 
 def pool_desc(k, stride, pad=0):
@@ -183,6 +192,14 @@ def conv2d_fwd(x, cd, w, bias, y, y_c_offset=0, stream=None):
     xd, yd = desc(x), desc(y)
     _check(lib().dr_conv2d_fwd(xd, _ptr(x), cd, _ptr(w), _ptr(bias), yd, _ptr(y), y_c_offset, _stream(stream)))
     return y
+
+
+def pack_filters(w, stream=None):
+    """KCRS device tensor -> new KRSC device tensor (same dtype, shape (k, r, s, c))."""
+    k, c, r, s = w.shape
+    out = torch.empty((k, r, s, c), dtype=w.dtype, device=w.device)
+    _check(lib().dr_pack_filters(conv_desc(k, c, r, s), _dtype_code(w), _ptr(w), _ptr(out), _stream(stream)))
+    return out
 
 
 def slim_conv_fwd(x, cd, pool_stride, w, bias, y, y_c_offset=0, stream=None):

@@ -81,6 +81,10 @@ int check_conv_desc(const char* who, const dr_conv* c)
     if (c->k < 1 || c->c < 1 || c->r < 1 || c->s < 1 || c->stride_h < 1 || c->stride_w < 1 || c->pad_h < 0 || c->pad_w < 0)
         return fail(DR_ERR_SHAPE, "%s: bad convolution k=%d c=%d r=%d s=%d stride=%d,%d pad=%d,%d", who, c->k, c->c, c->r, c->s,
                     c->stride_h, c->stride_w, c->pad_h, c->pad_w);
+    if (c->filter_layout != DR_KCRS && c->filter_layout != DR_KRSC)
+        return fail(DR_ERR_UNSUPPORTED, "%s: unknown filter layout %d", who, c->filter_layout);
+    if (c->filter_layout == DR_KRSC && c->c % 16 != 0)
+        return fail(DR_ERR_UNSUPPORTED, "%s: KRSC filters need a channel count that is a multiple of 16 (got %d)", who, c->c);
     return DR_OK;
 }
 
@@ -136,6 +140,7 @@ int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv&
     g.y_ctot = yd.c; g.y_coff = y_c_offset;
     g.relu = cd.relu != 0;
     g.res_ctot = residual ? res_ctot : 0;
+    g.w_krsc = cd.filter_layout == DR_KRSC;
     if (xd.dtype == DR_F32)
         return launch_conv_f32(g, (const float*)x, (const float*)w, bias, (const float*)residual, (float*)y, st);
     return launch_conv_bf16(g, (const uint16_t*)x, (const uint16_t*)w, bias, (const uint16_t*)residual, (uint16_t*)y, st);
@@ -273,7 +278,7 @@ int bottleneck_run(const dr_tensor& xd, const void* x, const dr_bottleneck& bd, 
     const char* who = "dr_net_fwd(bottleneck)";
     const bool run = !ar.measure;
     const int per = bd.folded ? 2 : 6;   // pointers per conv(+bn) group
-    auto conv_of = [&](int k, int c, int r, int pad, int relu) { return dr_conv{k, c, r, r, 1, 1, pad, pad, relu}; };
+    auto conv_of = [&](int k, int c, int r, int pad, int relu) { return dr_conv{k, c, r, r, 1, 1, pad, pad, relu, bd.filter_layout}; };
     const dr_conv ca = conv_of(bd.mid, xd.c, 1, 0, bd.folded), cb = conv_of(bd.mid, bd.mid, 3, 1, bd.folded),
                   cc = conv_of(bd.out, bd.mid, 1, 0, bd.folded), cp = conv_of(bd.out, xd.c, 1, 0, 0);
     const dr_tensor ta = conv_out(xd, ca), tb = conv_out(ta, cb), tc = conv_out(tb, cc);
@@ -484,6 +489,18 @@ int dr_conv2d_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const v
     DR_TRY(check_tensor(who, "yd", yd));
     DR_TRY(check_conv_desc(who, cd));
     return conv_run(who, *xd, x, *cd, w, bias, nullptr, 0, *yd, y, y_c_offset, (hipStream_t)stream);
+}
+
+int dr_pack_filters(const dr_conv* cd, int dtype, const void* w_kcrs, void* w_krsc, void* stream)
+{
+    const char* who = "dr_pack_filters";
+    if (!cd) return fail(DR_ERR_NULL, "%s: descriptor is NULL", who);
+    if (cd->k < 1 || cd->c < 1 || cd->r < 1 || cd->s < 1) return fail(DR_ERR_SHAPE, "%s: bad filter shape", who);
+    if (dtype != DR_F32 && dtype != DR_BF16) return fail(DR_ERR_UNSUPPORTED, "%s: unknown dtype %d", who, dtype);
+    if (cd->c % 16 != 0) return fail(DR_ERR_UNSUPPORTED, "%s: channel count %d is not a multiple of 16", who, cd->c);
+    if (!w_kcrs || !w_krsc) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
+    if ((double)cd->k * cd->c * cd->r * cd->s >= 2147483648.0) return fail(DR_ERR_UNSUPPORTED, "%s: tensor too large", who);
+    return launch_pack_filters(dtype, w_kcrs, w_krsc, cd->k, cd->c, cd->r * cd->s, (hipStream_t)stream);
 }
 
 int dr_slim_conv_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, int pool_stride_h, int pool_stride_w,

@@ -4,18 +4,30 @@
 //   D[m][n] = sum_k A[m][k] * B[k][n]     m = output channel        (M  = K filters)
 //                                         n = (image, p, q)         (Ng = N*P*Q)
 //                                         k = (c, r, s)             (Kg = C*R*S)
-//   A = the KCRS weight tensor viewed as an M x Kg row-major matrix (no copy),
+//   A = the KCRS weight tensor viewed as an M x Kg matrix (no copy),
 //   B = the im2col matrix, never materialised: each element is gathered from NCHW x on the fly.
 //
-// A workgroup of 256 threads (4 wave64) owns a BM x BN tile of D and walks Kg in slices of
-// BK = 16.  Both operand slices are staged in LDS with the GEMM-k index contiguous per row
-// (rows padded to 20 floats so that 128-bit LDS accesses of consecutive rows fall in distinct
-// banks).  v_mfma_f32_32x32x2_f32 consumes two k per instruction, one from lanes 0-31 and one
-// from lanes 32-63; the kernel gives lane half g the slice's k in [8g, 8g+8) so that every lane
-// fetches its eight A (or B) values of a slice with two 128-bit LDS reads.  Global loads for slice
-// i+1 are issued before the MFMAs of slice i (register prefetch, two LDS buffers, one barrier per
-// slice).  With lanes running along n, both the gather from x and the store to NCHW y are
-// coalesced.  Bias, the optional residual sum and ReLU are applied in the store.
+// A workgroup of 256 threads (4 wave64) owns a BM x BN tile of D and walks Kg in slices of BK.
+// Both operand slices are staged in LDS with the slice's k index contiguous per row (rows padded by
+// 4 floats so that 128-bit LDS accesses of consecutive rows fall in distinct banks).
+// v_mfma_f32_32x32x2_f32 consumes two k per instruction, one from lanes 0-31 and one from lanes
+// 32-63; the kernel gives lane half g the slice's k in [g*BK/2, (g+1)*BK/2), so every lane fetches
+// its A (or B) values of a slice with BK/8 128-bit LDS reads.  Global loads run PF slices ahead of
+// the MFMAs in registers (PF register sets), LDS is double buffered, one barrier per slice.  With
+// lanes running along n, both the gather from x and the store to NCHW y are coalesced.  Bias, the
+// optional residual sum and ReLU are applied in the store.
+//
+// On this GPU fp32 MFMA and ordinary vector-ALU instructions do not overlap (measured: their times
+// add), so every address computation in the loop costs matrix throughput.  Two slice orders exist:
+//   CF = true  ("channel fastest": filters given in KRSC order, C % BK == 0): a slice is BK
+//        consecutive channels of one filter tap (r, s).  All per-lane offsets are loop invariants;
+//        the slice only moves a wave-uniform scalar offset, which rides in the buffer instructions'
+//        scalar operand, and the padding test is redone once per tap.  Almost no vector-ALU work
+//        per slice, and the filter rows are read with 16-byte loads.
+//   CF = false (filters in KCRS order, any shape): k runs in KCRS order and every gathered element
+//        decodes (c, r, s).
+#include <type_traits>
+
 #include "dr_internal.h"
 
 namespace dr {
@@ -24,8 +36,6 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 16;        // k per LDS slice
-constexpr int LDT = BK + 4;   // padded row length (floats) of both LDS tiles
 constexpr int NT = 256;       // threads per workgroup
 
 struct KArgs {
@@ -36,20 +46,47 @@ struct KArgs {
     float* y;
     ConvGeom g;
     int grid_m, grid_n;
+    int x_bytes, w_bytes;   // sizes of the x and w tensors (both < 2 GiB, checked by the launcher)
+    int w_krsc;             // filters are in KRSC order (else KCRS)
 };
 
-// FR, FS: compile-time filter size (0 = taken from the geometry at run time).
-template <int BM, int BN, int WGM, int WGN, int FR, int FS>
+template <int V> using IC = std::integral_constant<int, V>;
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// global load (its fence covers all address spaces), which would serialise the register prefetch
+// with the MFMAs; global memory needs no ordering inside this kernel.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+__device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, int voff, int soff)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+
+// BM x BN: workgroup tile; WGM x WGN: wave grid (4 waves); BK: k per LDS slice; PF: prefetch distance
+// in slices; CF: slice order (see above); FR, FS: compile-time filter size for CF = false (0 = taken
+// from the geometry at run time).
+template <int BM, int BN, int WGM, int WGN, int BK, int PF, bool CF, int FR, int FS>
 __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
 {
     constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;     // 32x32 MFMA tiles per wave
+    constexpr int LDT = BK + 4;                   // padded LDS row (floats)
+    constexpr int KQ = BK / 4;                    // float4 groups per row
+    constexpr int HK = BK / 2;                    // k per lane half
     static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1, "bad tiling");
-    constexpr int A_F4 = BM * (BK / 4);           // float4 groups in an A slice
-    constexpr int B_F4 = BN * (BK / 4);
+    static_assert(BK == 16 || BK == 32, "BK");
+    static_assert(PF == 1 || PF == 2, "PF");
+    constexpr int A_F4 = BM * KQ;                 // float4 groups in an A slice
+    constexpr int B_F4 = BN * KQ;
     constexpr int A_PER = (A_F4 + NT - 1) / NT;
     constexpr int B_PER = B_F4 / NT;
-    static_assert(B_F4 % NT == 0, "BN must be a multiple of 64");
+    static_assert(B_F4 % NT == 0, "BN * BK must be a multiple of 1024");
+    static_assert(BN <= NT && NT % BN == 0, "one n per thread");
 
     __shared__ __attribute__((aligned(16))) float As[2][BM * LDT];
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDT];
@@ -73,74 +110,120 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
 
     const int HW = g.H * g.W, PQ = g.P * g.Q;
 
+    // Global reads go through buffer descriptors: a lane whose element lies outside the tensor (zero
+    // padding, ragged M / n / k tails) gets its offset moved beyond num_records and the hardware
+    // returns 0 for it without touching memory, so the gather needs no branches.
+    constexpr int OOB = (int)0x80000000;
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, a.w_bytes, 0x00020000);
+
     // ---- per-thread gather state for B: one fixed n, B_PER groups of 4 consecutive k per slice
+    constexpr int BKQ_STEP = NT / BN;             // k-groups covered by one pass of the workgroup
     const int bn = tid % BN;
-    const int bkq0 = tid / BN;                   // first k-group; next ones at +NT/BN
-    constexpr int BKQ_STEP = NT / BN;
+    const int bkq0 = tid / BN;
     const int ng = n0 + bn;
     const bool n_ok = ng < g.Ng;
-    int ih0 = 0, iw0 = 0;
-    const float* xb = a.x;
+    int ih0 = -(1 << 30), iw0 = -(1 << 30);      // fails every bounds test when n is out of range
+    int xoff0 = 0;                                // element offset of x[img][0][ih0][iw0]
     if (n_ok) {
         const int img = ng / PQ, pix = ng - img * PQ;
         const int p = pix / g.Q, q = pix - p * g.Q;
         ih0 = p * g.sh - g.ph;
         iw0 = q * g.sw - g.pw;
-        xb = a.x + (size_t)img * g.C * HW;
+        xoff0 = img * g.C * HW + ih0 * g.W + iw0;
     }
+    // ---- per-thread state for A: rows f / KQ of the slice, byte offset of the row start
     const bool vecA = (g.Kg & 3) == 0;
-
-    f32x4 ra[A_PER], rb[B_PER];
-
-    auto load_slice = [&](int k0) {
+    int arow[A_PER];
 #pragma unroll
-        for (int i = 0; i < A_PER; ++i) {
-            const int f = tid + i * NT;
-            const int m = f >> 2, kq = f & 3;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            const int gm = m0 + m, gk = k0 + kq * 4;
-            if ((A_F4 % NT == 0 || f < A_F4) && gm < g.K) {
-                const float* src = a.w + (size_t)gm * g.Kg + gk;
+    for (int i = 0; i < A_PER; ++i) {
+        const int f = tid + i * NT;
+        const int gm = m0 + f / KQ;
+        arow[i] = ((A_F4 % NT == 0 || f < A_F4) && gm < g.K) ? gm * g.Kg * 4 : OOB;
+    }
+
+    f32x4 ra[PF][A_PER], rb[PF][B_PER];
+
+    // ---- CF = true: loader state.  Slices are visited tap by tap, BK channels at a time.
+    int ld_c0 = 0, ld_r = 0, ld_s = 0;            // wave-uniform position of the next slice to load
+    int vb[CF ? B_PER : 1][4];                    // per-lane byte offsets of the 4 channels of a group
+    int va[CF ? A_PER : 1];                       // per-lane byte offset of a float4 of the filter row
+    if constexpr (CF) {
+#pragma unroll
+        for (int i = 0; i < A_PER; ++i) va[i] = arow[i] + ((tid + i * NT) % KQ) * 16;
+    }
+    auto tap_offsets = [&]() {   // padding test of tap (ld_r, ld_s) for this lane's pixel
+        const bool ok = (unsigned)(ih0 + ld_r) < (unsigned)g.H && (unsigned)(iw0 + ld_s) < (unsigned)g.W;
+        const int base = ok ? (xoff0 + ld_r * g.W + ld_s) * 4 : OOB;
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) vb[CF ? i : 0][j] = base + ((bkq0 + i * BKQ_STEP) * 4 + j) * HW * 4;
+    };
+
+    auto load_slice = [&](int it, auto set_c) {
+        constexpr int SET = decltype(set_c)::value;
+        if constexpr (CF) {
+            if (ld_c0 == 0) tap_offsets();
+            const int sa = ((ld_r * S + ld_s) * g.C + ld_c0) * 4;   // scalar parts of the addresses
+            const int sb = ld_c0 * HW * 4;
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i)
+                ra[SET][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, va[i], sa, 0));
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                f32x4 v;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = buf_load(rx, vb[i][j], sb);
+                rb[SET][i] = v;
+            }
+            ld_c0 += BK;
+            if (ld_c0 == g.C) { ld_c0 = 0; if (++ld_s == S) { ld_s = 0; ++ld_r; } }
+        } else {
+            const int k0 = it * BK;
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i) {
+                const int gk = k0 + ((tid + i * NT) % KQ) * 4;
+                const int off = arow[i] + gk * 4;
                 if (vecA) {
-                    if (gk < g.Kg) v = *reinterpret_cast<const f32x4*>(src);
+                    ra[SET][i] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rw, gk < g.Kg ? off : OOB, 0, 0));
                 } else {
-                    if (gk + 0 < g.Kg) v.x = src[0];
-                    if (gk + 1 < g.Kg) v.y = src[1];
-                    if (gk + 2 < g.Kg) v.z = src[2];
-                    if (gk + 3 < g.Kg) v.w = src[3];
+                    f32x4 v;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = buf_load(rw, gk + j < g.Kg ? off + 4 * j : OOB, 0);
+                    ra[SET][i] = v;
                 }
             }
-            ra[i] = v;
-        }
 #pragma unroll
-        for (int i = 0; i < B_PER; ++i) {
-            const int gk = k0 + (bkq0 + i * BKQ_STEP) * 4;
-            int c = gk / RS;
-            int rs = gk - c * RS;
-            int r = rs / S;
-            int s = rs - r * S;
-            float v[4];
+            for (int i = 0; i < B_PER; ++i) {
+                const int gk = k0 + (bkq0 + i * BKQ_STEP) * 4;
+                int c = gk / RS;
+                int rs = gk - c * RS;
+                int r = rs / S;
+                int s = rs - r * S;
+                f32x4 v;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int ih = ih0 + r, iw = iw0 + s;
-                const bool ok = n_ok && (gk + j < g.Kg) && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
-                v[j] = ok ? xb[(size_t)c * HW + ih * g.W + iw] : 0.f;
-                if (++s == S) { s = 0; if (++r == R) { r = 0; ++c; } }
+                for (int j = 0; j < 4; ++j) {
+                    const bool ok = (gk + j < g.Kg) && (unsigned)(ih0 + r) < (unsigned)g.H && (unsigned)(iw0 + s) < (unsigned)g.W;
+                    v[j] = buf_load(rx, ok ? (xoff0 + c * HW + r * g.W + s) * 4 : OOB, 0);
+                    if (++s == S) { s = 0; if (++r == R) { r = 0; ++c; } }
+                }
+                rb[SET][i] = v;
             }
-            rb[i] = f32x4{v[0], v[1], v[2], v[3]};
         }
     };
 
-    auto store_slice = [&](int buf) {
+    auto store_slice = [&](int buf, auto set_c) {
+        constexpr int SET = decltype(set_c)::value;
 #pragma unroll
         for (int i = 0; i < A_PER; ++i) {
             const int f = tid + i * NT;
             if (A_F4 % NT == 0 || f < A_F4)
-                *reinterpret_cast<f32x4*>(&As[buf][(f >> 2) * LDT + (f & 3) * 4]) = ra[i];
+                *reinterpret_cast<f32x4*>(&As[buf][(f / KQ) * LDT + (f % KQ) * 4]) = ra[SET][i];
         }
 #pragma unroll
         for (int i = 0; i < B_PER; ++i)
-            *reinterpret_cast<f32x4*>(&Bs[buf][bn * LDT + (bkq0 + i * BKQ_STEP) * 4]) = rb[i];
+            *reinterpret_cast<f32x4*>(&Bs[buf][bn * LDT + (bkq0 + i * BKQ_STEP) * 4]) = rb[SET][i];
     };
 
     f32x16 acc[TM][TN];
@@ -151,39 +234,49 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nslices = (g.Kg + BK - 1) / BK;
-    load_slice(0);
-    store_slice(0);
-    __syncthreads();
+    const int nslices = CF ? RS * (g.C / BK) : (g.Kg + BK - 1) / BK;
 
-    for (int it = 0; it < nslices; ++it) {
+    // One slice: MFMAs on LDS buffer it&1; then register set SET (slice it+1, loaded PF slices ago)
+    // moves to the other LDS buffer and is refilled with slice it+1+PF.
+    auto slice_step = [&](int it, auto set_c) {
         const int buf = it & 1;
-        if (it + 1 < nslices) load_slice((it + 1) * BK);
-
-        f32x4 fa[TM][2], fb[TN][2];
+        f32x4 fa[TM][HK / 4], fb[TN][HK / 4];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const float* p = &As[buf][(wm * WM + i * 32 + l32) * LDT + half * 8];
-            fa[i][0] = *reinterpret_cast<const f32x4*>(p);
-            fa[i][1] = *reinterpret_cast<const f32x4*>(p + 4);
+            const float* p = &As[buf][(wm * WM + i * 32 + l32) * LDT + half * HK];
+#pragma unroll
+            for (int h = 0; h < HK / 4; ++h) fa[i][h] = *reinterpret_cast<const f32x4*>(p + 4 * h);
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const float* p = &Bs[buf][(wn * WN + j * 32 + l32) * LDT + half * 8];
-            fb[j][0] = *reinterpret_cast<const f32x4*>(p);
-            fb[j][1] = *reinterpret_cast<const f32x4*>(p + 4);
+            const float* p = &Bs[buf][(wn * WN + j * 32 + l32) * LDT + half * HK];
+#pragma unroll
+            for (int h = 0; h < HK / 4; ++h) fb[j][h] = *reinterpret_cast<const f32x4*>(p + 4 * h);
         }
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
+        for (int kk = 0; kk < HK; ++kk)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][kk >> 2][kk & 3], fb[j][kk >> 2][kk & 3],
                                                                      acc[i][j], 0, 0, 0);
+        if (it + 1 < nslices) {
+            store_slice(buf ^ 1, set_c);
+            if (it + 1 + PF < nslices) load_slice(it + 1 + PF, set_c);
+        }
+        lds_barrier();
+    };
 
-        if (it + 1 < nslices) store_slice(buf ^ 1);
-        __syncthreads();
+    load_slice(0, IC<0>{});
+    store_slice(0, IC<0>{});
+    if (1 < nslices) load_slice(1, IC<0>{});
+    if (PF == 2 && 2 < nslices) load_slice(2, IC<PF - 1>{});
+    lds_barrier();
+
+    for (int it = 0; it < nslices; it += PF) {
+        slice_step(it, IC<0>{});
+        if (PF == 2 && it + 1 < nslices) slice_step(it + 1, IC<PF - 1>{});
     }
 
     // ---- store: accumulator register v of a 32x32 tile holds row 8*(v/4) + 4*half + v%4, column l32
@@ -209,7 +302,7 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
     }
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int BK, int PF>
 int launch_tile(const KArgs& base, hipStream_t st)
 {
     KArgs a = base;
@@ -217,13 +310,14 @@ int launch_tile(const KArgs& base, hipStream_t st)
     a.grid_n = (a.g.Ng + BN - 1) / BN;
     const dim3 grid((unsigned)(a.grid_m * a.grid_n)), block(NT);
     const int R = a.g.R, S = a.g.S;
-#define DR_LAUNCH(FR, FS) hipLaunchKernelGGL((conv_f32_kernel<BM, BN, WGM, WGN, FR, FS>), grid, block, 0, st, a)
-    if (R == 1 && S == 1) DR_LAUNCH(1, 1);
-    else if (R == 3 && S == 3) DR_LAUNCH(3, 3);
-    else if (R == 5 && S == 5) DR_LAUNCH(5, 5);
-    else if (R == 7 && S == 7) DR_LAUNCH(7, 7);
-    else if (R == 11 && S == 11) DR_LAUNCH(11, 11);
-    else DR_LAUNCH(0, 0);
+#define DR_LAUNCH(CF, FR, FS) hipLaunchKernelGGL((conv_f32_kernel<BM, BN, WGM, WGN, BK, PF, CF, FR, FS>), grid, block, 0, st, a)
+    if (a.w_krsc) DR_LAUNCH(true, 0, 0);
+    else if (R == 1 && S == 1) DR_LAUNCH(false, 1, 1);
+    else if (R == 3 && S == 3) DR_LAUNCH(false, 3, 3);
+    else if (R == 5 && S == 5) DR_LAUNCH(false, 5, 5);
+    else if (R == 7 && S == 7) DR_LAUNCH(false, 7, 7);
+    else if (R == 11 && S == 11) DR_LAUNCH(false, 11, 11);
+    else DR_LAUNCH(false, 0, 0);
 #undef DR_LAUNCH
     return check_launch("conv_f32");
 }
@@ -237,18 +331,19 @@ int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const flo
     KArgs a;
     a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g;
     a.grid_m = a.grid_n = 0;
-    // Tile choice: the tile height that pads M (the filter count) least, taller tiles on ties;
-    // narrower tiles along n when the grid would otherwise leave compute units idle.
-    int best = 128, pad_best = (g.K + 127) / 128 * 128;
-    for (int bm : {64, 32}) {
-        const int padded = (g.K + bm - 1) / bm * bm;
-        if (padded < pad_best) { best = bm; pad_best = padded; }
-    }
-    if (best == 32) return launch_tile<32, 256, 1, 4>(a, st);
-    if (best == 64) return launch_tile<64, 128, 1, 4>(a, st);
-    const long tiles128 = (long)((g.K + 127) / 128) * ((g.Ng + 127) / 128);
-    if (tiles128 < 512) return launch_tile<128, 64, 2, 2>(a, st);
-    return launch_tile<128, 128, 2, 2>(a, st);
+    const size_t xb = (size_t)g.N * g.C * g.H * g.W * 4, wb = (size_t)g.K * g.Kg * 4;
+    if (xb >= (1ull << 31) || wb >= (1ull << 31))
+        return fail(DR_ERR_UNSUPPORTED, "conv_f32: input (%zu bytes) or filter tensor (%zu bytes) is 2 GiB or larger", xb, wb);
+    a.x_bytes = (int)xb; a.w_bytes = (int)wb;
+    a.w_krsc = g.w_krsc;
+    // Tile choice (from sweeps on the inception / streamline shapes): 32-row tiles when they pad the
+    // filter count less than 64-row tiles (16, 32, 96 filters ...), else 64 x 64 tiles; both give the
+    // grid several workgroups per compute unit, which matters more here than operand reuse.  The
+    // deepest slice the channel count allows, two slices of prefetch.
+    const bool rows32 = (g.K + 31) / 32 * 32 < (g.K + 63) / 64 * 64;
+    if (g.w_krsc && g.C % 32 == 0)
+        return rows32 ? launch_tile<32, 128, 1, 4, 32, 2>(a, st) : launch_tile<64, 64, 2, 2, 32, 2>(a, st);
+    return rows32 ? launch_tile<32, 128, 1, 4, 16, 2>(a, st) : launch_tile<64, 64, 2, 2, 16, 2>(a, st);
 }
 
 }  // namespace dr

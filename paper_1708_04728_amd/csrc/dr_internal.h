@@ -38,6 +38,7 @@ struct ConvGeom {
     int y_ctot, y_coff;  // channels of the output tensor, first channel written
     int relu;            // fused max(.,0)
     int res_ctot;        // channels of the residual tensor (0 = no residual add)
+    int w_krsc;          // filters are in KRSC order (else KCRS)
 };
 
 // conv_f32.hip / conv_bf16.hip: y = conv(x, w) + bias [+ residual] [ReLU].
@@ -48,6 +49,7 @@ int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, co
                      const uint16_t* residual, uint16_t* y, hipStream_t st);
 
 // pointwise.hip
+int launch_pack_filters(int dtype, const void* w_kcrs, void* w_krsc, int K, int C, int RS, hipStream_t st);
 int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st);
 int launch_lrn(int dtype, const void* x, void* y, int N, int C, int HW, const dr_lrn& p, hipStream_t st);
 int launch_maxpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p,

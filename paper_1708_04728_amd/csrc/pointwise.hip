@@ -292,6 +292,22 @@ int concat_launch(int nb, const ConcatSeg* segs, void* y, int N, int Cy, int HW,
     return check_launch("concat");
 }
 
+// ---- filter repack KCRS -> KRSC -----------------------------------------------------------------
+// One thread per output element (lanes along c: coalesced writes; the strided reads hit the caches).
+template <typename T>
+__global__ __launch_bounds__(256) void pack_filters_kernel(const T* __restrict__ src, T* __restrict__ dst, int C, int RS,
+                                                           size_t total)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int c = (int)(i % C);
+        const size_t t = i / C;
+        const int rs = (int)(t % RS);
+        const size_t k = t / RS;
+        dst[i] = src[(k * C + c) * RS + rs];
+    }
+}
+
 // ---- BatchNorm + Scale ------------------------------------------------------------------------------
 // blockIdx.y walks the (n, c) planes, so the four per-channel parameters are wave-uniform.
 template <typename T, int V>
@@ -389,6 +405,19 @@ __global__ __launch_bounds__(256) void softmax_kernel(const T* __restrict__ x, f
 }  // namespace
 
 #define DR_BY_DTYPE(dtype, call_f32, call_bf16) ((dtype) == DR_BF16 ? (call_bf16) : (call_f32))
+
+int launch_pack_filters(int dtype, const void* w_kcrs, void* w_krsc, int K, int C, int RS, hipStream_t st)
+{
+    const size_t total = (size_t)K * C * RS;
+    TraceScope trace("pack_filters", nullptr, (long long)total, st);
+    if (dtype == DR_BF16)
+        hipLaunchKernelGGL((pack_filters_kernel<uint16_t>), dim3(blocks_for(total, 256, 4096)), dim3(256), 0, st,
+                           (const uint16_t*)w_kcrs, (uint16_t*)w_krsc, C, RS, total);
+    else
+        hipLaunchKernelGGL((pack_filters_kernel<float>), dim3(blocks_for(total, 256, 4096)), dim3(256), 0, st,
+                           (const float*)w_kcrs, (float*)w_krsc, C, RS, total);
+    return check_launch("pack_filters");
+}
 
 int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st)
 {

@@ -22,11 +22,12 @@ def to_device(a, dtype="f32", device="cuda"):
     return t.to(device)
 
 
-def conv_desc(p, c_in, relu=False):
-    return B.conv_desc(p["k"], c_in, p["r"], p["s"], p["stride"], p["pad"], relu)
+def conv_desc(p, c_in, relu=False, pack=False):
+    layout = B.DR_KRSC if (pack and B.can_pack(c_in)) else B.DR_KCRS
+    return B.conv_desc(p["k"], c_in, p["r"], p["s"], p["stride"], p["pad"], relu, layout)
 
 
-def inception_desc(p, c_in, mode=0):
+def inception_desc(p, c_in, mode=0, pack=False):
     """dr_inception from an ("inception", {...}) layer; a conv directly followed by a relu gets
     conv.relu = 1."""
     d = B.dr_inception()
@@ -39,7 +40,7 @@ def inception_desc(p, c_in, mode=0):
             step = d.branches[bi].steps[si]
             if kind == "conv":
                 relu = i + 1 < len(br) and br[i + 1][0] == "relu"
-                step.kind, step.conv = B.DR_STEP_CONV, conv_desc(q, c, relu)
+                step.kind, step.conv = B.DR_STEP_CONV, conv_desc(q, c, relu, pack)
                 c = q["k"]
                 i += 2 if relu else 1
             elif kind == "maxpool":
@@ -66,7 +67,7 @@ def _out_channels(layers, c_in):
     return c
 
 
-def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False):
+def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False, pack=False):
     """List of dr_layer_desc for a layer list.
 
     fuse_relu: a conv directly followed by a relu becomes one conv with the ReLU in its store
@@ -78,7 +79,7 @@ def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False):
         L = B.dr_layer_desc()
         if kind == "conv":
             relu = fuse_relu and i + 1 < len(layers) and layers[i + 1][0] == "relu"
-            L.kind, L.conv = B.DR_LAYER_CONV, conv_desc(p, c, relu)
+            L.kind, L.conv = B.DR_LAYER_CONV, conv_desc(p, c, relu, pack)
             c = p["k"]
             if relu:
                 i += 1
@@ -91,11 +92,12 @@ def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False):
         elif kind == "avgpool":
             L.kind, L.pool = B.DR_LAYER_AVGPOOL, B.pool_desc(p["k"], 1, 0)
         elif kind == "inception":
-            L.kind, L.inception = B.DR_LAYER_INCEPTION, inception_desc(p, c, inception_mode)
+            L.kind, L.inception = B.DR_LAYER_INCEPTION, inception_desc(p, c, inception_mode, pack)
             c = _out_channels([(kind, p)], c)
         elif kind == "bottleneck":
             L.kind = B.DR_LAYER_BOTTLENECK
-            L.bottleneck = B.dr_bottleneck(p["mid"], p["out"], int(p["project"]), int(folded), p["eps"])
+            lay = B.DR_KRSC if (pack and B.can_pack(c) and B.can_pack(p["mid"])) else B.DR_KCRS
+            L.bottleneck = B.dr_bottleneck(p["mid"], p["out"], int(p["project"]), int(folded), p["eps"], lay)
             c = p["out"]
         elif kind == "fc":
             L.kind, L.fc_out = B.DR_LAYER_FC, p["out"]
@@ -109,13 +111,17 @@ def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False):
     return out
 
 
-def flat_params(params, dtype="f32", device="cuda", folded_from=None):
+def flat_params(params, dtype="f32", device="cuda", pack=False):
     """Device tensors in the order dr_net_fwd expects: conv/fc -> w, bias; bn -> gamma, beta,
-    mean, var (all fp32 except w)."""
+    mean, var (all fp32 except w).  pack: convolution filters whose channel count allows it are
+    reordered to KRSC by the library (must match the `pack` given to the descriptor builders)."""
     out = []
     for q in params:
         if "w" in q:
-            out += [to_device(q["w"], dtype, device), to_device(q["b"], "f32", device)]
+            w = to_device(q["w"], dtype, device)
+            if pack and w.dim() == 4 and B.can_pack(w.shape[1]):
+                w = B.pack_filters(w)
+            out += [w, to_device(q["b"], "f32", device)]
         else:
             out += [to_device(q[k], "f32", device) for k in ("gamma", "beta", "mean", "var")]
     return out

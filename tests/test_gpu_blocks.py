@@ -15,13 +15,13 @@ MODES = [0, B.DR_FUSE_RELU, B.DR_FUSE_CONCAT, B.DR_FUSE_RELU | B.DR_FUSE_CONCAT,
          B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK]
 
 
-def run_inception(layer, params, x, mode, dtype="f32"):
+def run_inception(layer, params, x, mode, dtype="f32", pack=False):
     xg = G.to_device(x, dtype)
-    d = G.inception_desc(layer[1], x.shape[1], mode)
+    d = G.inception_desc(layer[1], x.shape[1], mode, pack)
     ws = torch.empty(max(B.inception_workspace_bytes(xg, d), 256), dtype=torch.uint8, device="cuda")
     c_out = G._out_channels([layer], x.shape[1])
     y = torch.full((x.shape[0], c_out, x.shape[2], x.shape[3]), float("nan"), dtype=G.torch_dtype(dtype), device="cuda")
-    flat = G.flat_params(params, dtype)
+    flat = G.flat_params(params, dtype, pack=pack)
     B.inception_fwd(xg, d, flat[0::2], flat[1::2], y, ws)
     torch.cuda.synchronize()
     return host(y)
@@ -29,12 +29,13 @@ def run_inception(layer, params, x, mode, dtype="f32"):
 
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("form", ["original", "slim"])
-def test_inception_3a(form, mode):
+@pytest.mark.parametrize("pack", [False, True])
+def test_inception_3a(form, mode, pack):
     layer = workloads.CONFIGS[2][form][0]
     params = workloads.make_params(2, form)
     x = workloads.make_input(2, 3)
     ref = oracle.forward([layer], params, x)
-    got = run_inception(layer, params, x, mode)
+    got = run_inception(layer, params, x, mode, pack=pack)
     assert rel_err(got, ref) < TOL_F32
 
 
@@ -48,16 +49,17 @@ def test_inception_3a_paper_variant_and_ragged_spatial():
         assert rel_err(run_inception(layer, params, x, mode), ref) < TOL_F32
 
 
-def run_net(layers, params, x, dtype="f32", fuse_relu=False, inception_mode=0, folded=False, timing=False):
+def run_net(layers, params, x, dtype="f32", fuse_relu=False, inception_mode=0, folded=False, timing=False, pack=True):
     xg = G.to_device(x, dtype)
-    net = B.Net(G.net_descs(layers, x.shape[1], inception_mode=inception_mode, fuse_relu=fuse_relu, folded=folded))
+    net = B.Net(G.net_descs(layers, x.shape[1], inception_mode=inception_mode, fuse_relu=fuse_relu, folded=folded,
+                            pack=pack))
     yd = net.output_desc(B.desc(xg))
     y = torch.full((yd.n, yd.c, yd.h, yd.w), float("nan"), dtype=torch.float32 if yd.dtype == B.DR_F32 else torch.bfloat16,
                    device="cuda")
     ws = torch.empty(max(net.workspace_bytes(B.desc(xg)), 256), dtype=torch.uint8, device="cuda")
     if timing:
         net.set_timing(True)
-    net.fwd(xg, G.flat_params(params, dtype), y, ws)
+    net.fwd(xg, G.flat_params(params, dtype, pack=pack), y, ws)
     torch.cuda.synchronize()
     out = host(y)
     return (out, net.layer_times()) if timing else out

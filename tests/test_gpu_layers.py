@@ -47,21 +47,31 @@ CONV_CASES = [
     (3, 5, 9, 7, 7, 3, 3, 1, 1),           # everything ragged and tiny
     (1, 7, 13, 17, 33, 2, 4, 3, 1),        # run-time filter size path, M = 33
     (1, 4, 6, 6, 150, 1, 1, 1, 0),         # M = 150: two tiles with a ragged second one
+    (2, 48, 14, 14, 40, 3, 3, 1, 1),       # C = 48: KRSC with 16-deep slices only
+    (1, 32, 9, 11, 70, 5, 5, 2, 2),        # KRSC, strided, ragged everything
 ]
 
 
 @pytest.mark.parametrize("case", CONV_CASES)
 @pytest.mark.parametrize("relu", [False, True])
-def test_conv2d_f32(case, relu):
+@pytest.mark.parametrize("layout", ["kcrs", "krsc"])
+def test_conv2d_f32(case, relu, layout):
     N, C, H, W, K, R, S, stride, pad = case
     if relu and case not in (CONV_CASES[0], CONV_CASES[4], CONV_CASES[12]):
         pytest.skip("ReLU epilogue covered on three shapes")
+    if layout == "krsc" and not B.can_pack(C):
+        pytest.skip("KRSC filters need a channel count that is a multiple of 16")
     rng = _rng(hash(case) % 2 ** 31)
     x, w = _vals(rng, (N, C, H, W), "f32"), _vals(rng, (K, C, R, S), "f32") * np.float32(np.sqrt(2.0 / (C * R * S)))
     b = (_vals(rng, (K,), "f32") * np.float32(0.1))
     ref = oracle.conv2d(x, w, b, stride, pad, relu)
     y = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
-    B.conv2d_fwd(gpu(x), B.conv_desc(K, C, R, S, stride, pad, relu), gpu(w), gpu(b), y)
+    wg = gpu(w)
+    if layout == "krsc":
+        wg = B.pack_filters(wg)
+        assert np.array_equal(host(wg), np.transpose(w, (0, 2, 3, 1)))       # the repack is a pure permutation
+    B.conv2d_fwd(gpu(x), B.conv_desc(K, C, R, S, stride, pad, relu, B.DR_KRSC if layout == "krsc" else B.DR_KCRS), wg,
+                 gpu(b), y)
     torch.cuda.synchronize()
     assert rel_err(host(y), ref) < TOL_F32
 
