@@ -5,8 +5,9 @@
  * streamline block, two tensor branches per inception module, BatchNorm folded into the conv).
  *
  * Conventions common to every entry point
- *   - Tensors: activations are dense NCHW, weights are dense KCRS (output channel, input channel,
- *     filter row, filter column), biases and per-channel vectors are dense K.  DR_F32 tensors hold
+ *   - Tensors: activations are dense, in NCHW or NHWC order (dr_tensor.layout); filters are dense
+ *     KCRS (output channel, input channel, filter row, filter column) or KRSC (dr_conv.filter_layout);
+ *     biases and per-channel vectors are dense K.  DR_F32 tensors hold
  *     IEEE binary32; DR_BF16 tensors hold bfloat16 (upper half of a binary32) and are computed with
  *     fp32 accumulation and round-to-nearest-even on store.  Biases and BatchNorm vectors are
  *     always fp32.
@@ -40,8 +41,15 @@ typedef enum {
 
 typedef enum { DR_F32 = 0, DR_BF16 = 1 } dr_dtype;
 
-/* Feature map X^i / Y (Sec. 3.1): batch n of c channels of h x w, NCHW. */
-typedef struct { int n, c, h, w; int dtype; } dr_tensor;
+/* Activation orders: DR_NCHW (channel planes) or DR_NHWC (channels last: the c values of one pixel
+ * are contiguous).  fp32 convolutions take NCHW; bf16 convolutions take NHWC, the order in which the
+ * contraction index of the matrix cores is contiguous (bf16 NCHW runs in a slow fallback kernel).
+ * The other layers take either order for both data types.  Inputs and outputs of one call share
+ * the order. */
+typedef enum { DR_NCHW = 0, DR_NHWC = 1 } dr_layout;
+
+/* Feature map X^i / Y (Sec. 3.1): batch n of c channels of h x w, in the memory order `layout`. */
+typedef struct { int n, c, h, w; int dtype; int layout; } dr_tensor;
 
 /* Filter tensor orders.  DR_KCRS is the order the filters are defined in (output channel, input
  * channel, row, column).  DR_KRSC (input channel innermost) is the order the fast kernels read:
@@ -50,7 +58,7 @@ typedef enum { DR_KCRS = 0, DR_KRSC = 1 } dr_filter_layout;
 
 /* Convolution layer f_conv(W, b) (Sec. 3.1 Eq. (3), Eq. (7)): k filters over c channels, r x s taps.
  * relu != 0 fuses max(.,0) into the store.  filter_layout says how the w passed with this
- * descriptor is ordered; DR_KRSC requires c to be a multiple of 16. */
+ * descriptor is ordered; DR_KRSC requires c to be a multiple of 16 (fp32) or 8 (bf16). */
 typedef struct { int k, c, r, s, stride_h, stride_w, pad_h, pad_w, relu, filter_layout; } dr_conv;
 
 /* LRN layer f_LRN (Sec. 3.1 Eq. (3)): across-channel window of local_size channels. */
@@ -83,7 +91,8 @@ int dr_conv2d_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const v
 
 /* Reorders a filter tensor from KCRS to KRSC on the device: w_krsc[j][r][s][c] = w_kcrs[j][c][r][s]
  * (cd->k, c, r, s give the shape; dtype DR_F32 or DR_BF16; the two buffers must not overlap).
- * Returns DR_ERR_UNSUPPORTED when cd->c is not a multiple of 16: such filters stay in KCRS. */
+ * Returns DR_ERR_UNSUPPORTED when cd->c is not a multiple of 16 (fp32) or 8 (bf16): such filters
+ * stay in KCRS. */
 int dr_pack_filters(const dr_conv* cd, int dtype, const void* w_kcrs, void* w_krsc, void* stream);
 
 /* Slim layer of streamline slimming (Sec. 3.1 "Pooling Layer" / "Non-Pooling Layer"): the

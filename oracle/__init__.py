@@ -195,7 +195,9 @@ def forward(layers, params, x, mirror_bf16=False, fold=False, trace=None):
     mirror_bf16: round every layer's output to bf16 before the next layer reads it (the storage
                  rule of the bf16 configurations); arithmetic inside a layer stays fp64.
     fold:        slim form of a BatchNorm network (Lemma 2): every conv+BN pair is replaced by one
-                 conv with folded weights and bias.
+                 conv with folded weights and bias.  True: the fold is computed here from the
+                 conv and BN parameters; "given": `params` already holds the folded conv
+                 parameters (one dict per conv, no BN dicts), e.g. after rounding them to bf16.
     trace:       optional list; receives (kind, output) after each top-level layer.
     """
     pit = params if isinstance(params, _Params) else _Params(params)
@@ -233,7 +235,10 @@ def forward(layers, params, x, mirror_bf16=False, fold=False, trace=None):
 def _conv_bn(y, cq, bq, stride, pad, eps, rnd, fold, relu_after):
     """conv -> BN(+Scale) [-> ReLU] of Eq. (2); `fold` = the merged conv of Lemma 2 instead."""
     if fold:
-        wf, bf = fold_bn(cq["w"], cq["b"], bq["gamma"], bq["beta"], bq["mean"], bq["var"], eps)
+        if bq is None:      # parameters were folded by the caller
+            wf, bf = cq["w"], cq["b"]
+        else:
+            wf, bf = fold_bn(cq["w"], cq["b"], bq["gamma"], bq["beta"], bq["mean"], bq["var"], eps)
         y = conv2d(y, wf, bf, stride, pad)
         return rnd(relu(y) if relu_after else y)
     y = rnd(conv2d(y, cq["w"], cq["b"], stride, pad))
@@ -245,13 +250,19 @@ def _bottleneck(x, p, pit, rnd, fold):
     """ResNet bottleneck (Sec. 4.2: one branch of three convs, one shortcut branch with one conv on
     the first block): relu(bn(conv1x1(relu(bn(conv3x3(relu(bn(conv1x1 x))))))) + shortcut(x))."""
     eps = p["eps"]
-    ca, ba, cb, bb, cc, bc = (pit.next() for _ in range(6))
+    given = fold == "given"
+    nxt = (lambda: (pit.next(), None)) if given else (lambda: (pit.next(), pit.next()))
+    (ca, ba), (cb, bb), (cc, bc) = nxt(), nxt(), nxt()
     y = _conv_bn(x, ca, ba, 1, 0, eps, rnd, fold, True)
     y = _conv_bn(y, cb, bb, 1, 1, eps, rnd, fold, True)
-    y = _conv_bn(y, cc, bc, 1, 0, eps, rnd, fold, False)
     if p["project"]:
-        cp, bp = pit.next(), pit.next()
+        cp, bp = nxt()
         sc = _conv_bn(x, cp, bp, 1, 0, eps, rnd, fold, False)
     else:
         sc = x
+    if fold:
+        # slim form: the last conv's store adds the shortcut and applies the ReLU (one rounding)
+        y = _conv_bn(y, cc, bc, 1, 0, eps, (lambda a: a), fold, False)
+        return rnd(add_relu(y, sc))
+    y = _conv_bn(y, cc, bc, 1, 0, eps, rnd, fold, False)
     return rnd(add_relu(y, sc))

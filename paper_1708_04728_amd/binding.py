@@ -19,6 +19,7 @@ DR_OK = 0
 DR_ERR_NULL, DR_ERR_SHAPE, DR_ERR_UNSUPPORTED, DR_ERR_WORKSPACE, DR_ERR_HIP = 1, 2, 3, 4, 5
 DR_F32, DR_BF16 = 0, 1
 DR_KCRS, DR_KRSC = 0, 1
+DR_NCHW, DR_NHWC = 0, 1
 DR_MAX_BRANCHES, DR_MAX_STEPS = 8, 4
 DR_STEP_CONV, DR_STEP_MAXPOOL = 0, 1
 DR_FUSE_RELU, DR_FUSE_CONCAT, DR_FUSE_STACK = 1, 2, 4
@@ -27,7 +28,7 @@ DR_FUSE_RELU, DR_FUSE_CONCAT, DR_FUSE_STACK = 1, 2, 4
 
 
 class dr_tensor(C.Structure):
-    _fields_ = [("n", C.c_int), ("c", C.c_int), ("h", C.c_int), ("w", C.c_int), ("dtype", C.c_int)]
+    _fields_ = [("n", C.c_int), ("c", C.c_int), ("h", C.c_int), ("w", C.c_int), ("dtype", C.c_int), ("layout", C.c_int)]
 
 
 class dr_conv(C.Structure):
@@ -146,12 +147,29 @@ def _dtype_code(t):
     raise TypeError("unsupported dtype %s" % t.dtype)
 
 
+class NHWC:
+    """Marks a contiguous torch tensor of shape (n, h, w, c) as a channels-last activation."""
+
+    def __init__(self, t):
+        if t.dim() != 4:
+            raise ValueError("NHWC tensors are 4-d (n, h, w, c)")
+        self.t = t
+
+    def __getattr__(self, name):          # data_ptr, dtype, numel, ... of the wrapped tensor
+        return getattr(self.t, name)
+
+
 def desc(t):
-    """dr_tensor of a contiguous 4-d (or 2-d: {n, c, 1, 1}) torch tensor."""
+    """dr_tensor of a contiguous torch tensor: 4-d (n, c, h, w), 2-d {n, c, 1, 1}, or NHWC(...)."""
+    if isinstance(t, NHWC):
+        if not t.t.is_contiguous():
+            raise ValueError("tensor must be contiguous")
+        n, h, w, c = t.t.shape
+        return dr_tensor(n, c, h, w, _dtype_code(t.t), DR_NHWC)
     if not t.is_contiguous():
-        raise ValueError("tensor must be contiguous (NCHW)")
+        raise ValueError("tensor must be contiguous")
     shape = tuple(t.shape) + (1,) * (4 - t.dim())
-    return dr_tensor(shape[0], shape[1], shape[2], shape[3], _dtype_code(t))
+    return dr_tensor(shape[0], shape[1], shape[2], shape[3], _dtype_code(t), DR_NCHW)
 
 
 def _ptr(t):
@@ -170,9 +188,9 @@ def conv_desc(k, c, r, s=None, stride=1, pad=0, relu=False, layout=DR_KCRS):
     return dr_conv(k, c, r, s, sh, sw, ph, pw, int(relu), layout)
 
 
-def can_pack(c):
+def can_pack(c, dtype="f32"):
     """Filters over c input channels have a KRSC form the fast kernels accept."""
-    return c % 16 == 0
+    return c % (8 if dtype in ("bf16", torch.bfloat16) else 16) == 0
 
 
 def pool_desc(k, stride, pad=0):

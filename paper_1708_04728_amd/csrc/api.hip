@@ -70,6 +70,7 @@ int check_tensor(const char* who, const char* name, const dr_tensor* t)
     if (t->n < 0 || t->c < 0 || t->h < 0 || t->w < 0)
         return fail(DR_ERR_SHAPE, "%s: %s has a negative dimension (%d,%d,%d,%d)", who, name, t->n, t->c, t->h, t->w);
     if (t->dtype != DR_F32 && t->dtype != DR_BF16) return fail(DR_ERR_UNSUPPORTED, "%s: %s has unknown dtype %d", who, name, t->dtype);
+    if (t->layout != DR_NCHW && t->layout != DR_NHWC) return fail(DR_ERR_UNSUPPORTED, "%s: %s has unknown layout %d", who, name, t->layout);
     if ((double)t->n * t->c * t->h * t->w >= 2147483648.0)
         return fail(DR_ERR_UNSUPPORTED, "%s: %s has more than 2^31-1 elements", who, name);
     return DR_OK;
@@ -83,8 +84,8 @@ int check_conv_desc(const char* who, const dr_conv* c)
                     c->stride_h, c->stride_w, c->pad_h, c->pad_w);
     if (c->filter_layout != DR_KCRS && c->filter_layout != DR_KRSC)
         return fail(DR_ERR_UNSUPPORTED, "%s: unknown filter layout %d", who, c->filter_layout);
-    if (c->filter_layout == DR_KRSC && c->c % 16 != 0)
-        return fail(DR_ERR_UNSUPPORTED, "%s: KRSC filters need a channel count that is a multiple of 16 (got %d)", who, c->c);
+    if (c->filter_layout == DR_KRSC && c->c % 8 != 0)
+        return fail(DR_ERR_UNSUPPORTED, "%s: KRSC filters need a channel count that is a multiple of 8 (got %d)", who, c->c);
     return DR_OK;
 }
 
@@ -102,18 +103,21 @@ int check_pool_desc(const char* who, const dr_pool* p)
 dr_tensor conv_out(const dr_tensor& x, const dr_conv& c)
 {
     return dr_tensor{x.n, c.k, dr_conv_out_size(x.h, c.r, c.stride_h, c.pad_h), dr_conv_out_size(x.w, c.s, c.stride_w, c.pad_w),
-                     x.dtype};
+                     x.dtype, x.layout};
 }
 dr_tensor pool_out(const dr_tensor& x, const dr_pool& p)
 {
     return dr_tensor{x.n, x.c, dr_pool_out_size(x.h, p.kh, p.stride_h, p.pad_h), dr_pool_out_size(x.w, p.kw, p.stride_w, p.pad_w),
-                     x.dtype};
+                     x.dtype, x.layout};
 }
 dr_tensor avgpool_out(const dr_tensor& x, const dr_pool& p)
 {
-    return dr_tensor{x.n, x.c, dr_conv_out_size(x.h, p.kh, p.stride_h, 0), dr_conv_out_size(x.w, p.kw, p.stride_w, 0), x.dtype};
+    return dr_tensor{x.n, x.c, dr_conv_out_size(x.h, p.kh, p.stride_h, 0), dr_conv_out_size(x.w, p.kw, p.stride_w, 0), x.dtype, x.layout};
 }
-bool same_shape(const dr_tensor& a, const dr_tensor& b) { return a.n == b.n && a.c == b.c && a.h == b.h && a.w == b.w; }
+bool same_shape(const dr_tensor& a, const dr_tensor& b)
+{
+    return a.n == b.n && a.c == b.c && a.h == b.h && a.w == b.w && a.layout == b.layout;
+}
 
 // Validated convolution launch (shared by the single-layer entry points and the composite ones).
 int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias,
@@ -125,7 +129,10 @@ int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv&
         return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%d per channel, the layer produces %dx%dx%d", who, yd.n, yd.h, yd.w, o.n, o.h, o.w);
     if (y_c_offset < 0 || y_c_offset + cd.k > yd.c)
         return fail(DR_ERR_SHAPE, "%s: channels [%d,%d) do not fit an output of %d channels", who, y_c_offset, y_c_offset + cd.k, yd.c);
-    if (yd.dtype != xd.dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
+    if (yd.dtype != xd.dtype || yd.layout != xd.layout) return fail(DR_ERR_UNSUPPORTED, "%s: input and output differ in dtype or layout", who);
+    if (xd.dtype == DR_F32 && xd.layout != DR_NCHW) return fail(DR_ERR_UNSUPPORTED, "%s: fp32 convolution takes NCHW tensors", who);
+    if (xd.dtype == DR_F32 && cd.filter_layout == DR_KRSC && cd.c % 16 != 0)
+        return fail(DR_ERR_UNSUPPORTED, "%s: fp32 KRSC filters need a channel count that is a multiple of 16 (got %d)", who, cd.c);
     if ((double)cd.c * cd.r * cd.s >= 2147483648.0 || (double)o.n * o.h * o.w >= 2147483648.0)
         return fail(DR_ERR_UNSUPPORTED, "%s: problem too large", who);
     if ((size_t)o.n * cd.k * o.h * o.w == 0) return DR_OK;   // nothing to compute: pointers may be NULL
@@ -141,6 +148,7 @@ int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv&
     g.relu = cd.relu != 0;
     g.res_ctot = residual ? res_ctot : 0;
     g.w_krsc = cd.filter_layout == DR_KRSC;
+    g.nhwc = xd.layout == DR_NHWC;
     if (xd.dtype == DR_F32)
         return launch_conv_f32(g, (const float*)x, (const float*)w, bias, (const float*)residual, (float*)y, st);
     return launch_conv_bf16(g, (const uint16_t*)x, (const uint16_t*)w, bias, (const uint16_t*)residual, (uint16_t*)y, st);
@@ -196,7 +204,7 @@ int inception_validate(const dr_tensor& xd, const dr_inception& d, dr_tensor* ou
         else if (t.h != oh || t.w != ow) return fail(DR_ERR_SHAPE, "%s: branch %d ends at %dx%d, branch 0 at %dx%d", who, b, t.h, t.w, oh, ow);
         ctot += t.c;
     }
-    *out = dr_tensor{xd.n, ctot, oh, ow, xd.dtype};
+    *out = dr_tensor{xd.n, ctot, oh, ow, xd.dtype, xd.layout};
     return DR_OK;
 }
 
@@ -238,7 +246,7 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
                 const dr_tensor o = pool_out(t, stp.pool);
                 void* dst = ar.take(tensor_bytes(o));
                 if (!dst && !ar.measure) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
-                if (!ar.measure) DR_TRY(launch_maxpool(t.dtype, cur, dst, t.n * t.c, t.h, t.w, o.h, o.w, stp.pool, st));
+                if (!ar.measure) DR_TRY(launch_maxpool(t, cur, o, dst, stp.pool, st));
                 if (last) segs[nseg++] = ConcatSeg{dst, o.c, c_off};
                 cur = dst;
                 t = o;
@@ -246,7 +254,7 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
         }
         c_off += t.c;
     }
-    if (nseg && !ar.measure) DR_TRY(launch_concat(yd.dtype, nseg, segs, y, yd.n, yd.c, yd.h * yd.w, st));
+    if (nseg && !ar.measure) DR_TRY(launch_concat(yd, nseg, segs, y, st));
     return DR_OK;
 }
 
@@ -305,7 +313,7 @@ int bottleneck_run(const dr_tensor& xd, const void* x, const dr_bottleneck& bd, 
     }
     auto conv_bn = [&](const dr_tensor& in, const void* src, const dr_conv& c, int grp, const dr_tensor& o, void* dst, bool relu) -> int {
         DR_TRY(conv_run(who, in, src, c, P(grp, 0), F(grp, 1), nullptr, 0, o, dst, 0, st));
-        DR_TRY(launch_bn(o.dtype, dst, dst, o.n, o.c, o.h * o.w, F(grp, 2), F(grp, 3), F(grp, 4), F(grp, 5), bd.eps, 0, st));
+        DR_TRY(launch_bn(o, dst, dst, F(grp, 2), F(grp, 3), F(grp, 4), F(grp, 5), bd.eps, 0, st));
         if (relu) DR_TRY(launch_relu(o.dtype, dst, dst, tensor_elems(o), st));
         return DR_OK;
     };
@@ -360,15 +368,15 @@ int layer_out(const dr_layer_desc& L, const dr_tensor& t, dr_tensor* o)
     case DR_LAYER_BOTTLENECK:
         if (L.bottleneck.mid < 1 || L.bottleneck.out < 1) return fail(DR_ERR_SHAPE, "%s: bad bottleneck widths", who);
         if (!L.bottleneck.project && t.c != L.bottleneck.out) return fail(DR_ERR_SHAPE, "%s: identity shortcut needs %d channels, gets %d", who, L.bottleneck.out, t.c);
-        *o = dr_tensor{t.n, L.bottleneck.out, t.h, t.w, t.dtype};
+        *o = dr_tensor{t.n, L.bottleneck.out, t.h, t.w, t.dtype, t.layout};
         return DR_OK;
     case DR_LAYER_FC:
         if (L.fc_out < 1) return fail(DR_ERR_SHAPE, "%s: fc_out %d", who, L.fc_out);
-        *o = dr_tensor{t.n, L.fc_out, 1, 1, t.dtype};
+        *o = dr_tensor{t.n, L.fc_out, 1, 1, t.dtype, t.layout};
         return DR_OK;
     case DR_LAYER_SOFTMAX:
         if (t.h != 1 || t.w != 1) return fail(DR_ERR_SHAPE, "%s: softmax needs an {n, c, 1, 1} input", who);
-        *o = dr_tensor{t.n, t.c, 1, 1, DR_F32};
+        *o = dr_tensor{t.n, t.c, 1, 1, DR_F32, t.layout};
         return DR_OK;
     default: return fail(DR_ERR_UNSUPPORTED, "%s: unknown layer kind %d", who, L.kind);
     }
@@ -497,7 +505,8 @@ int dr_pack_filters(const dr_conv* cd, int dtype, const void* w_kcrs, void* w_kr
     if (!cd) return fail(DR_ERR_NULL, "%s: descriptor is NULL", who);
     if (cd->k < 1 || cd->c < 1 || cd->r < 1 || cd->s < 1) return fail(DR_ERR_SHAPE, "%s: bad filter shape", who);
     if (dtype != DR_F32 && dtype != DR_BF16) return fail(DR_ERR_UNSUPPORTED, "%s: unknown dtype %d", who, dtype);
-    if (cd->c % 16 != 0) return fail(DR_ERR_UNSUPPORTED, "%s: channel count %d is not a multiple of 16", who, cd->c);
+    if (cd->c % (dtype == DR_F32 ? 16 : 8) != 0)
+        return fail(DR_ERR_UNSUPPORTED, "%s: channel count %d is not a multiple of %d", who, cd->c, dtype == DR_F32 ? 16 : 8);
     if (!w_kcrs || !w_krsc) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
     if ((double)cd->k * cd->c * cd->r * cd->s >= 2147483648.0) return fail(DR_ERR_UNSUPPORTED, "%s: tensor too large", who);
     return launch_pack_filters(dtype, w_kcrs, w_krsc, cd->k, cd->c, cd->r * cd->s, (hipStream_t)stream);
@@ -535,7 +544,7 @@ int dr_lrn_fwd(const dr_tensor* d, const void* x, const dr_lrn* p, void* y, void
     if (tensor_elems(*d) == 0) return DR_OK;
     if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
     if (x == y) return fail(DR_ERR_UNSUPPORTED, "%s: in-place operation is not supported", who);
-    return launch_lrn(d->dtype, x, y, d->n, d->c, d->h * d->w, *p, (hipStream_t)stream);
+    return launch_lrn(*d, x, y, *p, (hipStream_t)stream);
 }
 
 int dr_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream)
@@ -549,7 +558,7 @@ int dr_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const d
     if (yd->dtype != xd->dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
     if (tensor_elems(o) == 0) return DR_OK;
     if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
-    return launch_maxpool(xd->dtype, x, y, xd->n * xd->c, xd->h, xd->w, o.h, o.w, *p, (hipStream_t)stream);
+    return launch_maxpool(*xd, x, o, y, *p, (hipStream_t)stream);
 }
 
 int dr_avgpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream)
@@ -564,7 +573,7 @@ int dr_avgpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const d
     if (yd->dtype != xd->dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
     if (tensor_elems(o) == 0) return DR_OK;
     if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
-    return launch_avgpool(xd->dtype, x, y, xd->n * xd->c, xd->h, xd->w, o.h, o.w, *p, (hipStream_t)stream);
+    return launch_avgpool(*xd, x, o, y, *p, (hipStream_t)stream);
 }
 
 int dr_concat(int nb, const dr_tensor* xds, const void* const* xs, const dr_tensor* yd, void* y, void* stream)
@@ -579,13 +588,13 @@ int dr_concat(int nb, const dr_tensor* xds, const void* const* xs, const dr_tens
     for (int i = 0; i < nb; ++i) {
         DR_TRY(check_tensor(who, "xds[i]", &xds[i]));
         if (!xs[i]) return fail(DR_ERR_NULL, "%s: xs[%d] is NULL", who, i);
-        if (xds[i].n != yd->n || xds[i].h != yd->h || xds[i].w != yd->w || xds[i].dtype != yd->dtype)
-            return fail(DR_ERR_SHAPE, "%s: input %d does not match the output's n, h, w or dtype", who, i);
+        if (xds[i].n != yd->n || xds[i].h != yd->h || xds[i].w != yd->w || xds[i].dtype != yd->dtype || xds[i].layout != yd->layout)
+            return fail(DR_ERR_SHAPE, "%s: input %d does not match the output's n, h, w, dtype or layout", who, i);
         segs[i] = ConcatSeg{xs[i], xds[i].c, c};
         c += xds[i].c;
     }
     if (c != yd->c) return fail(DR_ERR_SHAPE, "%s: inputs have %d channels in total, output has %d", who, c, yd->c);
-    return launch_concat(yd->dtype, nb, segs, y, yd->n, yd->c, yd->h * yd->w, (hipStream_t)stream);
+    return launch_concat(*yd, nb, segs, y, (hipStream_t)stream);
 }
 
 int dr_bn_fwd(const dr_tensor* d, const void* x, const float* gamma, const float* beta, const float* mean,
@@ -596,7 +605,7 @@ int dr_bn_fwd(const dr_tensor* d, const void* x, const float* gamma, const float
     if (tensor_elems(*d) == 0) return DR_OK;
     if (!x || !y || !gamma || !beta || !mean || !var) return fail(DR_ERR_NULL, "%s: a pointer is NULL", who);
     if (!(eps >= 0.f)) return fail(DR_ERR_SHAPE, "%s: eps must be >= 0", who);
-    return launch_bn(d->dtype, x, y, d->n, d->c, d->h * d->w, gamma, beta, mean, var, eps, relu, (hipStream_t)stream);
+    return launch_bn(*d, x, y, gamma, beta, mean, var, eps, relu, (hipStream_t)stream);
 }
 
 int dr_add_relu(const dr_tensor* d, const void* a, const void* b, void* y, void* stream)
@@ -809,9 +818,9 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
             DR_TRY(conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], nullptr, 0, od, dst, 0, st));
             break;
         case DR_LAYER_RELU: DR_TRY(launch_relu(t.dtype, cur, dst, tensor_elems(t), st)); break;
-        case DR_LAYER_LRN: DR_TRY(launch_lrn(t.dtype, cur, dst, t.n, t.c, t.h * t.w, L.lrn, st)); break;
-        case DR_LAYER_MAXPOOL: DR_TRY(launch_maxpool(t.dtype, cur, dst, t.n * t.c, t.h, t.w, od.h, od.w, L.pool, st)); break;
-        case DR_LAYER_AVGPOOL: DR_TRY(launch_avgpool(t.dtype, cur, dst, t.n * t.c, t.h, t.w, od.h, od.w, L.pool, st)); break;
+        case DR_LAYER_LRN: DR_TRY(launch_lrn(t, cur, dst, L.lrn, st)); break;
+        case DR_LAYER_MAXPOOL: DR_TRY(launch_maxpool(t, cur, od, dst, L.pool, st)); break;
+        case DR_LAYER_AVGPOOL: DR_TRY(launch_avgpool(t, cur, od, dst, L.pool, st)); break;
         case DR_LAYER_INCEPTION: {
             const int np = param_count(L) / 2;
             std::vector<const void*> w(np);

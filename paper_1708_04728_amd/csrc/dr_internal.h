@@ -39,6 +39,7 @@ struct ConvGeom {
     int relu;            // fused max(.,0)
     int res_ctot;        // channels of the residual tensor (0 = no residual add)
     int w_krsc;          // filters are in KRSC order (else KCRS)
+    int nhwc;            // activations (x, y, residual) are channels-last
 };
 
 // conv_f32.hip / conv_bf16.hip: y = conv(x, w) + bias [+ residual] [ReLU].
@@ -51,16 +52,21 @@ int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, co
 // pointwise.hip
 int launch_pack_filters(int dtype, const void* w_kcrs, void* w_krsc, int K, int C, int RS, hipStream_t st);
 int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st);
-int launch_lrn(int dtype, const void* x, void* y, int N, int C, int HW, const dr_lrn& p, hipStream_t st);
-int launch_maxpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p,
-                   hipStream_t st);
-int launch_avgpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p,
-                   hipStream_t st);
+int launch_lrn(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipStream_t st);
+int launch_maxpool(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, hipStream_t st);
+int launch_avgpool(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, hipStream_t st);
 struct ConcatSeg { const void* src; int c; int c_off; };
-int launch_concat(int dtype, int nb, const ConcatSeg* segs, void* y, int N, int Cy, int HW, hipStream_t st);
-int launch_bn(int dtype, const void* x, void* y, int N, int C, int HW, const float* gamma, const float* beta,
-              const float* mean, const float* var, float eps, int relu, hipStream_t st);
+int launch_concat(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st);
+int launch_bn(const dr_tensor& d, const void* x, void* y, const float* gamma, const float* beta, const float* mean,
+              const float* var, float eps, int relu, hipStream_t st);
 int launch_add_relu(int dtype, const void* a, const void* b, void* y, size_t count, hipStream_t st);
+
+// pointwise_nhwc.hip: the channels-last versions (called by the launchers above)
+int launch_lrn_nhwc(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipStream_t st);
+int launch_pool_nhwc(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, bool avg, hipStream_t st);
+int launch_concat_nhwc(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st);
+int launch_bn_nhwc(const dr_tensor& d, const void* x, void* y, const float* gamma, const float* beta, const float* mean,
+                   const float* var, float eps, int relu, hipStream_t st);
 int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* y, int N, int I, int O, hipStream_t st);
 int launch_softmax(int dtype, const void* x, float* y, int N, int O, hipStream_t st);
 

@@ -3,65 +3,10 @@
 // fp32 arithmetic.  Every kernel reads each input element once from HBM (neighbouring windows are
 // served by the caches) and writes each output once, with 16-byte accesses where the shape allows.
 #include "dr_internal.h"
+#include "dr_store.h"
 
 namespace dr {
 namespace {
-
-// ---- storage helpers -------------------------------------------------------------------------------
-__device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float((uint32_t)u << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;   // NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);                      // round to nearest, ties to even
-    return (uint16_t)(u >> 16);
-}
-
-template <typename T> struct Store;
-template <> struct Store<float> {
-    static constexpr int VN = 4;   // elements per 16 bytes
-    static __device__ __forceinline__ float ld(const float* p) { return *p; }
-    static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
-    static __device__ __forceinline__ void ldv(const float* p, float* v)
-    {
-        const float4 t = *reinterpret_cast<const float4*>(p);
-        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    }
-    static __device__ __forceinline__ void stv(float* p, const float* v)
-    {
-        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    }
-};
-template <> struct Store<uint16_t> {
-    static constexpr int VN = 8;
-    static __device__ __forceinline__ float ld(const uint16_t* p) { return bf16_to_f32(*p); }
-    static __device__ __forceinline__ void st(uint16_t* p, float v) { *p = f32_to_bf16(v); }
-    static __device__ __forceinline__ void ldv(const uint16_t* p, float* v)
-    {
-        const uint4 t = *reinterpret_cast<const uint4*>(p);
-        const uint32_t w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = __uint_as_float(w[i] << 16);
-            v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-        }
-    }
-    static __device__ __forceinline__ void stv(uint16_t* p, const float* v)
-    {
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
-        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
-    }
-};
-
-inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
-inline unsigned blocks_for(size_t items, int per_block, size_t cap = 1u << 20)
-{
-    size_t b = (items + per_block - 1) / per_block;
-    if (b < 1) b = 1;
-    return (unsigned)(b > cap ? cap : b);
-}
 
 // ---- ReLU / add+ReLU -----------------------------------------------------------------------------
 // ADD = false: y = max(a, 0);  ADD = true: y = max(a + b, 0).
@@ -432,39 +377,45 @@ int launch_add_relu(int dtype, const void* a, const void* b, void* y, size_t cou
     return DR_BY_DTYPE(dtype, (relu_launch<float, true>(a, b, y, count, st)), (relu_launch<uint16_t, true>(a, b, y, count, st)));
 }
 
-int launch_lrn(int dtype, const void* x, void* y, int N, int C, int HW, const dr_lrn& p, hipStream_t st)
+int launch_lrn(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipStream_t st)
 {
-    TraceScope trace("lrn", nullptr, (long long)((size_t)N * C * HW), st);
-    if ((size_t)N * C * HW == 0) return DR_OK;
-    return DR_BY_DTYPE(dtype, lrn_launch<float>(x, y, N, C, HW, p, st), lrn_launch<uint16_t>(x, y, N, C, HW, p, st));
+    TraceScope trace("lrn", nullptr, (long long)tensor_elems(d), st);
+    if (tensor_elems(d) == 0) return DR_OK;
+    if (d.layout == DR_NHWC) return launch_lrn_nhwc(d, x, y, p, st);
+    return DR_BY_DTYPE(d.dtype, lrn_launch<float>(x, y, d.n, d.c, d.h * d.w, p, st), lrn_launch<uint16_t>(x, y, d.n, d.c, d.h * d.w, p, st));
 }
 
-int launch_maxpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p, hipStream_t st)
+int launch_maxpool(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, hipStream_t st)
 {
-    TraceScope trace("maxpool", nullptr, (long long)((size_t)NC * P * Q), st);
-    return DR_BY_DTYPE(dtype, (pool_launch<float, false>(x, y, NC, H, W, P, Q, p, st)),
-                       (pool_launch<uint16_t, false>(x, y, NC, H, W, P, Q, p, st)));
+    TraceScope trace("maxpool", nullptr, (long long)tensor_elems(yd), st);
+    if (xd.layout == DR_NHWC) return launch_pool_nhwc(xd, x, yd, y, p, false, st);
+    return DR_BY_DTYPE(xd.dtype, (pool_launch<float, false>(x, y, xd.n * xd.c, xd.h, xd.w, yd.h, yd.w, p, st)),
+                       (pool_launch<uint16_t, false>(x, y, xd.n * xd.c, xd.h, xd.w, yd.h, yd.w, p, st)));
 }
 
-int launch_avgpool(int dtype, const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p, hipStream_t st)
+int launch_avgpool(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, hipStream_t st)
 {
-    TraceScope trace("avgpool", nullptr, (long long)((size_t)NC * P * Q), st);
-    return DR_BY_DTYPE(dtype, (pool_launch<float, true>(x, y, NC, H, W, P, Q, p, st)),
-                       (pool_launch<uint16_t, true>(x, y, NC, H, W, P, Q, p, st)));
+    TraceScope trace("avgpool", nullptr, (long long)tensor_elems(yd), st);
+    if (xd.layout == DR_NHWC) return launch_pool_nhwc(xd, x, yd, y, p, true, st);
+    return DR_BY_DTYPE(xd.dtype, (pool_launch<float, true>(x, y, xd.n * xd.c, xd.h, xd.w, yd.h, yd.w, p, st)),
+                       (pool_launch<uint16_t, true>(x, y, xd.n * xd.c, xd.h, xd.w, yd.h, yd.w, p, st)));
 }
 
-int launch_concat(int dtype, int nb, const ConcatSeg* segs, void* y, int N, int Cy, int HW, hipStream_t st)
+int launch_concat(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st)
 {
-    TraceScope trace("concat", nullptr, (long long)((size_t)N * Cy * HW), st);
-    return DR_BY_DTYPE(dtype, concat_launch<float>(nb, segs, y, N, Cy, HW, st), concat_launch<uint16_t>(nb, segs, y, N, Cy, HW, st));
+    TraceScope trace("concat", nullptr, (long long)tensor_elems(yd), st);
+    if (yd.layout == DR_NHWC) return launch_concat_nhwc(yd, nb, segs, y, st);
+    return DR_BY_DTYPE(yd.dtype, concat_launch<float>(nb, segs, y, yd.n, yd.c, yd.h * yd.w, st),
+                       concat_launch<uint16_t>(nb, segs, y, yd.n, yd.c, yd.h * yd.w, st));
 }
 
-int launch_bn(int dtype, const void* x, void* y, int N, int C, int HW, const float* gamma, const float* beta,
-              const float* mean, const float* var, float eps, int relu, hipStream_t st)
+int launch_bn(const dr_tensor& d, const void* x, void* y, const float* gamma, const float* beta, const float* mean,
+              const float* var, float eps, int relu, hipStream_t st)
 {
-    TraceScope trace("bn", nullptr, (long long)((size_t)N * C * HW), st);
-    return DR_BY_DTYPE(dtype, bn_launch<float>(x, y, N, C, HW, gamma, beta, mean, var, eps, relu, st),
-                       bn_launch<uint16_t>(x, y, N, C, HW, gamma, beta, mean, var, eps, relu, st));
+    TraceScope trace("bn", nullptr, (long long)tensor_elems(d), st);
+    if (d.layout == DR_NHWC) return launch_bn_nhwc(d, x, y, gamma, beta, mean, var, eps, relu, st);
+    return DR_BY_DTYPE(d.dtype, bn_launch<float>(x, y, d.n, d.c, d.h * d.w, gamma, beta, mean, var, eps, relu, st),
+                       bn_launch<uint16_t>(x, y, d.n, d.c, d.h * d.w, gamma, beta, mean, var, eps, relu, st));
 }
 
 int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* y, int N, int I, int O, hipStream_t st)

@@ -1,0 +1,262 @@
+// Bandwidth-bound layers for channels-last (NHWC) tensors: max/avg pooling, across-channel LRN,
+// concat, BatchNorm(+Scale).  The c values of a pixel are contiguous, so one lane owns one 16-byte
+// group of channels (8 bf16 or 4 fp32) of one pixel and consecutive lanes walk the channel axis:
+// every access is a coalesced 16-byte vector, window neighbours are whole vectors, and the
+// cross-channel LRN window is completed with wavefront shuffles from the neighbouring lanes.
+#include "dr_internal.h"
+#include "dr_store.h"
+
+namespace dr {
+namespace {
+
+// ---- pooling ------------------------------------------------------------------------------------------
+// V = elements per lane (a 16-byte vector, or 1 when C is not a multiple of the vector width).
+template <typename T, int V, bool AVG>
+__global__ __launch_bounds__(256) void pool_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int H, int W, int P,
+                                                        int Q, size_t total, dr_pool p)
+{
+    const int CV = C / V;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int cv = (int)(i % CV);
+        size_t t = i / CV;
+        const int q = (int)(t % Q); t /= Q;
+        const int pp = (int)(t % P);
+        const size_t n = t / P;
+        const int h0 = pp * p.stride_h - p.pad_h, w0 = q * p.stride_w - p.pad_w;
+        const int ha = max(h0, 0), hb = min(h0 + p.kh, H);
+        const int wa = max(w0, 0), wb = min(w0 + p.kw, W);
+        float m[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) m[j] = AVG ? 0.f : -INFINITY;
+        for (int h = ha; h < hb; ++h)
+            for (int w = wa; w < wb; ++w) {
+                const T* src = x + ((n * H + h) * W + w) * C + (size_t)cv * V;
+                float v[V];
+                if constexpr (V == 1) v[0] = Store<T>::ld(src);
+                else Store<T>::ldv(src, v);
+#pragma unroll
+                for (int j = 0; j < V; ++j) m[j] = AVG ? m[j] + v[j] : fmaxf(m[j], v[j]);
+            }
+        if (AVG) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) m[j] /= (float)(p.kh * p.kw);
+        }
+        T* dst = y + i * V;
+        if constexpr (V == 1) Store<T>::st(dst, m[0]);
+        else Store<T>::stv(dst, m);
+    }
+}
+
+template <typename T>
+int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, bool avg, hipStream_t st)
+{
+    constexpr int VN = Store<T>::VN;
+    const bool vec = xd.c % VN == 0 && aligned16(x) && aligned16(y);
+    const size_t total = (size_t)yd.n * yd.h * yd.w * (vec ? yd.c / VN : yd.c);
+    if (total == 0) return DR_OK;
+    const dim3 grid(blocks_for(total, 256, 256 * 64)), block(256);
+#define DR_POOL(V, AVG) hipLaunchKernelGGL((pool_nhwc_kernel<T, V, AVG>), grid, block, 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, total, p)
+    if (vec) { if (avg) DR_POOL(VN, true); else DR_POOL(VN, false); }
+    else { if (avg) DR_POOL(1, true); else DR_POOL(1, false); }
+#undef DR_POOL
+    return check_launch(avg ? "avgpool" : "maxpool");
+}
+
+// ---- LRN -------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float pow_neg_beta(float s, float beta, bool b075)
+{
+    if (b075) {                       // s^-0.75 = rsqrt(s) * sqrt(rsqrt(s))
+        const float r = 1.0f / sqrtf(s);
+        return r * sqrtf(r);
+    }
+    return powf(s, -beta);
+}
+
+// Window of 5 channels.  A pixel occupies LPP = C / V consecutive lanes of one wave (PPW pixels per
+// wave, the remaining lanes idle), so the two channels on either side of a lane's vector live in the
+// neighbouring lanes and arrive by shuffle; the first / last lane of a pixel sees zeros instead.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void lrn5_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int LPP, int PPW,
+                                                        size_t pixels, float a_over_n, float beta, float k, int b075)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const size_t nwaves = ((size_t)gridDim.x * blockDim.x) >> 6;
+    const int sub = lane / LPP, cv = lane - sub * LPP;       // pixel slot within the wave, vector within the pixel
+    const bool lane_on = sub < PPW;
+    for (size_t pw = wave; pw * PPW < pixels; pw += nwaves) {
+        const size_t pix = pw * PPW + sub;
+        const bool on = lane_on && pix < pixels;
+        float v[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) v[j] = 0.f;
+        if (on) Store<T>::ldv(x + pix * C + (size_t)cv * V, v);
+        float sq[V + 4];                                     // squares of channels c0-2 .. c0+V+1
+#pragma unroll
+        for (int j = 0; j < V; ++j) sq[j + 2] = v[j] * v[j];
+        // every lane takes part in the shuffles (idle lanes carry zeros)
+        const float l0 = __shfl_up(sq[V], 1, 64), l1 = __shfl_up(sq[V + 1], 1, 64);       // neighbour's last two
+        const float r0 = __shfl_down(sq[2], 1, 64), r1 = __shfl_down(sq[3], 1, 64);       // neighbour's first two
+        const bool has_l = cv > 0 && lane > 0, has_r = cv < LPP - 1 && lane < 63;
+        sq[0] = has_l ? l0 : 0.f; sq[1] = has_l ? l1 : 0.f;
+        sq[V + 2] = has_r ? r0 : 0.f; sq[V + 3] = has_r ? r1 : 0.f;
+        if (on) {
+            float o[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                const float ss = ((sq[j] + sq[j + 1]) + sq[j + 2]) + (sq[j + 3] + sq[j + 4]);
+                o[j] = v[j] * pow_neg_beta(fmaf(a_over_n, ss, k), beta, b075);
+            }
+            Store<T>::stv(y + pix * C + (size_t)cv * V, o);
+        }
+    }
+}
+
+// Any window length / channel count: every output re-reads its window (served by the caches).
+template <typename T>
+__global__ __launch_bounds__(256) void lrn_generic_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y, int C, size_t total,
+                                                               int nl, float a_over_n, float beta, float k)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int c = (int)(i % C);
+        const size_t base = i - c;
+        float ss = 0.f;
+        for (int cc = c - nl / 2; cc < c - nl / 2 + nl; ++cc)
+            if (cc >= 0 && cc < C) {
+                const float v = Store<T>::ld(x + base + cc);
+                ss = fmaf(v, v, ss);
+            }
+        Store<T>::st(y + i, Store<T>::ld(x + i) * powf(fmaf(a_over_n, ss, k), -beta));
+    }
+}
+
+template <typename T>
+int lrn_launch(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipStream_t st)
+{
+    constexpr int VN = Store<T>::VN;
+    const float a_over_n = p.alpha / (float)p.local_size;
+    const size_t pixels = (size_t)d.n * d.h * d.w;
+    const int lpp = d.c / VN;
+    if (p.local_size == 5 && d.c % VN == 0 && lpp >= 1 && lpp <= 64 && aligned16(x) && aligned16(y)) {
+        const int ppw = 64 / lpp;
+        const size_t waves = (pixels + ppw - 1) / ppw;
+        hipLaunchKernelGGL((lrn5_nhwc_kernel<T, VN>), dim3(blocks_for(waves, 4, 256 * 64)), dim3(256), 0, st, (const T*)x, (T*)y,
+                           d.c, lpp, ppw, pixels, a_over_n, p.beta, p.k, (int)(p.beta == 0.75f));
+        return check_launch("lrn");
+    }
+    const size_t total = pixels * d.c;
+    hipLaunchKernelGGL((lrn_generic_nhwc_kernel<T>), dim3(blocks_for(total, 256, 256 * 32)), dim3(256), 0, st, (const T*)x, (T*)y,
+                       d.c, total, p.local_size, a_over_n, p.beta, p.k);
+    return check_launch("lrn");
+}
+
+// ---- concat ----------------------------------------------------------------------------------------------
+struct ConcatArgs {
+    const void* src[DR_MAX_BRANCHES];
+    int c[DR_MAX_BRANCHES];       // channels of each input, in units of V
+    int c_off[DR_MAX_BRANCHES];   // first output channel of each input, in units of V
+    int nb;
+};
+
+// One lane per 16-byte group of the output pixel: the group's position picks the input it comes from.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void concat_nhwc_kernel(ConcatArgs a, T* __restrict__ y, int CyV, size_t total)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int cv = (int)(i % CyV);
+        const size_t pix = i / CyV;
+        int b = 0;
+#pragma unroll
+        for (int j = 1; j < DR_MAX_BRANCHES; ++j)
+            if (j < a.nb && cv >= a.c_off[j]) b = j;
+        const T* src = (const T*)a.src[b] + (pix * a.c[b] + (cv - a.c_off[b])) * V;
+        if constexpr (V == 1) y[i] = *src;
+        else *reinterpret_cast<uint4*>(y + i * V) = *reinterpret_cast<const uint4*>(src);
+    }
+}
+
+template <typename T>
+int concat_launch(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st)
+{
+    constexpr int VN = Store<T>::VN;
+    bool vec = aligned16(y) && yd.c % VN == 0;
+    for (int i = 0; i < nb; ++i) vec = vec && aligned16(segs[i].src) && segs[i].c % VN == 0 && segs[i].c_off % VN == 0;
+    const int v = vec ? VN : 1;
+    ConcatArgs a;
+    a.nb = nb;
+    for (int i = 0; i < DR_MAX_BRANCHES; ++i) { a.src[i] = nullptr; a.c[i] = 0; a.c_off[i] = 0; }
+    for (int i = 0; i < nb; ++i) { a.src[i] = segs[i].src; a.c[i] = segs[i].c / v; a.c_off[i] = segs[i].c_off / v; }
+    const size_t total = (size_t)yd.n * yd.h * yd.w * (yd.c / v);
+    if (total == 0) return DR_OK;
+    const dim3 grid(blocks_for(total, 256, 256 * 64)), block(256);
+    if (vec) hipLaunchKernelGGL((concat_nhwc_kernel<T, VN>), grid, block, 0, st, a, (T*)y, yd.c / v, total);
+    else hipLaunchKernelGGL((concat_nhwc_kernel<T, 1>), grid, block, 0, st, a, (T*)y, yd.c, total);
+    return check_launch("concat");
+}
+
+// ---- BatchNorm + Scale ----------------------------------------------------------------------------------
+template <typename T, int V>
+__global__ __launch_bounds__(256) void bn_nhwc_kernel(const T* x, T* y, int C, size_t total, const float* __restrict__ gamma,
+                                                      const float* __restrict__ beta, const float* __restrict__ mean,
+                                                      const float* __restrict__ var, float eps, int relu)
+{
+    const int CV = C / V;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int c0 = (int)(i % CV) * V;
+        float v[V];
+        if constexpr (V == 1) v[0] = Store<T>::ld(x + i);
+        else Store<T>::ldv(x + i * V, v);
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const int c = c0 + j;
+            v[j] = gamma[c] * ((v[j] - mean[c]) * (1.0f / sqrtf(var[c] + eps))) + beta[c];
+            if (relu) v[j] = fmaxf(v[j], 0.f);
+        }
+        if constexpr (V == 1) Store<T>::st(y + i, v[0]);
+        else Store<T>::stv(y + i * V, v);
+    }
+}
+
+template <typename T>
+int bn_launch(const dr_tensor& d, const void* x, void* y, const float* gamma, const float* beta, const float* mean,
+              const float* var, float eps, int relu, hipStream_t st)
+{
+    constexpr int VN = Store<T>::VN;
+    const bool vec = d.c % VN == 0 && aligned16(x) && aligned16(y);
+    const size_t total = tensor_elems(d) / (vec ? VN : 1);
+    if (total == 0) return DR_OK;
+    const dim3 grid(blocks_for(total, 256, 256 * 64)), block(256);
+    if (vec) hipLaunchKernelGGL((bn_nhwc_kernel<T, VN>), grid, block, 0, st, (const T*)x, (T*)y, d.c, total, gamma, beta, mean, var, eps, relu);
+    else hipLaunchKernelGGL((bn_nhwc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, d.c, total, gamma, beta, mean, var, eps, relu);
+    return check_launch("bn");
+}
+
+}  // namespace
+
+int launch_pool_nhwc(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, bool avg, hipStream_t st)
+{
+    return xd.dtype == DR_BF16 ? pool_launch<uint16_t>(xd, x, yd, y, p, avg, st) : pool_launch<float>(xd, x, yd, y, p, avg, st);
+}
+
+int launch_lrn_nhwc(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipStream_t st)
+{
+    return d.dtype == DR_BF16 ? lrn_launch<uint16_t>(d, x, y, p, st) : lrn_launch<float>(d, x, y, p, st);
+}
+
+int launch_concat_nhwc(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st)
+{
+    return yd.dtype == DR_BF16 ? concat_launch<uint16_t>(yd, nb, segs, y, st) : concat_launch<float>(yd, nb, segs, y, st);
+}
+
+int launch_bn_nhwc(const dr_tensor& d, const void* x, void* y, const float* gamma, const float* beta, const float* mean,
+                   const float* var, float eps, int relu, hipStream_t st)
+{
+    return d.dtype == DR_BF16 ? bn_launch<uint16_t>(d, x, y, gamma, beta, mean, var, eps, relu, st)
+                              : bn_launch<float>(d, x, y, gamma, beta, mean, var, eps, relu, st);
+}
+
+}  // namespace dr

@@ -13,17 +13,36 @@ def torch_dtype(dtype):
     return torch.bfloat16 if dtype == "bf16" else torch.float32
 
 
-def to_device(a, dtype="f32", device="cuda"):
+def to_device(a, dtype="f32", device="cuda", nhwc=False):
     """numpy fp32 array -> device tensor; for bf16 the values must already be bf16-representable,
-    so the conversion is exact."""
+    so the conversion is exact.  nhwc: an (n, c, h, w) array is stored channels-last and returned
+    wrapped in binding.NHWC."""
     t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
     if dtype == "bf16":
         t = t.to(torch.bfloat16)
+    if nhwc:
+        return B.NHWC(t.permute(0, 2, 3, 1).contiguous().to(device))
     return t.to(device)
 
 
+def to_host(t):
+    """Device tensor (plain, or binding.NHWC) -> numpy float64 in (n, c, h, w) order."""
+    if isinstance(t, B.NHWC):
+        return t.t.float().permute(0, 3, 1, 2).contiguous().cpu().numpy().astype(np.float64)
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def empty_like_desc(d, device="cuda"):
+    """Uninitialised device tensor for a dr_tensor descriptor (binding.NHWC-wrapped if channels-last)."""
+    dt = torch.bfloat16 if d.dtype == B.DR_BF16 else torch.float32
+    if d.layout == B.DR_NHWC:
+        return B.NHWC(torch.empty((d.n, d.h, d.w, d.c), dtype=dt, device=device))
+    return torch.empty((d.n, d.c, d.h, d.w), dtype=dt, device=device)
+
+
 def conv_desc(p, c_in, relu=False, pack=False):
-    layout = B.DR_KRSC if (pack and B.can_pack(c_in)) else B.DR_KCRS
+    """pack: False, or the dtype ("f32" / "bf16") whose packing rule decides KRSC vs KCRS."""
+    layout = B.DR_KRSC if (pack and B.can_pack(c_in, pack)) else B.DR_KCRS
     return B.conv_desc(p["k"], c_in, p["r"], p["s"], p["stride"], p["pad"], relu, layout)
 
 
@@ -96,7 +115,7 @@ def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False, pac
             c = _out_channels([(kind, p)], c)
         elif kind == "bottleneck":
             L.kind = B.DR_LAYER_BOTTLENECK
-            lay = B.DR_KRSC if (pack and B.can_pack(c) and B.can_pack(p["mid"])) else B.DR_KCRS
+            lay = B.DR_KRSC if (pack and B.can_pack(c, pack) and B.can_pack(p["mid"], pack)) else B.DR_KCRS
             L.bottleneck = B.dr_bottleneck(p["mid"], p["out"], int(p["project"]), int(folded), p["eps"], lay)
             c = p["out"]
         elif kind == "fc":
@@ -119,7 +138,7 @@ def flat_params(params, dtype="f32", device="cuda", pack=False):
     for q in params:
         if "w" in q:
             w = to_device(q["w"], dtype, device)
-            if pack and w.dim() == 4 and B.can_pack(w.shape[1]):
+            if pack and w.dim() == 4 and B.can_pack(w.shape[1], dtype):
                 w = B.pack_filters(w)
             out += [w, to_device(q["b"], "f32", device)]
         else:

@@ -1,0 +1,150 @@
+"""GPU parity of the channels-last (NHWC) kernels and of the bf16 convolution against the fp64
+oracle (which is layout free: tensors are permuted at the boundary only)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from paper_1708_04728_amd import binding as B
+from util import TOL_BF16, TOL_F32, empty_nhwc, gpu, gpu_nhwc, host, host_nhwc, rel_err
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _vals(rng, shape, dtype):
+    a = rng.standard_normal(shape).astype(np.float32)
+    return workloads.round_to_bf16(a) if dtype == "bf16" else a
+
+
+def _tol(dtype):
+    return TOL_BF16 if dtype == "bf16" else TOL_F32
+
+
+# N, C, H, W, K, R, S, stride, pad
+BF16_CONV_CASES = [
+    (2, 64, 56, 56, 64, 1, 1, 1, 0),       # ResNet conv2_x 1x1
+    (2, 64, 56, 56, 64, 3, 3, 1, 1),
+    (1, 64, 56, 56, 256, 1, 1, 1, 0),
+    (1, 256, 28, 28, 64, 1, 1, 1, 0),
+    (2, 16, 28, 28, 32, 5, 5, 1, 2),       # inception 5x5, one 16-channel chunk pair per slice
+    (2, 24, 14, 14, 64, 5, 5, 1, 2),       # C = 24: ragged channel tail inside a slice
+    (1, 112, 14, 14, 224, 3, 3, 1, 1),     # C = 112: ragged tail of a 64-deep slice, M = 224
+    (2, 192, 28, 28, 16, 1, 1, 1, 0),      # M smaller than a tile
+    (1, 64, 56, 56, 192, 3, 3, 2, 1),      # slim conv2 (stride 2)
+    (1, 8, 9, 7, 20, 3, 3, 2, 1),          # tiny, everything ragged
+    (2, 832, 7, 7, 384, 1, 1, 1, 0),       # inception 5b
+]
+
+
+@pytest.mark.parametrize("case", BF16_CONV_CASES)
+@pytest.mark.parametrize("relu", [False, True])
+def test_conv2d_bf16_nhwc(case, relu):
+    N, C, H, W, K, R, S, stride, pad = case
+    if relu and case not in (BF16_CONV_CASES[1], BF16_CONV_CASES[5], BF16_CONV_CASES[9]):
+        pytest.skip("ReLU epilogue covered on three shapes")
+    rng = np.random.default_rng(hash(case) % 2 ** 31)
+    x = _vals(rng, (N, C, H, W), "bf16")
+    w = workloads.round_to_bf16(_vals(rng, (K, C, R, S), "f32") * np.float32(np.sqrt(2.0 / (C * R * S))))
+    b = _vals(rng, (K,), "f32") * np.float32(0.1)
+    ref = oracle.conv2d(x, w, b, stride, pad, relu)
+    y = empty_nhwc(ref.shape, "bf16")
+    wg = B.pack_filters(gpu(w, "bf16"))
+    assert np.array_equal(host(wg), np.transpose(w, (0, 2, 3, 1)))
+    B.conv2d_fwd(gpu_nhwc(x, "bf16"), B.conv_desc(K, C, R, S, stride, pad, relu, B.DR_KRSC), wg, gpu(b), y)
+    torch.cuda.synchronize()
+    assert rel_err(host_nhwc(y), ref) < TOL_BF16
+    # tighter: against the oracle's result rounded to bf16, at most one unit in the last place apart
+    assert rel_err(host_nhwc(y), oracle.round_bf16(ref)) < 2.0 ** -7
+
+
+def test_conv2d_bf16_fallback_paths():
+    """3 input channels (no KRSC form) in NHWC, and NCHW tensors: the plain gather kernel."""
+    rng = np.random.default_rng(11)
+    x = _vals(rng, (2, 3, 32, 30), "bf16")
+    w = workloads.round_to_bf16(_vals(rng, (64, 3, 7, 7), "f32") * np.float32(0.1))
+    b = _vals(rng, (64,), "f32") * np.float32(0.1)
+    ref = oracle.conv2d(x, w, b, 2, 3, True)
+    y = empty_nhwc(ref.shape, "bf16")
+    B.conv2d_fwd(gpu_nhwc(x, "bf16"), B.conv_desc(64, 3, 7, 7, 2, 3, True), gpu(w, "bf16"), gpu(b), y)
+    torch.cuda.synchronize()
+    assert rel_err(host_nhwc(y), ref) < TOL_BF16
+    y2 = torch.full(ref.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.conv2d_fwd(gpu(x, "bf16"), B.conv_desc(64, 3, 7, 7, 2, 3, True), gpu(w, "bf16"), gpu(b), y2)
+    torch.cuda.synchronize()
+    assert rel_err(host(y2), ref) < TOL_BF16
+
+
+def test_conv2d_bf16_channel_offset():
+    rng = np.random.default_rng(12)
+    x = _vals(rng, (2, 16, 10, 10), "bf16")
+    w = workloads.round_to_bf16(_vals(rng, (24, 16, 3, 3), "f32") * np.float32(0.1))
+    ref = oracle.conv2d(x, w, None, 1, 1)
+    y = B.NHWC(torch.full((2, 10, 10, 40), -7.0, dtype=torch.bfloat16, device="cuda"))
+    B.conv2d_fwd(gpu_nhwc(x, "bf16"), B.conv_desc(24, 16, 3, pad=1, layout=B.DR_KRSC), B.pack_filters(gpu(w, "bf16")), None, y,
+                 y_c_offset=8)
+    torch.cuda.synchronize()
+    got = host_nhwc(y)
+    assert rel_err(got[:, 8:32], ref) < TOL_BF16
+    assert (got[:, :8] == -7.0).all() and (got[:, 32:] == -7.0).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [(2, 64, 112, 112, 3, 2, 0), (2, 192, 28, 28, 3, 1, 1), (1, 480, 28, 28, 3, 2, 0),
+                                  (2, 6, 7, 9, 3, 2, 0), (1, 8, 5, 5, 2, 2, 1), (1, 16, 9, 9, 3, 3, 1)])
+def test_maxpool_nhwc_bit_exact(dtype, case):
+    N, C, H, W, k, s, pad = case
+    x = -np.abs(_vals(np.random.default_rng(5), (N, C, H, W), dtype)) - np.float32(0.5)
+    if dtype == "bf16":
+        x = workloads.round_to_bf16(x)
+    ref = oracle.maxpool(x, k, s, pad)
+    y = empty_nhwc(ref.shape, dtype)
+    B.maxpool_fwd(gpu_nhwc(x, dtype), B.pool_desc(k, s, pad), y)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_nhwc(y), ref)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 64, 56, 56), (1, 192, 28, 28), (2, 8, 3, 5), (1, 520, 4, 4), (2, 6, 5, 5)])
+def test_lrn_nhwc(dtype, shape):
+    x = _vals(np.random.default_rng(3), shape, dtype) * np.float32(30.0)
+    if dtype == "bf16":
+        x = workloads.round_to_bf16(x)
+    ref = oracle.lrn(x, 5, 1e-4, 0.75, 1.0)
+    y = empty_nhwc(shape, dtype)
+    B.lrn_fwd(gpu_nhwc(x, dtype), y, 5, 1e-4, 0.75, 1.0)
+    torch.cuda.synchronize()
+    assert rel_err(host_nhwc(y), ref) < _tol(dtype)
+    ref3 = oracle.lrn(x, 3, 0.5, 0.5, 2.0)
+    B.lrn_fwd(gpu_nhwc(x, dtype), y, 3, 0.5, 0.5, 2.0)
+    torch.cuda.synchronize()
+    assert rel_err(host_nhwc(y), ref3) < _tol(dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_concat_bn_avgpool_nhwc(dtype):
+    rng = np.random.default_rng(6)
+    for shapes in ([(2, 64, 28, 28), (2, 128, 28, 28), (2, 32, 28, 28), (2, 32, 28, 28)], [(3, 1, 5, 3), (3, 2, 5, 3), (3, 5, 5, 3)]):
+        xs = [_vals(rng, s, dtype) for s in shapes]
+        ref = oracle.concat(xs)
+        y = empty_nhwc(ref.shape, dtype)
+        B.concat([gpu_nhwc(x, dtype) for x in xs], y)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_nhwc(y), ref)
+    for shape in ((2, 64, 14, 14), (3, 5, 7, 3)):
+        x = _vals(rng, shape, dtype)
+        C = shape[1]
+        g, be = rng.uniform(0.5, 1.5, C).astype(np.float32), (rng.standard_normal(C) * 0.1).astype(np.float32)
+        mu, var = (rng.standard_normal(C) * 0.1).astype(np.float32), rng.uniform(0.5, 1.5, C).astype(np.float32)
+        eps = float(np.float32(1e-5))
+        ref = oracle.bn(x, g, be, mu, var, eps)
+        xg = gpu_nhwc(x, dtype)
+        B.bn_fwd(xg, gpu(g), gpu(be), gpu(mu), gpu(var), eps, True, xg)
+        torch.cuda.synchronize()
+        assert rel_err(host_nhwc(xg), np.maximum(ref, 0)) < _tol(dtype)
+    x = _vals(rng, (4, 1024, 7, 7), dtype)
+    ref = oracle.avgpool(x, 7)
+    y = empty_nhwc(ref.shape, dtype)
+    B.avgpool_fwd(gpu_nhwc(x, dtype), B.pool_desc(7, 1), y)
+    torch.cuda.synchronize()
+    assert rel_err(host_nhwc(y), ref) < _tol(dtype)

@@ -28,3 +28,22 @@ def gpu(a, dtype="f32"):
 
 def host(t):
     return t.float().cpu().numpy().astype(np.float64)
+
+
+def gpu_nhwc(a, dtype="f32"):
+    """(n, c, h, w) numpy array -> channels-last device tensor wrapped for the binding."""
+    from paper_1708_04728_amd import graph as G
+    return G.to_device(a, dtype, nhwc=True)
+
+
+def host_nhwc(t):
+    from paper_1708_04728_amd import graph as G
+    return G.to_host(t)
+
+
+def empty_nhwc(shape_nchw, dtype="f32"):
+    import torch
+    from paper_1708_04728_amd import binding as B
+    n, c, h, w = shape_nchw
+    return B.NHWC(torch.full((n, h, w, c), float("nan"), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32,
+                             device="cuda"))
