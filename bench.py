@@ -2,13 +2,14 @@
 """Benchmark of the forward hot path on one MI355X: original form vs slim form.
 
 One "step" = one forward pass of the ORIGINAL block (layer by layer: conv, ReLU, LRN / max-pool /
-concat kernels as separate passes, the form the paper times) followed by one forward pass of the
-SLIM block (slimmed structure, ReLU in the conv store, branches written straight into the
-concatenated tensor), both over the same batch already resident in HBM.
+concat / BatchNorm kernels as separate passes, the form the paper times) followed by one forward
+pass of the SLIM block (slimmed structure, ReLU in the conv store, branches written straight into
+the concatenated tensor, BatchNorm folded), both over the same batch already resident in HBM.
 
 Prints ONE JSON line: whole-step throughput (`value`, images/s through both forms), the per-form
 times and the slim/original speed-up, the roofline of the dominant kernel (measured with HIP events
-around that kernel inside the timed region) and the CPU oracle timed on the host cores.
+around that kernel inside the timed region), the CPU oracle timed on the host cores, and a short
+summary of the other configurations (`all_configs`).
 """
 import argparse
 import json
@@ -23,15 +24,105 @@ MI355X_HBM_GBS = 8000.0
 MI355X_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 
 WORKLOAD_NAMES = {
-    1: "config 1: GoogLeNet conv2 streamline block, batch 1, fp32, 64x56x56 -> 192x28x28",
-    2: "config 2: GoogLeNet inception(3a), batch 32, fp32, 192x28x28 -> 256x28x28",
-    3: "config 3: AlexNet front end (conv1+conv2 blocks), batch 128, fp32, 3x227x227",
+    1: "config 1: GoogLeNet conv2 streamline block, batch 1, fp32 NCHW, 64x56x56 -> 192x28x28",
+    2: "config 2: GoogLeNet inception(3a), batch 32, fp32 NCHW, 192x28x28 -> 256x28x28",
+    3: "config 3: AlexNet front end (conv1+conv2 blocks), batch 128, fp32 NCHW, 3x227x227",
+    4: "config 4: ResNet-50 conv2_x stage (3 bottlenecks), batch 128, bf16 NHWC / fp32 accumulate, 64x56x56",
+    5: "config 5: GoogLeNet-v1 forward, batch 128, bf16 NHWC / fp32 accumulate, 3x224x224 -> 1000",
 }
 
 
 def conv_flops(rec):
     label, k, c, r, s, items, ms = rec
     return 2.0 * k * c * r * s * items
+
+
+def is_tensor(rec):
+    return rec[0].startswith("conv") or rec[0] == "fc"
+
+
+class Workload:
+    """Both forms of one configuration, resident on the GPU."""
+
+    def __init__(self, cfg_id, batch=None):
+        import numpy as np
+        import torch
+
+        import workloads
+        from paper_1708_04728_amd import binding as B, graph as G
+        self.B, self.G, self.torch, self.np = B, G, torch, np
+        self.cfg_id = cfg_id
+        cfg = workloads.CONFIGS[cfg_id]
+        self.dtype = cfg["dtype"]
+        bf16 = self.dtype == "bf16"
+        self.x_host = workloads.make_input(cfg_id, batch)
+        self.batch, c_in = self.x_host.shape[0], self.x_host.shape[1]
+        self.x = G.to_device(self.x_host, self.dtype, nhwc=bf16)
+        self.stream = torch.cuda.current_stream()
+        self.forms = {}
+        for form in ("original", "slim"):
+            slim = form == "slim"
+            layers = cfg["original"] if isinstance(cfg[form], str) else cfg[form]
+            folded = slim and isinstance(cfg[form], str)
+            if folded:      # Lemma 2: BatchNorm folded into the filters by the library's host routine
+                src = workloads.make_params(cfg_id, "original")
+                params_host = []
+                for i in range(0, len(src), 2):
+                    cq, bq = src[i], src[i + 1]
+                    wf, bf = B.fold_bn(cq["w"], cq["b"], bq["gamma"], bq["beta"], bq["mean"], bq["var"],
+                                       float(np.float32(workloads.BN_EPS)))
+                    params_host.append({"w": workloads.round_to_bf16(wf) if bf16 else wf, "b": bf})
+            else:
+                params_host = workloads.make_params(cfg_id, form)
+            net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT) if slim else 0,
+                                    fuse_relu=slim, folded=folded, pack=self.dtype))
+            xd = B.desc(self.x)
+            y = G.empty_like_desc(net.output_desc(xd))
+            ws = torch.empty(max(net.workspace_bytes(xd), 256), dtype=torch.uint8, device="cuda")
+            self.forms[form] = dict(net=net, y=y, ws=ws, params=G.flat_params(params_host, self.dtype, pack=True),
+                                    layers=layers, params_host=params_host, folded=folded)
+
+    def run(self, form):
+        f = self.forms[form]
+        f["net"].fwd(self.x, f["params"], f["y"], f["ws"], self.stream)
+
+    def step(self):
+        self.run("original")
+        self.run("slim")
+
+    def trace(self, form):
+        self.B.trace_begin("", capacity=8192)
+        self.run(form)
+        return self.B.trace_end(8192)
+
+    def form_times(self, reps):
+        out = {}
+        for form in ("original", "slim"):
+            ts = []
+            for _ in range(reps):
+                e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
+                e0.record(self.stream)
+                self.run(form)
+                e1.record(self.stream)
+                e1.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            out[form] = (float(self.np.min(ts)), float(self.np.median(ts)))
+        return out
+
+    def summary(self, reps, warmup):
+        for _ in range(warmup):
+            self.step()
+        self.torch.cuda.synchronize()
+        fm = self.form_times(reps)
+        recs = self.trace("original")
+        tens = sum(r[6] for r in recs if is_tensor(r))
+        other = sum(r[6] for r in recs if not is_tensor(r))
+        return {"workload": WORKLOAD_NAMES[self.cfg_id], "batch": self.batch, "dtype": self.dtype,
+                "original_ms": round(fm["original"][0], 4), "slim_ms": round(fm["slim"][0], 4),
+                "original_images_per_s": round(self.batch / (fm["original"][0] * 1e-3), 1),
+                "slim_images_per_s": round(self.batch / (fm["slim"][0] * 1e-3), 1),
+                "slim_speedup": round(fm["original"][0] / fm["slim"][0], 3),
+                "pct_latency_non_tensor_original": round(100.0 * other / max(tens + other, 1e-9), 1)}
 
 
 def main():
@@ -41,6 +132,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--only", action="store_true", help="skip the summary of the other configurations")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path shards by batch with no communication, "
@@ -51,85 +143,44 @@ def main():
     import torch
 
     import workloads
-    from paper_1708_04728_amd import binding as B, graph as G
+    from paper_1708_04728_amd import binding as B
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     B.lib()                                    # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
-    cfg = workloads.CONFIGS[args.config]
-    dtype = cfg["dtype"]
-    x_host = workloads.make_input(args.config)
-    batch, c_in = x_host.shape[0], x_host.shape[1]
-    x = G.to_device(x_host, dtype)
-    stream = torch.cuda.current_stream()
-
-    forms = {}
-    for form in ("original", "slim"):
-        layers = cfg[form]
-        params_host = workloads.make_params(args.config, form)
-        slim = form == "slim"
-        net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT) if slim else 0,
-                                fuse_relu=slim, pack=True))
-        yd = net.output_desc(B.desc(x))
-        y = torch.empty((yd.n, yd.c, yd.h, yd.w), dtype=G.torch_dtype(dtype), device="cuda")
-        ws = torch.empty(max(net.workspace_bytes(B.desc(x)), 256), dtype=torch.uint8, device="cuda")
-        forms[form] = dict(net=net, y=y, ws=ws, params=G.flat_params(params_host, dtype, pack=True), layers=layers,
-                           params_host=params_host)
-
-    def run(form):
-        f = forms[form]
-        f["net"].fwd(x, f["params"], f["y"], f["ws"], stream)
-
-    def step():
-        run("original")
-        run("slim")
+    wl = Workload(args.config)
+    dtype, batch = wl.dtype, wl.batch
 
     for _ in range(args.warmup):
-        step()
+        wl.step()
     torch.cuda.synchronize()
 
     # ---- untimed traced pass: every kernel of one step, to find the dominant one and the per-kind split
-    B.trace_begin("", capacity=4096)
-    run("original")
-    n_orig = None
-    recs = B.trace_end()
-    n_orig = len(recs)
-    B.trace_begin("", capacity=4096)
-    run("slim")
-    recs_slim = B.trace_end()
-    all_recs = recs + recs_slim
-    dom = max(all_recs, key=lambda r: r[6])
+    recs = wl.trace("original")
+    recs_slim = wl.trace("slim")
+    dom = max(recs + recs_slim, key=lambda r: r[6])
     dom_is_conv = dom[0].startswith("conv")
 
     # ---- timed region: K steps, with one event pair around every launch of the dominant kernel
+    cap = 64 * args.steps + 16
     if dom_is_conv:
-        B.trace_begin(dom[0], dom[1], dom[2], dom[3], capacity=4 * args.steps + 16)
+        B.trace_begin(dom[0], dom[1], dom[2], dom[3], capacity=cap)
     else:
-        B.trace_begin(dom[0], capacity=64 * args.steps + 16)
+        B.trace_begin(dom[0], capacity=cap)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        wl.step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    dom_recs = [r for r in B.trace_end(64 * args.steps + 16) if r[:6] == dom[:6]]
+    dom_recs = [r for r in B.trace_end(cap) if r[:6] == dom[:6]]
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     dom_ms = float(np.mean([r[6] for r in dom_recs]))
 
     # ---- per-form times (events on the launch stream), best and median as the paper reports best runs
-    form_ms = {}
-    for form in ("original", "slim"):
-        ts = []
-        for _ in range(max(args.steps, 10)):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            run(form)
-            e1.record(stream)
-            e1.synchronize()
-            ts.append(e0.elapsed_time(e1))
-        form_ms[form] = (float(np.min(ts)), float(np.median(ts)))
+    form_ms = wl.form_times(max(args.steps, 10))
 
     # ---- roofline of the dominant kernel
     esz = 2 if dtype == "bf16" else 4
@@ -149,13 +200,13 @@ def main():
 
     # ---- per-kind split of one step: time in tensor layers vs non-tensor layers (Eq. (1))
     def split(rs):
-        conv = sum(r[6] for r in rs if r[0].startswith("conv") or r[0] == "fc")
-        other = sum(r[6] for r in rs if not (r[0].startswith("conv") or r[0] == "fc"))
+        conv = sum(r[6] for r in rs if is_tensor(r))
+        other = sum(r[6] for r in rs if not is_tensor(r))
         fl = sum(conv_flops(r) for r in rs if r[0].startswith("conv"))
         return conv, other, fl
     co, oo, fo = split(recs)
     cs, os_, fs = split(recs_slim)
-    nontensor_bytes = sum(2.0 * r[5] * esz for r in recs if not r[0].startswith("conv"))
+    nontensor_bytes = sum(2.0 * r[5] * esz for r in recs if not is_tensor(r))
 
     out = {
         "metric": "images/sec fwd (orig vs slim GoogLeNet), conv MFMA util %, non-tensor HBM GB/s",
@@ -165,8 +216,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[args.config], "batch": batch,
                    "filters": "pre-packed KRSC where the channel count allows",
-                   "original": "layer-by-layer (separate ReLU / pool / LRN / concat kernels)",
-                   "slim": "slimmed structure, ReLU and concat fused into the conv stores"},
+                   "original": "layer-by-layer (separate ReLU / pool / LRN / concat / BatchNorm kernels)",
+                   "slim": "slimmed structure, ReLU / concat / residual fused into the conv stores, BatchNorm folded"},
         "original_ms": {"best": round(form_ms["original"][0], 4), "median": round(form_ms["original"][1], 4)},
         "slim_ms": {"best": round(form_ms["slim"][0], 4), "median": round(form_ms["slim"][1], 4)},
         "original_images_per_s": round(batch / (form_ms["original"][0] * 1e-3), 1),
@@ -186,14 +237,15 @@ def main():
     # ---- CPU baseline: the fp64 oracle, as it stands, on the host cores (bounded sample, >= 10 s)
     if not args.no_cpu_baseline:
         import oracle
-        sample = {1: 1, 2: 32, 3: 4}[args.config]
-        xs = x_host[:sample]
-        oracle.forward(cfg["original"][:1], forms["original"]["params_host"], xs[:1])     # builds / warms the library
+        sample = {1: 1, 2: 32, 3: 4, 4: 4, 5: 4}[args.config]
+        xs = wl.x_host[:sample]
+        oracle.relu(xs[:1])                                   # builds / loads the C library
         reps = 0
         c0 = c1 = time.perf_counter()
         while c1 - c0 < 10.0:
             for form in ("original", "slim"):
-                oracle.forward(forms[form]["layers"], forms[form]["params_host"], xs)
+                f = wl.forms[form]
+                oracle.forward(f["layers"], f["params_host"], xs, fold="given" if f["folded"] else False)
             reps += 1
             c1 = time.perf_counter()
         try:
@@ -205,6 +257,18 @@ def main():
         out["cpu_baseline"] = {"value": round(sample * reps / (c1 - c0), 2), "unit": out["unit"], "cores": cores, "kind": "oracle",
                                "sample": "%d of %d images, one original + one slim forward, repeated %d times, fp64 "
                                          "nested loops, %.1f s" % (sample, batch, reps, c1 - c0)}
+
+    # ---- the other configurations, briefly (best of a few runs each)
+    if not args.only:
+        del wl
+        torch.cuda.empty_cache()
+        allc = {}
+        for cid in sorted(WORKLOAD_NAMES):
+            w2 = Workload(cid)
+            allc[str(cid)] = w2.summary(reps=10, warmup=3)
+            del w2
+            torch.cuda.empty_cache()
+        out["all_configs"] = allc
     print(json.dumps(out))
 
 

@@ -43,6 +43,7 @@ struct KArgs {
     ConvGeom g;
     int grid_m, grid_n;
     int x_bytes, w_bytes;
+    unsigned magic_rs, magic_s, magic_c;   // ceil(2^32 / d) for d = R*S, S, C (gather mode: k < 65536)
 };
 
 __device__ __forceinline__ void lds_barrier()
@@ -61,7 +62,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f)
     return u >> 16;
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK>
+// GATHER = false: the fast path described above (KRSC filters, C % 8 == 0).
+// GATHER = true:  any C and either filter order; k runs in the filters' own memory order, every
+//                 operand element is fetched by its own 2-byte buffer load after decoding (c, r, s),
+//                 eight of them are packed into the 16-byte LDS chunk.  Meant for the 3-channel
+//                 network input, where Kg = 147 is a handful of slices.
+template <int BM, int BN, int WGM, int WGN, int BK, bool GATHER>
 __global__ __launch_bounds__(NT) void conv_bf16_nhwc_kernel(const KArgs a)
 {
     constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -133,7 +139,54 @@ __global__ __launch_bounds__(NT) void conv_bf16_nhwc_kernel(const KArgs a)
         }
     };
     const bool ragged_c = (g.C % BK) != 0;
+    int ld_k0 = 0;                               // gather mode: first k of the next slice
+    auto load_u16 = [&](__amdgpu_buffer_rsrc_t r, int off) -> unsigned {
+        return (unsigned)(unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, 0);
+    };
+    auto divm = [](int v, int d, unsigned magic) { return d == 1 ? v : (int)__umulhi((unsigned)v, magic); };
     auto load_slice = [&]() {
+        if constexpr (GATHER) {
+            const int RS = g.R * g.S;
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i) {
+                unsigned e[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int k = ld_k0 + a_c8[i] + j;
+                    e[j] = load_u16(rw, (k < g.Kg && va[i] != OOB) ? va[i] + (ld_k0 + j) * 2 : OOB);
+                }
+                ra[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+            }
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                // decode the chunk's first k in the filters' order, then step element by element
+                const int k = ld_k0 + b_c8[i];
+                int c, r, sx;
+                if (g.w_krsc) {
+                    const int t = divm(k, g.C, a.magic_c);                   // k / C
+                    c = k - t * g.C;
+                    r = divm(t, g.S, a.magic_s);
+                    sx = t - r * g.S;
+                } else {
+                    c = divm(k, RS, a.magic_rs);                             // k / (R*S)
+                    const int t = k - c * RS;
+                    r = divm(t, g.S, a.magic_s);
+                    sx = t - r * g.S;
+                }
+                unsigned e[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const bool ok = k + j < g.Kg && (unsigned)(b_ih0[i] + r) < (unsigned)g.H && (unsigned)(b_iw0[i] + sx) < (unsigned)g.W;
+                    // b_base holds the offset of x[img][ih0][iw0][chunk's first channel]; remove that channel again
+                    e[j] = load_u16(rx, ok ? b_base[i] - b_c8[i] * 2 + ((r * g.W + sx) * g.C + c) * 2 : OOB);
+                    if (g.w_krsc) { if (++c == g.C) { c = 0; if (++sx == g.S) { sx = 0; ++r; } } }
+                    else { if (++sx == g.S) { sx = 0; if (++r == g.R) { r = 0; ++c; } } }
+                }
+                rb[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+            }
+            ld_k0 += BK;
+            return;
+        }
         if (ld_c0 == 0) tap_offsets();
         const int tap = ld_r * g.S + ld_s;
         const int sa = (tap * g.C + ld_c0) * 2;
@@ -172,7 +225,7 @@ __global__ __launch_bounds__(NT) void conv_bf16_nhwc_kernel(const KArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nslices = g.R * g.S * ((g.C + BK - 1) / BK);
+    const int nslices = GATHER ? (g.Kg + BK - 1) / BK : g.R * g.S * ((g.C + BK - 1) / BK);
     load_slice();
     store_slice(0);
     if (1 < nslices) load_slice();
@@ -299,13 +352,13 @@ __global__ __launch_bounds__(256) void conv_bf16_gather_kernel(const GArgs a)
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK>
+template <int BM, int BN, int WGM, int WGN, int BK, bool GATHER = false>
 int launch_tile(const KArgs& base, hipStream_t st)
 {
     KArgs a = base;
     a.grid_m = (a.g.K + BM - 1) / BM;
     a.grid_n = (a.g.Ng + BN - 1) / BN;
-    hipLaunchKernelGGL((conv_bf16_nhwc_kernel<BM, BN, WGM, WGN, BK>), dim3((unsigned)(a.grid_m * a.grid_n)), dim3(NT), 0, st, a);
+    hipLaunchKernelGGL((conv_bf16_nhwc_kernel<BM, BN, WGM, WGN, BK, GATHER>), dim3((unsigned)(a.grid_m * a.grid_n)), dim3(NT), 0, st, a);
     return check_launch("conv_bf16");
 }
 
@@ -321,11 +374,21 @@ int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, co
         a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g;
         a.grid_m = a.grid_n = 0;
         a.x_bytes = (int)xb; a.w_bytes = (int)wb;
+        a.magic_rs = a.magic_s = a.magic_c = 0;
         const bool deep = g.C % 64 == 0 || g.C > 64;
         if (g.K <= 32) return deep ? launch_tile<32, 128, 1, 4, 64>(a, st) : launch_tile<32, 128, 1, 4, 32>(a, st);
         if (g.K <= 64 || (g.K + 63) / 64 * 64 < (g.K + 127) / 128 * 128)
             return deep ? launch_tile<64, 128, 2, 2, 64>(a, st) : launch_tile<64, 128, 2, 2, 32>(a, st);
         return deep ? launch_tile<128, 128, 2, 2, 64>(a, st) : launch_tile<128, 128, 2, 2, 32>(a, st);
+    }
+    if (g.nhwc && g.Kg < 65536 && xb < (1ull << 31) && wb < (1ull << 31)) {
+        KArgs a;
+        a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g;
+        a.grid_m = a.grid_n = 0;
+        a.x_bytes = (int)xb; a.w_bytes = (int)wb;
+        auto magic = [](int d) { return (unsigned)((0x100000000ull + d - 1) / d); };
+        a.magic_rs = magic(g.R * g.S); a.magic_s = magic(g.S); a.magic_c = magic(g.C);
+        return g.K <= 32 ? launch_tile<32, 128, 1, 4, 32, true>(a, st) : launch_tile<64, 128, 2, 2, 32, true>(a, st);
     }
     GArgs a;
     a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g; a.w_krsc = g.w_krsc;

@@ -69,6 +69,14 @@ def test_conv2d_bf16_fallback_paths():
     B.conv2d_fwd(gpu_nhwc(x, "bf16"), B.conv_desc(64, 3, 7, 7, 2, 3, True), gpu(w, "bf16"), gpu(b), y)
     torch.cuda.synchronize()
     assert rel_err(host_nhwc(y), ref) < TOL_BF16
+    for (N, C, H, W, K, R, S, stride, pad) in [(2, 3, 224, 224, 64, 7, 7, 4, 3), (1, 5, 19, 23, 24, 3, 5, 2, 1), (3, 1, 9, 9, 40, 1, 1, 1, 0)]:
+        x2 = _vals(rng, (N, C, H, W), "bf16")
+        w2 = workloads.round_to_bf16(_vals(rng, (K, C, R, S), "f32") * np.float32(0.2))
+        ref2 = oracle.conv2d(x2, w2, None, stride, (pad, pad))
+        yy = empty_nhwc(ref2.shape, "bf16")
+        B.conv2d_fwd(gpu_nhwc(x2, "bf16"), B.conv_desc(K, C, R, S, stride, pad), gpu(w2, "bf16"), None, yy)
+        torch.cuda.synchronize()
+        assert rel_err(host_nhwc(yy), ref2) < TOL_BF16
     y2 = torch.full(ref.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
     B.conv2d_fwd(gpu(x, "bf16"), B.conv_desc(64, 3, 7, 7, 2, 3, True), gpu(w, "bf16"), gpu(b), y2)
     torch.cuda.synchronize()
