@@ -50,55 +50,52 @@ int relu_launch(const void* a, const void* b, void* y, size_t count, hipStream_t
 __device__ __forceinline__ float pow_neg_beta(float s, float beta, bool b075)
 {
     if (b075) {
-        const float r = 1.0f / sqrtf(s);
-        return r * sqrtf(r);
+        const float r = __builtin_amdgcn_rsqf(s);          // 1 ulp hardware approximations: s >= k > 0 here
+        return r * __builtin_amdgcn_sqrtf(r);
     }
     return powf(s, -beta);
 }
 
 // One thread owns V adjacent pixels (one 16-byte vector, or one element when V == 1) of one image and a
-// run of channels [c0, c1); it slides a window of NL channels held in registers down the channel
-// axis, so every input element is loaded once per run (plus NL-1 halo loads per run).
-template <typename T, int V, int NL>
+// run of CH channels.  It first issues all CH + NL - 1 loads of the run and its halo (independent, so
+// they overlap in the memory system), then slides the window of NL channels over the registers.
+template <typename T, int V, int NL, int CH>
 __global__ __launch_bounds__(256) void lrn_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int HW, int HWv,
-                                                  int chunk, int nchunks, float a_over_n, float beta, float k, int b075)
+                                                  int nruns, float a_over_n, float beta, float k, int b075)
 {
     const int pv = blockIdx.x * blockDim.x + threadIdx.x;
     if (pv >= HWv) return;
-    const int n = blockIdx.y / nchunks, ch = blockIdx.y - n * nchunks;
-    const int c0 = ch * chunk, c1 = min(C, c0 + chunk);
+    const int n = blockIdx.y / nruns, run = blockIdx.y - n * nruns;
+    const int c0 = run * CH;
     constexpr int LO = NL / 2;                    // window of channel c = [c - LO, c - LO + NL)
     const T* xb = x + (size_t)n * C * HW + (size_t)pv * V;
     T* yb = y + (size_t)n * C * HW + (size_t)pv * V;
 
-    float win[NL][V];
-    auto fetch = [&](int c, float* v) {
+    float v[CH + NL - 1][V];                      // channels c0 - LO .. c0 + CH + NL - 2 - LO
+#pragma unroll
+    for (int i = 0; i < CH + NL - 1; ++i) {
+        const int c = c0 - LO + i;
         if (c >= 0 && c < C) {
-            if constexpr (V == 1) v[0] = Store<T>::ld(xb + (size_t)c * HW);
-            else Store<T>::ldv(xb + (size_t)c * HW, v);
+            if constexpr (V == 1) v[i][0] = Store<T>::ld(xb + (size_t)c * HW);
+            else Store<T>::ldv(xb + (size_t)c * HW, v[i]);
         } else {
 #pragma unroll
-            for (int j = 0; j < V; ++j) v[j] = 0.f;
+            for (int j = 0; j < V; ++j) v[i][j] = 0.f;
         }
-    };
+    }
 #pragma unroll
-    for (int i = 0; i < NL - 1; ++i) fetch(c0 - LO + i, win[i + 1]);   // slots 1..NL-1; slot 0 is dropped first
-    for (int c = c0; c < c1; ++c) {
-#pragma unroll
-        for (int i = 0; i < NL - 1; ++i)
-#pragma unroll
-            for (int j = 0; j < V; ++j) win[i][j] = win[i + 1][j];
-        fetch(c - LO + NL - 1, win[NL - 1]);
+    for (int i = 0; i < CH; ++i) {
+        if (c0 + i >= C) break;
         float o[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) {
             float ss = 0.f;
 #pragma unroll
-            for (int i = 0; i < NL; ++i) ss = fmaf(win[i][j], win[i][j], ss);
-            o[j] = win[LO][j] * pow_neg_beta(fmaf(a_over_n, ss, k), beta, b075);
+            for (int w = 0; w < NL; ++w) ss = fmaf(v[i + w][j], v[i + w][j], ss);
+            o[j] = v[i + LO][j] * pow_neg_beta(fmaf(a_over_n, ss, k), beta, b075);
         }
-        if constexpr (V == 1) Store<T>::st(yb + (size_t)c * HW, o[0]);
-        else Store<T>::stv(yb + (size_t)c * HW, o);
+        if constexpr (V == 1) Store<T>::st(yb + (size_t)(c0 + i) * HW, o[0]);
+        else Store<T>::stv(yb + (size_t)(c0 + i) * HW, o);
     }
 }
 
@@ -134,62 +131,112 @@ int lrn_launch(const void* x, void* y, int N, int C, int HW, const dr_lrn& p, hi
         return check_launch("lrn");
     }
     constexpr int VN = Store<T>::VN;
+    constexpr int CH = 64 / VN;                   // channels per run: (CH + 4) * VN registers of window
     const bool vec = (HW % VN == 0) && aligned16(x) && aligned16(y);
     const int HWv = vec ? HW / VN : HW;
-    if (N > 8192) return fail(DR_ERR_UNSUPPORTED, "lrn: batch %d exceeds 8192", N);
-    // split the channel axis into runs until the launch has enough threads to fill the device
-    const long want = 256L * 2048;
-    int nchunks = (int)((want + (long)N * HWv - 1) / ((long)N * HWv));
-    if (nchunks > C / 16) nchunks = C / 16;   // runs of >= 16 channels keep the halo re-reads <= 25%
-    if (nchunks < 1) nchunks = 1;
-    const int chunk = (C + nchunks - 1) / nchunks;
-    nchunks = (C + chunk - 1) / chunk;
-    const dim3 grid((HWv + 255) / 256, (unsigned)(N * nchunks));
+    const int nruns = (C + CH - 1) / CH;
+    if ((long)N * nruns > 65535) return fail(DR_ERR_UNSUPPORTED, "lrn: batch %d x %d channel runs exceeds the grid limit", N, nruns);
+    const dim3 grid((HWv + 255) / 256, (unsigned)(N * (vec ? nruns : (C + 15) / 16)));
     const int b075 = p.beta == 0.75f;
+    if (vec && (long)N * HWv * nruns < 65536 && (long)N * ((C + 3) / 4) <= 65535) {
+        // small tensor: shorter runs (more halo re-reads, served by the caches) to put more waves to work
+        const int nr4 = (C + 3) / 4;
+        hipLaunchKernelGGL((lrn_kernel<T, VN, 5, 4>), dim3((HWv + 255) / 256, (unsigned)(N * nr4)), dim3(256), 0, st, (const T*)x,
+                           (T*)y, C, HW, HWv, nr4, a_over_n, p.beta, p.k, b075);
+        return check_launch("lrn");
+    }
     if (vec)
-        hipLaunchKernelGGL((lrn_kernel<T, VN, 5>), grid, dim3(256), 0, st, (const T*)x, (T*)y, C, HW, HWv, chunk, nchunks,
-                           a_over_n, p.beta, p.k, b075);
+        hipLaunchKernelGGL((lrn_kernel<T, VN, 5, CH>), grid, dim3(256), 0, st, (const T*)x, (T*)y, C, HW, HWv, nruns, a_over_n,
+                           p.beta, p.k, b075);
     else
-        hipLaunchKernelGGL((lrn_kernel<T, 1, 5>), grid, dim3(256), 0, st, (const T*)x, (T*)y, C, HW, HWv, chunk, nchunks,
+        hipLaunchKernelGGL((lrn_kernel<T, 1, 5, 16>), grid, dim3(256), 0, st, (const T*)x, (T*)y, C, HW, HWv, (C + 15) / 16,
                            a_over_n, p.beta, p.k, b075);
     return check_launch("lrn");
 }
 
 // ---- pooling --------------------------------------------------------------------------------------------
-// One output element per thread, lanes along q.  AVG = false: maximum over the window clipped to the
-// input;  AVG = true: mean over the full window (no padding allowed).
+// A workgroup computes PR output rows of one (n, c) plane.  The input rows those windows touch are one
+// contiguous range of the plane: it is copied to LDS with coalesced loads (every input element is
+// fetched from global memory once, all loads of a workgroup in flight together), then each thread
+// reduces its windows out of LDS.  AVG = false: maximum over the window clipped to the input
+// (padding never wins);  AVG = true: mean over the full window (no padding allowed).
+constexpr int POOL_LDS_BYTES = 32 * 1024;
+
 template <typename T, bool AVG>
 __global__ __launch_bounds__(256) void pool_kernel(const T* __restrict__ x, T* __restrict__ y, int H, int W, int P, int Q,
-                                                   size_t total, dr_pool p)
+                                                   int PR, int pgroups, float inv_q, dr_pool p)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        const int q = (int)(i % Q);
-        const size_t t = i / Q;
-        const int pp = (int)(t % P);
-        const size_t nc = t / P;
-        const int h0 = pp * p.stride_h - p.pad_h, w0 = q * p.stride_w - p.pad_w;
+    extern __shared__ __attribute__((aligned(16))) unsigned char pool_lds[];   // (PR - 1) * stride + kh rows of W elements
+    T* tile = reinterpret_cast<T*>(pool_lds);
+    const unsigned plane = blockIdx.x / (unsigned)pgroups;
+    const int p0 = (int)(blockIdx.x - plane * (unsigned)pgroups) * PR;
+    const int p1 = min(p0 + PR, P);
+    const int h_lo = max(p0 * p.stride_h - p.pad_h, 0);
+    const int h_hi = min((p1 - 1) * p.stride_h - p.pad_h + p.kh, H);      // exclusive
+    const T* src = x + (size_t)plane * H * W + (size_t)h_lo * W;
+    const int count = (h_hi - h_lo) * W;
+    for (int base = 0; base < count; base += 256 * 8) {      // 8 independent loads in flight per thread
+        T r[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = base + j * 256 + threadIdx.x;
+            r[j] = i < count ? src[i] : T(0);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = base + j * 256 + threadIdx.x;
+            if (i < count) tile[i] = r[j];
+        }
+    }
+    __syncthreads();
+    T* yb = y + ((size_t)plane * P + p0) * Q;
+    const int outs = (p1 - p0) * Q;
+    for (int i = threadIdx.x; i < outs; i += 256) {
+        int pr = (int)(((float)i + 0.5f) * inv_q);                          // i / Q for i < 2^20
+        int q = i - pr * Q;
+        if (q < 0) { --pr; q += Q; } else if (q >= Q) { ++pr; q -= Q; }
+        const int h0 = (p0 + pr) * p.stride_h - p.pad_h, w0 = q * p.stride_w - p.pad_w;
         const int ha = max(h0, 0), hb = min(h0 + p.kh, H);
         const int wa = max(w0, 0), wb = min(w0 + p.kw, W);
-        const T* xb = x + nc * H * W;
         float m = AVG ? 0.f : -INFINITY;
-        for (int h = ha; h < hb; ++h)
-            for (int w = wa; w < wb; ++w) {
-                const float v = Store<T>::ld(xb + h * W + w);
-                m = AVG ? m + v : fmaxf(m, v);
-            }
+        if (p.kh == 3 && p.kw == 3 && hb - ha == 3 && wb - wa == 3) {
+            // whole 3x3 window inside the input (all but the edge windows): straight-line code
+            const T* t = &tile[(ha - h_lo) * W + wa];
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {
+                    const float v = Store<T>::ld(t + r * W + c);
+                    m = AVG ? m + v : fmaxf(m, v);
+                }
+        } else {
+            for (int h = ha; h < hb; ++h)
+                for (int w = wa; w < wb; ++w) {
+                    const float v = Store<T>::ld(&tile[(h - h_lo) * W + w]);
+                    m = AVG ? m + v : fmaxf(m, v);
+                }
+        }
         if (AVG) m /= (float)(p.kh * p.kw);
-        Store<T>::st(y + i, m);
+        Store<T>::st(yb + i, m);
     }
 }
 
 template <typename T, bool AVG>
 int pool_launch(const void* x, void* y, int NC, int H, int W, int P, int Q, const dr_pool& p, hipStream_t st)
 {
-    const size_t total = (size_t)NC * P * Q;
-    if (total == 0) return DR_OK;
-    hipLaunchKernelGGL((pool_kernel<T, AVG>), dim3(blocks_for(total, 256, 256 * 64)), dim3(256), 0, st, (const T*)x, (T*)y,
-                       H, W, P, Q, total, p);
+    if ((size_t)NC * P * Q == 0) return DR_OK;
+    // output rows per workgroup: as many as fit the LDS tile, at most ~4 outputs per thread
+    const int rows_fit = (int)(POOL_LDS_BYTES / sizeof(T)) / W;
+    if (rows_fit < p.kh) return fail(DR_ERR_UNSUPPORTED, "pooling: rows of %d elements do not fit the LDS tile", W);
+    int PR = (rows_fit - p.kh) / p.stride_h + 1;
+    const int cap = (1024 + Q - 1) / Q;
+    if (PR > cap) PR = cap;
+    if (PR > P) PR = P;
+    const int pgroups = (P + PR - 1) / PR;
+    if ((double)NC * pgroups >= 2147483648.0 || (double)PR * Q >= 1048576.0) return fail(DR_ERR_UNSUPPORTED, "pooling: tensor too large");
+    const size_t lds = (size_t)((PR - 1) * p.stride_h + p.kh) * W * sizeof(T);
+    hipLaunchKernelGGL((pool_kernel<T, AVG>), dim3((unsigned)(NC * pgroups)), dim3(256), lds, st, (const T*)x, (T*)y, H, W, P, Q, PR,
+                       pgroups, 1.0f / (float)Q, p);
     return check_launch(AVG ? "avgpool" : "maxpool");
 }
 

@@ -11,40 +11,74 @@ namespace {
 
 // ---- pooling ------------------------------------------------------------------------------------------
 // V = elements per lane (a 16-byte vector, or 1 when C is not a multiple of the vector width).
+// A workgroup of BX x BY threads: BX (a power of two >= C / V, at most 256) lanes walk the channel
+// groups of a pixel, the BY rows of the workgroup take consecutive output pixels of one output row
+// (n, p); no per-element division.
 template <typename T, int V, bool AVG>
 __global__ __launch_bounds__(256) void pool_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int H, int W, int P,
-                                                        int Q, size_t total, dr_pool p)
+                                                        int Q, int qgroups, int bx_log2, dr_pool p)
 {
     const int CV = C / V;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        const int cv = (int)(i % CV);
-        size_t t = i / CV;
-        const int q = (int)(t % Q); t /= Q;
-        const int pp = (int)(t % P);
-        const size_t n = t / P;
-        const int h0 = pp * p.stride_h - p.pad_h, w0 = q * p.stride_w - p.pad_w;
-        const int ha = max(h0, 0), hb = min(h0 + p.kh, H);
-        const int wa = max(w0, 0), wb = min(w0 + p.kw, W);
+    const int bx = 1 << bx_log2, by = 256 >> bx_log2;
+    const int tx = threadIdx.x & (bx - 1), ty = threadIdx.x >> bx_log2;
+    const unsigned row = blockIdx.x / (unsigned)qgroups;          // n * P + p
+    const int qg = (int)(blockIdx.x - row * (unsigned)qgroups);
+    const unsigned n = row / (unsigned)P;
+    const int pp = (int)(row - n * (unsigned)P);
+    const int q = qg * by + ty;
+    if (q >= Q) return;
+    const int h0 = pp * p.stride_h - p.pad_h, w0 = q * p.stride_w - p.pad_w;
+    const int ha = max(h0, 0), hb = min(h0 + p.kh, H);
+    const int wa = max(w0, 0), wb = min(w0 + p.kw, W);
+    const T* xb = x + (size_t)n * H * W * C;
+    T* yb = y + ((size_t)row * Q + q) * C;
+    for (int cv = tx; cv < CV; cv += bx) {
         float m[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) m[j] = AVG ? 0.f : -INFINITY;
-        for (int h = ha; h < hb; ++h)
-            for (int w = wa; w < wb; ++w) {
-                const T* src = x + ((n * H + h) * W + w) * C + (size_t)cv * V;
-                float v[V];
-                if constexpr (V == 1) v[0] = Store<T>::ld(src);
-                else Store<T>::ldv(src, v);
+        if (hb - ha == 3 && wb - wa == 3) {
+            // a full 3x3 window (every window of the workloads but the edge ones): nine independent loads
+            const T* src = xb + ((size_t)ha * W + wa) * C + cv * V;
+            float v[9][V];
 #pragma unroll
-                for (int j = 0; j < V; ++j) m[j] = AVG ? m[j] + v[j] : fmaxf(m[j], v[j]);
-            }
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {
+                    if constexpr (V == 1) v[r * 3 + c][0] = Store<T>::ld(src + ((size_t)r * W + c) * C);
+                    else Store<T>::ldv(src + ((size_t)r * W + c) * C, v[r * 3 + c]);
+                }
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+#pragma unroll
+                for (int j = 0; j < V; ++j) m[j] = AVG ? m[j] + v[t][j] : fmaxf(m[j], v[t][j]);
+        } else {
+            // any window: walk its rows, up to 8 independent loads in flight per row segment
+            for (int h = ha; h < hb; ++h)
+                for (int w = wa; w < wb; w += 8) {
+                    const T* src = xb + ((size_t)h * W + w) * C + cv * V;
+                    float v[8][V];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        if (w + t < wb) {
+                            if constexpr (V == 1) v[t][0] = Store<T>::ld(src + (size_t)t * C);
+                            else Store<T>::ldv(src + (size_t)t * C, v[t]);
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < V; ++j) v[t][j] = AVG ? 0.f : -INFINITY;
+                        }
+                    }
+#pragma unroll
+                    for (int t = 0; t < 8; ++t)
+#pragma unroll
+                        for (int j = 0; j < V; ++j) m[j] = AVG ? m[j] + v[t][j] : fmaxf(m[j], v[t][j]);
+                }
+        }
         if (AVG) {
 #pragma unroll
             for (int j = 0; j < V; ++j) m[j] /= (float)(p.kh * p.kw);
         }
-        T* dst = y + i * V;
-        if constexpr (V == 1) Store<T>::st(dst, m[0]);
-        else Store<T>::stv(dst, m);
+        if constexpr (V == 1) Store<T>::st(yb + cv, m[0]);
+        else Store<T>::stv(yb + cv * V, m);
     }
 }
 
@@ -52,11 +86,16 @@ template <typename T>
 int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, bool avg, hipStream_t st)
 {
     constexpr int VN = Store<T>::VN;
+    if (tensor_elems(yd) == 0) return DR_OK;
     const bool vec = xd.c % VN == 0 && aligned16(x) && aligned16(y);
-    const size_t total = (size_t)yd.n * yd.h * yd.w * (vec ? yd.c / VN : yd.c);
-    if (total == 0) return DR_OK;
-    const dim3 grid(blocks_for(total, 256, 256 * 64)), block(256);
-#define DR_POOL(V, AVG) hipLaunchKernelGGL((pool_nhwc_kernel<T, V, AVG>), grid, block, 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, total, p)
+    const int cv = vec ? xd.c / VN : xd.c;
+    int bx_log2 = 0;
+    while ((1 << bx_log2) < cv && bx_log2 < 8) ++bx_log2;
+    const int by = 256 >> bx_log2;
+    const int qgroups = (yd.w + by - 1) / by;
+    if ((double)yd.n * yd.h * qgroups >= 2147483648.0) return fail(DR_ERR_UNSUPPORTED, "pooling: tensor too large");
+    const dim3 grid((unsigned)(yd.n * yd.h * qgroups)), block(256);
+#define DR_POOL(V, AVG) hipLaunchKernelGGL((pool_nhwc_kernel<T, V, AVG>), grid, block, 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, qgroups, bx_log2, p)
     if (vec) { if (avg) DR_POOL(VN, true); else DR_POOL(VN, false); }
     else { if (avg) DR_POOL(1, true); else DR_POOL(1, false); }
 #undef DR_POOL
@@ -66,9 +105,9 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
 // ---- LRN -------------------------------------------------------------------------------------------------
 __device__ __forceinline__ float pow_neg_beta(float s, float beta, bool b075)
 {
-    if (b075) {                       // s^-0.75 = rsqrt(s) * sqrt(rsqrt(s))
-        const float r = 1.0f / sqrtf(s);
-        return r * sqrtf(r);
+    if (b075) {                       // s^-0.75 = rsqrt(s) * sqrt(rsqrt(s)), 1 ulp hardware approximations
+        const float r = __builtin_amdgcn_rsqf(s);
+        return r * __builtin_amdgcn_sqrtf(r);
     }
     return powf(s, -beta);
 }
@@ -198,26 +237,42 @@ int concat_launch(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, h
 }
 
 // ---- BatchNorm + Scale ----------------------------------------------------------------------------------
+// BX (power of two >= C / V) lanes own one channel group each and keep its scale and shift in
+// registers; the BY rows of the workgroup stride over the pixels.
 template <typename T, int V>
-__global__ __launch_bounds__(256) void bn_nhwc_kernel(const T* x, T* y, int C, size_t total, const float* __restrict__ gamma,
-                                                      const float* __restrict__ beta, const float* __restrict__ mean,
-                                                      const float* __restrict__ var, float eps, int relu)
+__global__ __launch_bounds__(256) void bn_nhwc_kernel(const T* x, T* y, int C, size_t pixels, int bx_log2,
+                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                      const float* __restrict__ mean, const float* __restrict__ var, float eps,
+                                                      int relu)
 {
     const int CV = C / V;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        const int c0 = (int)(i % CV) * V;
-        float v[V];
-        if constexpr (V == 1) v[0] = Store<T>::ld(x + i);
-        else Store<T>::ldv(x + i * V, v);
+    const int bx = 1 << bx_log2, by = 256 >> bx_log2;
+    const int tx = threadIdx.x & (bx - 1), ty = threadIdx.x >> bx_log2;
+    for (int cv = tx; cv < CV; cv += bx) {
+        float sc[V], mu[V], sh[V];
 #pragma unroll
         for (int j = 0; j < V; ++j) {
-            const int c = c0 + j;
-            v[j] = gamma[c] * ((v[j] - mean[c]) * (1.0f / sqrtf(var[c] + eps))) + beta[c];
-            if (relu) v[j] = fmaxf(v[j], 0.f);
+            const int c = cv * V + j;
+            sc[j] = 1.0f / sqrtf(var[c] + eps);
+            mu[j] = mean[c];
+            sh[j] = beta[c];
         }
-        if constexpr (V == 1) Store<T>::st(y + i, v[0]);
-        else Store<T>::stv(y + i * V, v);
+        float ga[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) ga[j] = gamma[cv * V + j];
+        for (size_t pix = (size_t)blockIdx.x * by + ty; pix < pixels; pix += (size_t)gridDim.x * by) {
+            float v[V];
+            const size_t off = pix * C + (size_t)cv * V;
+            if constexpr (V == 1) v[0] = Store<T>::ld(x + off);
+            else Store<T>::ldv(x + off, v);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                v[j] = ga[j] * ((v[j] - mu[j]) * sc[j]) + sh[j];
+                if (relu) v[j] = fmaxf(v[j], 0.f);
+            }
+            if constexpr (V == 1) Store<T>::st(y + off, v[0]);
+            else Store<T>::stv(y + off, v);
+        }
     }
 }
 
@@ -226,12 +281,16 @@ int bn_launch(const dr_tensor& d, const void* x, void* y, const float* gamma, co
               const float* var, float eps, int relu, hipStream_t st)
 {
     constexpr int VN = Store<T>::VN;
+    if (tensor_elems(d) == 0) return DR_OK;
     const bool vec = d.c % VN == 0 && aligned16(x) && aligned16(y);
-    const size_t total = tensor_elems(d) / (vec ? VN : 1);
-    if (total == 0) return DR_OK;
-    const dim3 grid(blocks_for(total, 256, 256 * 64)), block(256);
-    if (vec) hipLaunchKernelGGL((bn_nhwc_kernel<T, VN>), grid, block, 0, st, (const T*)x, (T*)y, d.c, total, gamma, beta, mean, var, eps, relu);
-    else hipLaunchKernelGGL((bn_nhwc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, d.c, total, gamma, beta, mean, var, eps, relu);
+    const int cv = vec ? d.c / VN : d.c;
+    int bx_log2 = 0;
+    while ((1 << bx_log2) < cv && bx_log2 < 8) ++bx_log2;
+    const int by = 256 >> bx_log2;
+    const size_t pixels = (size_t)d.n * d.h * d.w;
+    const dim3 grid(blocks_for(pixels, by * 4, 256 * 32)), block(256);
+    if (vec) hipLaunchKernelGGL((bn_nhwc_kernel<T, VN>), grid, block, 0, st, (const T*)x, (T*)y, d.c, pixels, bx_log2, gamma, beta, mean, var, eps, relu);
+    else hipLaunchKernelGGL((bn_nhwc_kernel<T, 1>), grid, block, 0, st, (const T*)x, (T*)y, d.c, pixels, bx_log2, gamma, beta, mean, var, eps, relu);
     return check_launch("bn");
 }
 
