@@ -1,0 +1,480 @@
+// bf16 convolution forward (Eq. (7): Y_j = (W * X)_j + B_j), the main kernel: channels-last (NHWC)
+// activations, KRSC filters, fp32 accumulation on the gfx950 matrix cores, operands streamed from
+// global memory straight into LDS.
+//
+//   D[m][n] = sum_k A[m][k] * B[k][n]     m = output channel, n = (image, p, q), k = (r, s, c)
+//
+// Contraction order.  For a fixed filter row r the S*C values (s, c) of the filters are contiguous in
+// KRSC memory, and so are the S*C activations x[img][ih0 + r][iw0 .. iw0 + S - 1][0 .. C - 1] that they
+// multiply.  The kernel walks k as R such runs, 64 elements (eight 16-byte chunks) per slice; a chunk
+// never straddles a pixel because C is a multiple of 8.  Lanes whose chunk lies in the zero padding,
+// beyond the end of the run, or in a row / filter beyond the tensor get a buffer offset outside
+// the descriptor's range: the hardware then delivers zeros, so the loop has no branches.
+//   TAP = true  (C % 64 == 0): a slice lies inside one tap, the padding test is wave-uniform per
+//        tap and is hoisted out of the slice loop; only a scalar offset moves from slice to slice.
+//   TAP = false: the tap of a lane's chunk differs from lane to lane; it is looked up per slice in
+//        per-row validity bit masks (a few vector-ALU instructions per load).
+//
+// Data movement.  Every operand chunk is fetched by a 16-byte buffer load that writes LDS directly
+// (no register staging): lane l of a wave fills slot l of a 1 KiB block, i.e. 8 rows x 8 chunks of a
+// 128-byte-per-row tile.  Which chunk of its row a lane fetches is permuted (chunk ^ ((row >> 1) & 7))
+// so that the MFMA operand reads (32 rows x one 16-byte chunk per half-wave) hit all 64 banks evenly.
+// The tiles live in a ring of NS stages; loads run NS - 1 slices ahead of the matrix cores, across
+// tile boundaries: a workgroup is persistent, keeps one block of output channels and walks pixel
+// tiles nt, nt + stride, ... so that the store of one tile overlaps the loads of the next.  One barrier
+// per slice.  The compiler makes every LDS read it knows of wait for ALL outstanding loads that write
+// LDS, which would empty the ring once per slice; the operand reads are therefore issued as inline
+// assembly with their own lgkmcnt waits, and the bias lives in registers rather than in LDS.
+//
+// Store.  Accumulator register v of a 32x32 tile holds row 8 (v / 4) + 4 half + v % 4 of column
+// lane % 32.  One v_permlane32_swap per register pair gives every lane 8 consecutive output channels
+// of its pixel; bias, residual and ReLU are applied in fp32, the result is rounded to bf16 (nearest
+// even) once and written as one 16-byte store.
+#include "dr_internal.h"
+#ifdef DR_TUNE
+#include <stdlib.h>
+#endif
+
+namespace dr {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr;
+
+constexpr int NT = 256;
+constexpr int OOB = (int)0x80000000;
+
+struct DArgs {
+    const uint16_t* x;
+    const uint16_t* w;
+    const float* bias;
+    const uint16_t* res;
+    uint16_t* y;
+    ConvGeom g;
+    int grid_m, grid_n;       // tiles along m (channel blocks) and along n (pixel tiles)
+    int x_bytes, w_bytes;
+    int c8;                   // C / 8: chunks per tap
+    int run_chunks;           // S * C / 8: chunks per filter row
+    int slices_per_run;       // ceil(run_chunks / 8)
+    unsigned magic_c8;        // ceil(2^32 / c8)
+    unsigned long long m_pq, m_q;   // ceil(2^40 / (P*Q)), ceil(2^40 / Q)
+    int vec_ok;               // 16-byte stores / bias / residual accesses are aligned
+};
+
+// Workgroup barrier between the slices.  A fence would make the compiler wait for every outstanding
+// load that writes LDS (vmcnt(0)), which is exactly the prefetch this kernel keeps in flight, so the
+// ordering is spelled out instead: the compiler may not move memory accesses across either side
+// (the empty asm statements), this wave's own LDS reads have returned (lgkmcnt(0)), and the arrival of
+// the operand loads is awaited by the caller with wait_vmcnt.
+__device__ __forceinline__ void ring_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0); vmcnt and expcnt left at their maxima
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// One 16-byte buffer load per lane that writes LDS directly: lane l of the wave fills bytes
+// [16 l, 16 l + 16) of the 1 KiB block at `lds` (wave-uniform); lanes whose voff lies outside the
+// descriptor's range write zeros.  (Only the device pass may see the builtin: in the host pass it
+// fails to type-check without a diagnostic and takes the kernel's launch stub with it.)
+__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t r, unsigned char* lds, int voff, int soff)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)lds, 16, voff, soff, 0, 0);
+#endif
+}
+
+// LDS reads the compiler does not see (see the header): the data is valid after wait_lgkm + touch.
+template <int OFF>
+__device__ __forceinline__ u32x4 ds_read16(unsigned addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_lgkm()
+{
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void touch(u32x4& v) { asm volatile("" : "+v"(v)); }
+
+// two fp32 -> two bf16 (round to nearest even, NaN stays NaN) in one 32-bit word: v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+}
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) { return pack_bf16x2(f, 0.f) & 0xFFFFu; }
+
+// v / d for 0 <= v < 2^24 and 1 <= d <= 2^16, exact: (v * ceil(2^40 / d)) >> 40.  With m = (2^40 + e) / d,
+// 0 <= e < d, the product is v / d + v e / (d 2^40) and the second term is below 2^-16 <= 1 / d.
+__device__ __forceinline__ int div_small(int v, unsigned long long m)
+{
+    return (int)(((unsigned long long)(unsigned)v * m) >> 40);
+}
+
+// bits lo..hi set (hi < lo: none); lo, hi in 0..15
+__device__ __forceinline__ unsigned bit_range(int lo, int hi) { return hi >= lo ? (2u << hi) - (1u << lo) : 0u; }
+
+template <int TM, int TN, int WGM, int WGN, int NS, bool TAP>
+__global__ __launch_bounds__(NT) void conv_bf16_dma_kernel(const DArgs a)
+{
+    constexpr int WM = TM * 32, WN = TN * 32, BM = WGM * WM, BN = WGN * WN;
+    constexpr int A_PER = BM / 32, B_PER = BN / 32, L = A_PER + B_PER;   // loads per lane and slice
+    constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
+    static_assert(WGM * WGN == 4 && NS >= 2 && (NS - 2) * L < 64, "bad configuration");
+
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
+    const unsigned ring_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
+
+    const ConvGeom& g = a.g;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int half = lane >> 5, l32 = lane & 31;
+    const int PQ = g.P * g.Q;
+
+    // loader: this lane fetches row lrow of every 32-row group, logical chunk lc of the slice
+    const int lrow = wave * 8 + (lane >> 3);
+    const int lc = (lane & 7) ^ ((lrow >> 1) & 7);
+    // reader: LDS byte offset of this lane's operand chunk for k-step 0; k-step ks flips bits 5..6
+    const int lane_x = (half << 4) ^ (((l32 >> 1) & 7) << 4);
+    const unsigned a_rd = ring_lds + (wm * WM + l32) * 128 + lane_x;
+    const unsigned b_rd = ring_lds + A_BYTES + (wn * WN + l32) * 128 + lane_x;
+
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, a.w_bytes, 0x00020000);
+
+    // ---- persistent walk: workgroup b keeps channel block mt = b % grid_m and visits the pixel tiles
+    // nt0, nt0 + gn, ... (gn = workgroups per channel block).  Consecutive workgroup ids are dealt
+    // round-robin to the 8 XCDs; the remap gives each XCD a contiguous range of b, so that the
+    // workgroups sharing a pixel tile share an L2.
+    const int G = gridDim.x;
+    int bid = blockIdx.x;
+    if ((G & 7) == 0) bid = (bid & 7) * (G >> 3) + (bid >> 3);
+    const int mt = bid % a.grid_m, nt0 = bid / a.grid_m, gn = G / a.grid_m;
+    const int my_tiles = (a.grid_n - nt0 + gn - 1) / gn;
+    const int nslices = g.R * a.slices_per_run;
+    const int total = my_tiles * nslices;
+
+    // ---- per-lane constants of the channel block: filter offsets for the loader, bias for the store
+    int a_voff[A_PER];            // byte offset of (filter m, chunk lc) or OOB
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i) {
+        const int m = mt * BM + i * 32 + lrow;
+        a_voff[i] = m < g.K ? (m * g.Kg + lc * 8) * 2 : OOB;
+    }
+    // after the store's lane exchange a lane owns channels mb .. mb + 7, mb = m_lane + 32 i + 16 qp
+    const int m_lane = mt * BM + wm * WM + half * 8;
+    float bias_r[TM][2][8];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int m = m_lane + i * 32 + qp * 16 + e;
+                bias_r[i][qp][e] = (a.bias && m < g.K) ? a.bias[m] : 0.f;
+            }
+
+    // ---- loader state of the pixel tile being fetched
+    int b_base[B_PER];            // byte offset of x[img][ih0][iw0][lc * 8] (may lie outside the tensor)
+    unsigned b_mask[B_PER];       // bits 0..15: tap s is OUTSIDE the image row; bits 16..31: filter row r is inside
+    unsigned b_cur[B_PER];        // TAP: offset of the current tap or OOB;  else: b_mask with the current row's verdict
+    int ld_nt = nt0, ld_r = 0, ld_j0 = 0, ld_s = 0, ld_c = 0;   // wave-uniform cursor of the next slice to load
+
+    auto tile_setup = [&](int nt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i) {
+            const int n = nt * BN + i * 32 + lrow;
+            const int nn = n < g.Ng ? n : 0;
+            const int img = div_small(nn, a.m_pq), pix = nn - img * PQ;
+            const int p = div_small(pix, a.m_q), q = pix - p * g.Q;
+            const int ih0 = p * g.sh - g.ph, iw0 = q * g.sw - g.pw;
+            b_base[i] = (((img * g.H + ih0) * g.W + iw0) * g.C + lc * 8) * 2;
+            const unsigned wv = bit_range(max(0, -iw0), min(g.S - 1, g.W - 1 - iw0));
+            const unsigned hv = n < g.Ng ? bit_range(max(0, -ih0), min(g.R - 1, g.H - 1 - ih0)) : 0u;   // no row of a pixel beyond the tensor
+            b_mask[i] = (~wv & 0xFFFFu) | (hv << 16);
+        }
+    };
+    auto row_setup = [&]() __attribute__((always_inline)) {      // TAP = false: verdict of filter row ld_r for every fetched pixel
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i) b_cur[i] = ((b_mask[i] >> (16 + ld_r)) & 1u) ? (b_mask[i] | 0xFFFF0000u) : 0xFFFFFFFFu;
+    };
+    auto tap_setup = [&]() __attribute__((always_inline)) {      // TAP = true: offsets of tap (ld_r, ld_s)
+        const int tap_off = (ld_r * g.W + ld_s) * g.C * 2;
+        const unsigned want = 1u << (16 + ld_r), sel = want | (1u << ld_s);
+#pragma unroll
+        for (int i = 0; i < B_PER; ++i) b_cur[i] = (b_mask[i] & sel) == want ? (unsigned)(b_base[i] + tap_off) : (unsigned)OOB;
+    };
+
+    auto issue_slice = [&](int stage) __attribute__((always_inline)) {
+        unsigned char* sa = ring + stage * STAGE + wave * 1024;
+        unsigned char* sb = sa + A_BYTES;
+        if constexpr (TAP) {
+            if (ld_c == 0) tap_setup();
+            const int soff_a = ((ld_r * g.S + ld_s) * a.c8 + ld_c) * 16;
+            const int soff_b = ld_c * 16;
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i)
+                load_to_lds16(rw, sa + i * 4096, a_voff[i], soff_a);
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i)
+                load_to_lds16(rx, sb + i * 4096, (int)b_cur[i], soff_b);
+            ld_c += 8;
+            if (ld_c == a.c8) {
+                ld_c = 0;
+                if (++ld_s == g.S) {
+                    ld_s = 0;
+                    if (++ld_r == g.R) { ld_r = 0; ld_nt += gn; tile_setup(ld_nt); }
+                }
+            }
+        } else {
+            if (ld_j0 == 0) row_setup();
+            const int jl = ld_j0 + lc;                                             // this lane's chunk within the run
+            const int s = a.c8 == 1 ? jl : (int)__umulhi((unsigned)jl, a.magic_c8); // its tap: jl / (C / 8), at most 15
+            const int sh = 31 - s;
+            const bool a_ok = jl < a.run_chunks;
+            const int soff_a = (ld_r * a.run_chunks + ld_j0) * 16;
+            const int run_off = ld_r * g.W * g.C * 2 + ld_j0 * 16;
+#pragma unroll
+            for (int i = 0; i < A_PER; ++i)
+                load_to_lds16(rw, sa + i * 4096, a_ok ? a_voff[i] : OOB, soff_a);
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                const unsigned off = ((b_cur[i] << sh) & 0x80000000u) | (unsigned)(b_base[i] + run_off);
+                load_to_lds16(rx, sb + i * 4096, (int)off, 0);
+            }
+            ld_j0 += 8;
+            if (ld_j0 >= a.run_chunks) {
+                ld_j0 = 0;
+                if (++ld_r == g.R) { ld_r = 0; ld_nt += gn; tile_setup(ld_nt); }
+            }
+        }
+    };
+
+    f32x16 acc[TM][TN];
+    auto zero_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    };
+
+    // One slice = 4 k-steps of 16.  The operand reads of step ks + 1 are in flight while the matrix cores
+    // work on step ks: LDS reads return in order, so "at most TM + TN outstanding" means step ks is there.
+    auto compute_slice = [&](int stage) __attribute__((always_inline)) {
+        const unsigned sa = a_rd + stage * STAGE, sb = b_rd + stage * STAGE;
+        u32x4 fa[2][TM], fb[2][TN];
+        auto fetch = [&](int ks, int set) __attribute__((always_inline)) {
+            const unsigned pa = sa ^ (ks * 32), pb = sb ^ (ks * 32);
+            fa[set][0] = ds_read16<0>(pa);
+            if constexpr (TM > 1) fa[set][1] = ds_read16<4096>(pa);
+            if constexpr (TM > 2) fa[set][2] = ds_read16<8192>(pa);
+            if constexpr (TM > 3) fa[set][3] = ds_read16<12288>(pa);
+            fb[set][0] = ds_read16<0>(pb);
+            if constexpr (TN > 1) fb[set][1] = ds_read16<4096>(pb);
+            if constexpr (TN > 2) fb[set][2] = ds_read16<8192>(pb);
+            if constexpr (TN > 3) fb[set][3] = ds_read16<12288>(pb);
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks < 3) { fetch(ks + 1, (ks + 1) & 1); wait_lgkm<TM + TN>(); }
+            else wait_lgkm<0>();
+#pragma unroll
+            for (int i = 0; i < TM; ++i) touch(fa[ks & 1][i]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) touch(fb[ks & 1][j]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[ks & 1][i]),
+                                                                        __builtin_bit_cast(bf16x8, fb[ks & 1][j]), acc[i][j], 0, 0, 0);
+        }
+    };
+
+    auto epilogue = [&](int nt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = nt * BN + wn * WN + j * 32 + l32;
+            uint16_t* yb = a.y + (size_t)n * g.y_ctot + g.y_coff;
+            const uint16_t* rb = a.res + (size_t)n * g.res_ctot;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp) {
+                    // registers 8 qp .. 8 qp + 3 hold channels +0..3 (lower half-wave) / +4..7 (upper);
+                    // registers 8 qp + 4 .. 8 qp + 7 hold channels +8..11 / +12..15
+                    float o[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][qp * 8 + e]),
+                                                                         __float_as_uint(acc[i][j][qp * 8 + 4 + e]), false, false);
+                        o[e] = __uint_as_float(sw[0]);
+                        o[4 + e] = __uint_as_float(sw[1]);
+                    }
+                    const int mb = m_lane + i * 32 + qp * 16;     // first of this lane's 8 channels
+                    if (n >= g.Ng || mb >= g.K) continue;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] += bias_r[i][qp][e];
+                    if (a.vec_ok && mb + 7 < g.K) {
+                        if (a.res) {
+                            const u32x4 rv = *reinterpret_cast<const u32x4*>(rb + mb);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                o[2 * e] += __uint_as_float(rv[e] << 16);
+                                o[2 * e + 1] += __uint_as_float(rv[e] & 0xFFFF0000u);
+                            }
+                        }
+                        if (g.relu) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) o[e] = fmaxf(o[e], 0.f);
+                        }
+                        u32x4 pk;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) pk[e] = pack_bf16x2(o[2 * e], o[2 * e + 1]);
+                        *reinterpret_cast<u32x4*>(yb + mb) = pk;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const int m = mb + e;
+                            if (m < g.K) {
+                                float v = o[e];
+                                if (a.res) v += __uint_as_float((uint32_t)rb[m] << 16);
+                                if (g.relu) v = fmaxf(v, 0.f);
+                                yb[m] = (uint16_t)f32_to_bf16(v);
+                            }
+                        }
+                    }
+                }
+        }
+    };
+
+    // ---- pipeline: loads of slice gi + NS - 1 are issued while slice gi is multiplied
+    tile_setup(ld_nt);
+    int issued = 0, ld_stage = 0;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (issued < total) { issue_slice(ld_stage); ++issued; ld_stage = ld_stage + 1 == NS ? 0 : ld_stage + 1; }
+
+    int gi = 0, cp_stage = 0;
+    for (int t = 0; t < my_tiles; ++t) {
+        zero_acc();
+        for (int sl = 0; sl < nslices; ++sl, ++gi) {
+            // this wave's loads of slice gi have landed once at most the loads of the NS - 2 slices behind it are pending
+            if (gi + NS - 2 < total) wait_vmcnt<(NS - 2) * L>();
+            else wait_vmcnt<0>();
+            ring_barrier();    // everybody's loads of slice gi have landed; everybody is done reading slice gi - 1
+            if (issued < total) { issue_slice(ld_stage); ++issued; ld_stage = ld_stage + 1 == NS ? 0 : ld_stage + 1; }
+            compute_slice(cp_stage);
+            cp_stage = cp_stage + 1 == NS ? 0 : cp_stage + 1;
+        }
+        epilogue(nt0 + t * gn);
+    }
+}
+
+int device_cus()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+        else cus = 256;
+    }
+    return cus;
+}
+
+template <int TM, int TN, int WGM, int WGN, int NS>
+int launch_cfg(DArgs a, hipStream_t st)
+{
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int LDS = NS * (BM + BN) * 128;
+    static_assert(LDS <= 160 * 1024, "LDS ring too large");
+    a.grid_m = (a.g.K + BM - 1) / BM;
+    a.grid_n = (a.g.Ng + BN - 1) / BN;
+    // workgroups per channel block: what the device holds at once, at most one per pixel tile, a
+    // multiple of 8 when possible (the XCD remap needs it)
+    const int per_cu = (160 * 1024) / LDS > 3 ? 3 : (160 * 1024) / LDS;
+    int gn = device_cus() * per_cu / a.grid_m;
+    if (gn < 1) gn = 1;
+    if (gn > a.grid_n) gn = a.grid_n;
+    if (gn >= 8) gn &= ~7;
+    const unsigned G = (unsigned)(gn * a.grid_m);
+    if (a.g.C % 64 == 0)
+        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true>), dim3(G), dim3(NT), 0, st, a);
+    else
+        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, false>), dim3(G), dim3(NT), 0, st, a);
+    return check_launch("conv_bf16");
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+bool conv_bf16_dma_eligible(const ConvGeom& g, const void* x, const void* w)
+{
+    const size_t xb = (size_t)g.N * g.C * g.H * g.W * 2, wb = (size_t)g.K * g.Kg * 2;
+    return g.nhwc && g.w_krsc && g.C % 8 == 0 && g.S <= 9 && g.R <= 16 && g.Ng < (1 << 24) && (long)g.P * g.Q <= 65536 && xb < (1ull << 31) &&
+           wb < (1ull << 31) && aligned16(x) && aligned16(w);
+}
+
+int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
+                         const uint16_t* residual, uint16_t* y, hipStream_t st)
+{
+    DArgs a;
+    a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g;
+    a.grid_m = a.grid_n = 0;
+    a.x_bytes = (int)((size_t)g.N * g.C * g.H * g.W * 2);
+    a.w_bytes = (int)((size_t)g.K * g.Kg * 2);
+    a.c8 = g.C / 8;
+    a.run_chunks = g.S * a.c8;
+    a.slices_per_run = (a.run_chunks + 7) / 8;
+    a.magic_c8 = (unsigned)((0x100000000ull + a.c8 - 1) / a.c8);
+    a.m_pq = ((1ull << 40) + (unsigned)(g.P * g.Q) - 1) / (unsigned)(g.P * g.Q);
+    a.m_q = ((1ull << 40) + (unsigned)g.Q - 1) / (unsigned)g.Q;
+    a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y) && (!residual || (g.res_ctot % 8 == 0 && aligned16(residual)));
+#ifdef DR_TUNE
+    if (const char* e = getenv("DR_BF16_CFG")) {
+        switch (atoi(e)) {
+        case 1: return launch_cfg<1, 2, 1, 4, 4>(a, st);
+        case 2: return launch_cfg<1, 2, 1, 4, 2>(a, st);
+        case 3: return launch_cfg<2, 2, 1, 4, 3>(a, st);
+        case 4: return launch_cfg<2, 2, 1, 4, 2>(a, st);
+        case 5: return launch_cfg<2, 4, 2, 2, 3>(a, st);
+        case 6: return launch_cfg<2, 2, 2, 2, 4>(a, st);
+        case 7: return launch_cfg<2, 2, 2, 2, 2>(a, st);
+        case 8: return launch_cfg<2, 1, 1, 4, 3>(a, st);
+        case 9: return launch_cfg<2, 1, 1, 4, 2>(a, st);
+        case 10: return launch_cfg<1, 1, 1, 4, 3>(a, st);
+        case 11: return launch_cfg<2, 2, 2, 2, 3>(a, st);
+        default: break;
+        }
+    }
+#endif
+    const long tiles_256 = (long)((g.Ng + 255) / 256);
+    const int cus = device_cus();
+    if (g.K <= 32) return launch_cfg<1, 2, 1, 4, 2>(a, st);                                  // 32 x 256
+    if (g.K <= 64) return launch_cfg<2, 2, 1, 4, 2>(a, st);                                  // 64 x 256
+    if (tiles_256 * ((g.K + 127) / 128) >= cus) return launch_cfg<2, 4, 2, 2, 3>(a, st);    // 128 x 256
+    return launch_cfg<2, 2, 2, 2, 2>(a, st);                                                 // 128 x 128
+}
+
+}  // namespace dr

@@ -49,6 +49,11 @@ int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const flo
 int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
                      const uint16_t* residual, uint16_t* y, hipStream_t st);
 
+// conv_bf16_dma.hip: the main bf16 kernel (NHWC, KRSC filters, C % 8 == 0, 16-byte aligned tensors)
+bool conv_bf16_dma_eligible(const ConvGeom& g, const void* x, const void* w);
+int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
+                         const uint16_t* residual, uint16_t* y, hipStream_t st);
+
 // pointwise.hip
 int launch_pack_filters(int dtype, const void* w_kcrs, void* w_krsc, int K, int C, int RS, hipStream_t st);
 int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st);
