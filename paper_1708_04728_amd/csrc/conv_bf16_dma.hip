@@ -30,6 +30,8 @@
 // lane % 32.  One v_permlane32_swap per register pair gives every lane 8 consecutive output channels
 // of its pixel; bias, residual and ReLU are applied in fp32, the result is rounded to bf16 (nearest
 // even) once and written as one 16-byte store.
+#include <type_traits>
+
 #include "dr_internal.h"
 #ifdef DR_TUNE
 #include <stdlib.h>
@@ -43,6 +45,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
+template <int V> using IC = std::integral_constant<int, V>;
 
 constexpr int NT = 256;
 constexpr int OOB = (int)0x80000000;
@@ -130,13 +133,14 @@ __device__ __forceinline__ int div_small(int v, unsigned long long m)
 // bits lo..hi set (hi < lo: none); lo, hi in 0..15
 __device__ __forceinline__ unsigned bit_range(int lo, int hi) { return hi >= lo ? (2u << hi) - (1u << lo) : 0u; }
 
-template <int TM, int TN, int WGM, int WGN, int NS, bool TAP>
-__global__ __launch_bounds__(NT) void conv_bf16_dma_kernel(const DArgs a)
+// OCC: waves per SIMD the register allocation must leave room for (512 / OCC registers per lane)
+template <int TM, int TN, int WGM, int WGN, int NS, bool TAP, int OCC>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void conv_bf16_dma_kernel(const DArgs a)
 {
     constexpr int WM = TM * 32, WN = TN * 32, BM = WGM * WM, BN = WGN * WN;
     constexpr int A_PER = BM / 32, B_PER = BN / 32, L = A_PER + B_PER;   // loads per lane and slice
     constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
-    static_assert(WGM * WGN == 4 && NS >= 2 && (NS - 2) * L < 64, "bad configuration");
+    static_assert(WGM * WGN == 4 && NS >= 2 && (NS - 1) * L < 64, "bad configuration");
 
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
     const unsigned ring_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
@@ -190,6 +194,14 @@ __global__ __launch_bounds__(NT) void conv_bf16_dma_kernel(const DArgs a)
                 const int m = m_lane + i * 32 + qp * 16 + e;
                 bias_r[i][qp][e] = (a.bias && m < g.K) ? a.bias[m] : 0.f;
             }
+    // Use the bias values here, so that the compiler waits for their loads now: left alone it waits at the
+    // first use, in the store of every tile, with a vmcnt(0) that would also drain the operand ring.
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(bias_r[i][qp][e]));
 
     // ---- loader state of the pixel tile being fetched
     int b_base[B_PER];            // byte offset of x[img][ih0][iw0][lc * 8] (may lie outside the tensor)
@@ -277,38 +289,36 @@ __global__ __launch_bounds__(NT) void conv_bf16_dma_kernel(const DArgs a)
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     };
 
-    // One slice = 4 k-steps of 16.  The operand reads of step ks + 1 are in flight while the matrix cores
-    // work on step ks: LDS reads return in order, so "at most TM + TN outstanding" means step ks is there.
-    auto compute_slice = [&](int stage) __attribute__((always_inline)) {
-        const unsigned sa = a_rd + stage * STAGE, sb = b_rd + stage * STAGE;
-        u32x4 fa[2][TM], fb[2][TN];
-        auto fetch = [&](int ks, int set) __attribute__((always_inline)) {
-            const unsigned pa = sa ^ (ks * 32), pb = sb ^ (ks * 32);
-            fa[set][0] = ds_read16<0>(pa);
-            if constexpr (TM > 1) fa[set][1] = ds_read16<4096>(pa);
-            if constexpr (TM > 2) fa[set][2] = ds_read16<8192>(pa);
-            if constexpr (TM > 3) fa[set][3] = ds_read16<12288>(pa);
-            fb[set][0] = ds_read16<0>(pb);
-            if constexpr (TN > 1) fb[set][1] = ds_read16<4096>(pb);
-            if constexpr (TN > 2) fb[set][2] = ds_read16<8192>(pb);
-            if constexpr (TN > 3) fb[set][3] = ds_read16<12288>(pb);
-        };
-        fetch(0, 0);
+    // One slice = 4 k-steps of 16.  The operands of a k-step go from LDS into one of four register slots
+    // (slot = step % 4) three steps before the matrix cores use them, across slice boundaries, so that
+    // the LDS latency hides behind about three steps of MFMAs.  LDS reads return in order: "at most the
+    // reads of two steps outstanding" means the oldest of three steps in flight has arrived.
+    u32x4 fa[4][TM], fb[4][TN];
+    auto fetch_step = [&](int stage, auto ks_c) __attribute__((always_inline)) {     // k-step KS of a stage -> slot KS
+        constexpr int KS = decltype(ks_c)::value;
+        const unsigned pa = (a_rd + stage * STAGE) ^ (KS * 32), pb = (b_rd + stage * STAGE) ^ (KS * 32);
+        fa[KS][0] = ds_read16<0>(pa);
+        if constexpr (TM > 1) fa[KS][1] = ds_read16<4096>(pa);
+        if constexpr (TM > 2) fa[KS][2] = ds_read16<8192>(pa);
+        if constexpr (TM > 3) fa[KS][3] = ds_read16<12288>(pa);
+        fb[KS][0] = ds_read16<0>(pb);
+        if constexpr (TN > 1) fb[KS][1] = ds_read16<4096>(pb);
+        if constexpr (TN > 2) fb[KS][2] = ds_read16<8192>(pb);
+        if constexpr (TN > 3) fb[KS][3] = ds_read16<12288>(pb);
+    };
+    auto multiply_step = [&](auto ks_c) __attribute__((always_inline)) {              // waits for slot KS, multiplies it
+        constexpr int KS = decltype(ks_c)::value;
+        wait_lgkm<2 * (TM + TN)>();
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            if (ks < 3) { fetch(ks + 1, (ks + 1) & 1); wait_lgkm<TM + TN>(); }
-            else wait_lgkm<0>();
+        for (int i = 0; i < TM; ++i) touch(fa[KS][i]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) touch(fa[ks & 1][i]);
+        for (int j = 0; j < TN; ++j) touch(fb[KS][j]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) touch(fb[ks & 1][j]);
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[ks & 1][i]),
-                                                                        __builtin_bit_cast(bf16x8, fb[ks & 1][j]), acc[i][j], 0, 0, 0);
-        }
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[KS][i]),
+                                                                    __builtin_bit_cast(bf16x8, fb[KS][j]), acc[i][j], 0, 0, 0);
     };
 
     auto epilogue = [&](int nt) __attribute__((always_inline)) {
@@ -368,27 +378,47 @@ __global__ __launch_bounds__(NT) void conv_bf16_dma_kernel(const DArgs a)
         }
     };
 
-    // ---- pipeline: loads of slice gi + NS - 1 are issued while slice gi is multiplied
+    // ---- pipeline.  Slice k lives in ring stage k % NS.  Iteration gi multiplies slice gi; after its first
+    // k-step the workgroup meets: slice gi + 1 has landed and slice gi has been read completely, so the
+    // loads of slice gi + NS go out into the stage slice gi leaves, and the remaining three k-steps
+    // already fetch the first three k-steps of slice gi + 1.
     tile_setup(ld_nt);
-    int issued = 0, ld_stage = 0;
+    int issued = 0;
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
-        if (issued < total) { issue_slice(ld_stage); ++issued; ld_stage = ld_stage + 1 == NS ? 0 : ld_stage + 1; }
+    for (int s = 0; s < NS; ++s)
+        if (issued < total) { issue_slice(s); ++issued; }
+    if (NS - 1 < total) wait_vmcnt<(NS - 1) * L>();     // slice 0 has landed (this wave's part)
+    else wait_vmcnt<0>();
+    ring_barrier();
+    fetch_step(0, IC<0>{});
+    fetch_step(0, IC<1>{});
+    fetch_step(0, IC<2>{});
 
-    int gi = 0, cp_stage = 0;
+    int gi = 0, stage = 0;
     for (int t = 0; t < my_tiles; ++t) {
         zero_acc();
         for (int sl = 0; sl < nslices; ++sl, ++gi) {
-            // this wave's loads of slice gi have landed once at most the loads of the NS - 2 slices behind it are pending
-            if (gi + NS - 2 < total) wait_vmcnt<(NS - 2) * L>();
-            else wait_vmcnt<0>();
-            ring_barrier();    // everybody's loads of slice gi have landed; everybody is done reading slice gi - 1
-            if (issued < total) { issue_slice(ld_stage); ++issued; ld_stage = ld_stage + 1 == NS ? 0 : ld_stage + 1; }
-            compute_slice(cp_stage);
-            cp_stage = cp_stage + 1 == NS ? 0 : cp_stage + 1;
+            const int next_stage = stage + 1 == NS ? 0 : stage + 1;
+            multiply_step(IC<0>{});
+            fetch_step(stage, IC<3>{});
+            if (gi + 1 < total) {
+                // this wave's loads of slice gi + 1 have landed once at most the NS - 2 slices behind it are pending
+                if (gi + NS - 1 < total) wait_vmcnt<(NS - 2) * L>();
+                else wait_vmcnt<0>();
+                ring_barrier();
+                if (issued < total) { issue_slice(stage); ++issued; }
+            }
+            multiply_step(IC<1>{});
+            fetch_step(next_stage, IC<0>{});      // (after the last slice: reads nobody uses)
+            multiply_step(IC<2>{});
+            fetch_step(next_stage, IC<1>{});
+            multiply_step(IC<3>{});
+            fetch_step(next_stage, IC<2>{});
+            stage = next_stage;
         }
         epilogue(nt0 + t * gn);
     }
+    wait_lgkm<0>();
 }
 
 int device_cus()
@@ -402,7 +432,7 @@ int device_cus()
     return cus;
 }
 
-template <int TM, int TN, int WGM, int WGN, int NS>
+template <int TM, int TN, int WGM, int WGN, int NS, int OCC>
 int launch_cfg(DArgs a, hipStream_t st)
 {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
@@ -412,16 +442,17 @@ int launch_cfg(DArgs a, hipStream_t st)
     a.grid_n = (a.g.Ng + BN - 1) / BN;
     // workgroups per channel block: what the device holds at once, at most one per pixel tile, a
     // multiple of 8 when possible (the XCD remap needs it)
-    const int per_cu = (160 * 1024) / LDS > 3 ? 3 : (160 * 1024) / LDS;
+    static_assert(OCC * LDS <= 160 * 1024, "the ring does not fit OCC times");
+    const int per_cu = OCC;
     int gn = device_cus() * per_cu / a.grid_m;
     if (gn < 1) gn = 1;
     if (gn > a.grid_n) gn = a.grid_n;
     if (gn >= 8) gn &= ~7;
     const unsigned G = (unsigned)(gn * a.grid_m);
     if (a.g.C % 64 == 0)
-        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true>), dim3(G), dim3(NT), 0, st, a);
+        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true, OCC>), dim3(G), dim3(NT), 0, st, a);
     else
-        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, false>), dim3(G), dim3(NT), 0, st, a);
+        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, false, OCC>), dim3(G), dim3(NT), 0, st, a);
     return check_launch("conv_bf16");
 }
 
@@ -454,27 +485,29 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
 #ifdef DR_TUNE
     if (const char* e = getenv("DR_BF16_CFG")) {
         switch (atoi(e)) {
-        case 1: return launch_cfg<1, 2, 1, 4, 4>(a, st);
-        case 2: return launch_cfg<1, 2, 1, 4, 2>(a, st);
-        case 3: return launch_cfg<2, 2, 1, 4, 3>(a, st);
-        case 4: return launch_cfg<2, 2, 1, 4, 2>(a, st);
-        case 5: return launch_cfg<2, 4, 2, 2, 3>(a, st);
-        case 6: return launch_cfg<2, 2, 2, 2, 4>(a, st);
-        case 7: return launch_cfg<2, 2, 2, 2, 2>(a, st);
-        case 8: return launch_cfg<2, 1, 1, 4, 3>(a, st);
-        case 9: return launch_cfg<2, 1, 1, 4, 2>(a, st);
-        case 10: return launch_cfg<1, 1, 1, 4, 3>(a, st);
-        case 11: return launch_cfg<2, 2, 2, 2, 3>(a, st);
+        case 1: return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);   // 32 x 256
+        case 2: return launch_cfg<1, 2, 1, 4, 3, 1>(a, st);
+        case 3: return launch_cfg<2, 2, 1, 4, 3, 1>(a, st);   // 64 x 256
+        case 4: return launch_cfg<2, 2, 1, 4, 2, 2>(a, st);
+        case 5: return launch_cfg<2, 4, 2, 2, 3, 1>(a, st);   // 128 x 256
+        case 6: return launch_cfg<2, 2, 2, 2, 4, 1>(a, st);   // 128 x 128
+        case 7: return launch_cfg<2, 2, 2, 2, 2, 2>(a, st);
+        case 8: return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);   // 64 x 128
+        case 9: return launch_cfg<2, 1, 1, 4, 2, 3>(a, st);
+        case 10: return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);  // 32 x 128
+        case 11: return launch_cfg<2, 1, 1, 4, 2, 2>(a, st);
+        case 12: return launch_cfg<4, 2, 1, 4, 2, 1>(a, st);  // 128 x 256, wave tile 128 x 64
         default: break;
         }
     }
 #endif
-    const long tiles_256 = (long)((g.Ng + 255) / 256);
-    const int cus = device_cus();
-    if (g.K <= 32) return launch_cfg<1, 2, 1, 4, 2>(a, st);                                  // 32 x 256
-    if (g.K <= 64) return launch_cfg<2, 2, 1, 4, 2>(a, st);                                  // 64 x 256
-    if (tiles_256 * ((g.K + 127) / 128) >= cus) return launch_cfg<2, 4, 2, 2, 3>(a, st);    // 128 x 256
-    return launch_cfg<2, 2, 2, 2, 2>(a, st);                                                 // 128 x 128
+    // Tile choice, from sweeps over the ResNet / GoogLeNet layer shapes at batch 128.  The kernel is limited
+    // by how fast a compute unit's vector memory path feeds LDS (about 50-64 bytes per clock) and by
+    // instruction issue, not by the matrix cores: several small workgroups per compute unit, whose load
+    // bursts interleave, beat one large tile.
+    if (g.K <= 32) return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);       // 32 x 256 tiles, 2 workgroups per CU
+    if (g.Ng <= 8192) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);    // few pixels: 32 x 128 tiles, 3 per CU
+    return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                      // 64 x 128 tiles, 2 per CU
 }
 
 }  // namespace dr

@@ -40,10 +40,10 @@ def _run(case, relu=False, bias=True, seed=0):
 # N, C, H, W, K, R, S, stride, pad
 CASES = [
     # --- slices inside one tap (C % 64 == 0)
-    (1, 64, 12, 12, 24, 1, 1, 1, 0),        # 32-row tile, one slice per tile
-    (2, 64, 30, 30, 64, 3, 3, 1, 1),        # 64 x 256 tiles, 9 slices
-    (1, 128, 40, 40, 72, 3, 3, 1, 1),       # 128 x 128 tiles (few pixel tiles), ragged filter block
-    (1, 64, 190, 190, 136, 1, 1, 1, 0),     # 128 x 256 tiles, two channel blocks, ragged last pixel tile
+    (1, 64, 12, 12, 24, 1, 1, 1, 0),        # K <= 32: 32 x 256 tiles, one slice per tile
+    (2, 64, 30, 30, 64, 3, 3, 1, 1),        # few pixels: 32 x 128 tiles, two channel blocks, 9 slices
+    (1, 128, 40, 40, 72, 3, 3, 1, 1),       # ragged filter block
+    (1, 64, 190, 190, 136, 1, 1, 1, 0),     # many pixels: 64 x 128 tiles, three channel blocks, ragged last pixel tile
     (3, 128, 17, 19, 40, 3, 3, 2, 1),       # stride 2, odd sizes
     (1, 192, 9, 9, 200, 5, 5, 1, 2),        # 5x5 at 192 channels, 75 slices
     (2, 64, 8, 8, 16, 3, 3, 1, 0),          # no padding
@@ -63,6 +63,8 @@ CASES = [
     (1, 32, 11, 13, 20, 3, 5, 1, 2),        # 3x5 filter, pad 2: whole filter rows in the padding
     (1, 40, 6, 6, 12, 5, 5, 3, 2),          # stride 3
     (1, 8, 3, 3, 8, 3, 3, 1, 1),            # tiny
+    (2, 96, 70, 70, 72, 3, 3, 1, 1),        # many pixels (64 x 128 tiles) with slices running over filter rows
+    (1, 24, 200, 200, 40, 5, 5, 2, 2),      # the same at stride 2, 5x5
 ]
 
 
