@@ -65,6 +65,8 @@ struct DArgs {
     unsigned magic_c8;        // ceil(2^32 / c8)
     unsigned long long m_pq, m_q;   // ceil(2^40 / (P*Q)), ceil(2^40 / Q)
     int vec_ok;               // 16-byte stores / bias / residual accesses are aligned
+    int pointwise;            // 1x1 filter, stride 1, no padding
+    int step_img, step_p, step_q;   // 32 pixels as (images, rows, columns) of the output
 };
 
 // Workgroup barrier between the slices.  A fence would make the compiler wait for every outstanding
@@ -209,18 +211,37 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
     unsigned b_cur[B_PER];        // TAP: offset of the current tap or OOB;  else: b_mask with the current row's verdict
     int ld_nt = nt0, ld_r = 0, ld_j0 = 0, ld_s = 0, ld_c = 0;   // wave-uniform cursor of the next slice to load
 
+    // Per-lane state of pixel tile nt.  A 1x1 filter at stride 1 without padding reads input pixel n for
+    // output pixel n: no decoding.  Otherwise the first fetched pixel is decoded into (image, p, q) by
+    // exact division and the others follow by stepping 32 pixels at a time (32 = step_img P Q + step_p Q +
+    // step_q, so each coordinate wraps at most once per step).
     auto tile_setup = [&](int nt) __attribute__((always_inline)) {
+        const int n_first = nt * BN + lrow;
+        if (a.pointwise) {
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                const int n = n_first + i * 32;
+                b_base[i] = (n * g.C + lc * 8) * 2;
+                b_mask[i] = n < g.Ng ? 0x1FFFEu : 0xFFFFu;
+            }
+            return;
+        }
+        int img = div_small(n_first < g.Ng ? n_first : 0, a.m_pq);
+        int pix = (n_first < g.Ng ? n_first : 0) - img * PQ;
+        int p = div_small(pix, a.m_q), q = pix - p * g.Q;
 #pragma unroll
         for (int i = 0; i < B_PER; ++i) {
-            const int n = nt * BN + i * 32 + lrow;
-            const int nn = n < g.Ng ? n : 0;
-            const int img = div_small(nn, a.m_pq), pix = nn - img * PQ;
-            const int p = div_small(pix, a.m_q), q = pix - p * g.Q;
+            const int n = n_first + i * 32;
             const int ih0 = p * g.sh - g.ph, iw0 = q * g.sw - g.pw;
             b_base[i] = (((img * g.H + ih0) * g.W + iw0) * g.C + lc * 8) * 2;
             const unsigned wv = bit_range(max(0, -iw0), min(g.S - 1, g.W - 1 - iw0));
             const unsigned hv = n < g.Ng ? bit_range(max(0, -ih0), min(g.R - 1, g.H - 1 - ih0)) : 0u;   // no row of a pixel beyond the tensor
             b_mask[i] = (~wv & 0xFFFFu) | (hv << 16);
+            q += a.step_q;
+            if (q >= g.Q) { q -= g.Q; ++p; }
+            p += a.step_p;
+            if (p >= g.P) { p -= g.P; ++img; }
+            img += a.step_img;
         }
     };
     auto row_setup = [&]() __attribute__((always_inline)) {      // TAP = false: verdict of filter row ld_r for every fetched pixel
@@ -481,6 +502,10 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
     a.magic_c8 = (unsigned)((0x100000000ull + a.c8 - 1) / a.c8);
     a.m_pq = ((1ull << 40) + (unsigned)(g.P * g.Q) - 1) / (unsigned)(g.P * g.Q);
     a.m_q = ((1ull << 40) + (unsigned)g.Q - 1) / (unsigned)g.Q;
+    a.pointwise = g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
+    a.step_img = 32 / (g.P * g.Q);
+    a.step_p = (32 % (g.P * g.Q)) / g.Q;
+    a.step_q = 32 % g.Q;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y) && (!residual || (g.res_ctot % 8 == 0 && aligned16(residual)));
 #ifdef DR_TUNE
     if (const char* e = getenv("DR_BF16_CFG")) {
