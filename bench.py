@@ -81,7 +81,7 @@ def calibrate_copy():
 
 
 def conv_flops(rec):
-    label, k, c, r, s, items, ms = rec
+    label, k, c, r, s, items = rec[:6]
     return 2.0 * k * c * r * s * items
 
 
@@ -237,20 +237,29 @@ def main():
     # ---- roofline of the dominant kernel
     esz = 2 if dtype == "bf16" else 4
     if dom_is_conv:
-        flops = conv_flops(dom)
-        achieved = flops / (dom_ms * 1e-3) / 1e12
+        # the roof that binds: the matrix cores when the layer's arithmetic intensity (FLOP per byte it must
+        # move: input, filters and output once each) exceeds the machine balance, else HBM
+        flops, nbytes = conv_flops(dom), float(dom[7])
         peak = MI355X_MFMA_TFLOPS[dtype]
         desc = "%s %dx%d %d->%d n=%d" % (dom[0], dom[3], dom[4], dom[2], dom[1], dom[5])
-        roofline = {"bound": "mfma", "kernel": desc,
-                    "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                    "launch_ms": round(dom_ms, 5), "launches_timed": len(dom_recs),
-                    "algorithmic_flop_per_launch": flops, "traffic": measured_traffic(desc, dom[0])}
+        mfma_bound = flops / nbytes >= peak * 1e12 / (MI355X_HBM_GBS * 1e9)
+        if mfma_bound:
+            achieved = flops / (dom_ms * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "kernel": desc, "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                        "frac": round(achieved / peak, 4)}
+        else:
+            achieved = nbytes / (dom_ms * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "kernel": desc, "achieved": round(achieved, 1), "peak": MI355X_HBM_GBS, "unit": "GB/s",
+                        "frac": round(achieved / MI355X_HBM_GBS, 4)}
+        roofline.update({"launch_ms": round(dom_ms, 5), "launches_timed": len(dom_recs), "algorithmic_flop_per_launch": flops,
+                         "algorithmic_bytes_per_launch": nbytes, "flop_per_byte": round(flops / nbytes, 1),
+                         "tflops": round(flops / (dom_ms * 1e-3) / 1e12, 2), "traffic": measured_traffic(desc, dom[0])})
     else:
         nbytes = 2.0 * dom[5] * esz
         achieved = nbytes / (dom_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": dom[0], "achieved": round(achieved, 1), "peak": MI355X_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / MI355X_HBM_GBS, 4), "launch_ms": round(dom_ms, 5),
-                    "launches_timed": len(dom_recs), "traffic": None}
+                    "launches_timed": len(dom_recs), "algorithmic_bytes_per_launch": nbytes, "traffic": None}
 
     # ---- per-kind split of one step: time in tensor layers vs non-tensor layers (Eq. (1))
     def split(rs):

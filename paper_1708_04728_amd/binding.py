@@ -68,7 +68,7 @@ class dr_layer_desc(C.Structure):
 
 class dr_trace_record(C.Structure):
     _fields_ = [("label", C.c_char * 24), ("k", C.c_int), ("c", C.c_int), ("r", C.c_int), ("s", C.c_int),
-                ("items", C.c_longlong), ("ms", C.c_float)]
+                ("items", C.c_longlong), ("ms", C.c_float), ("bytes", C.c_longlong)]
 
 
 class DeepRebirthError(RuntimeError):
@@ -313,11 +313,11 @@ def trace_begin(label_filter="", conv_k=0, conv_c=0, conv_r=0, capacity=4096):
 
 
 def trace_end(capacity=4096):
-    """List of (label, k, c, r, s, items, ms) in launch order."""
+    """List of (label, k, c, r, s, items, ms, bytes) in launch order."""
     arr = (dr_trace_record * capacity)()
     n = C.c_int(0)
     _check(lib().dr_trace_end(arr, capacity, C.byref(n)))
-    return [(a.label.decode(), a.k, a.c, a.r, a.s, a.items, a.ms) for a in arr[:n.value]]
+    return [(a.label.decode(), a.k, a.c, a.r, a.s, a.items, a.ms, a.bytes) for a in arr[:n.value]]
 
 
 class Net:

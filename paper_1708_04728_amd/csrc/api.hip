@@ -44,11 +44,15 @@ TraceScope::TraceScope(const char* label, const ConvGeom* g, long long items, hi
 {
     if (!g_trace.active || g_trace.recs.size() >= g_trace.capacity) return;
     if (g_trace.filter[0] && !strstr(label, g_trace.filter)) return;
-    if (g && ((g_trace.k && g_trace.k != g->K) || (g_trace.c && g_trace.c != g->C) || (g_trace.r && g_trace.r != g->R))) return;
+    if (g && ((g_trace.k && g_trace.k != g->K) || (g_trace.c && g_trace.c != (g->c_logical ? g->c_logical : g->C)) || (g_trace.r && g_trace.r != g->R))) return;
     dr_trace_record rec;
     memset(&rec, 0, sizeof rec);
     snprintf(rec.label, sizeof rec.label, "%s", label);
-    if (g) { rec.k = g->K; rec.c = g->C; rec.r = g->R; rec.s = g->S; }
+    if (g) {
+        const long long c = g->c_logical ? g->c_logical : g->C, esz = strstr(label, "f32") ? 4 : 2;
+        rec.k = g->K; rec.c = (int)c; rec.r = g->R; rec.s = g->S;
+        rec.bytes = esz * ((long long)g->N * c * g->H * g->W + (long long)g->K * c * g->R * g->S + (long long)g->Ng * g->K * (g->res_ctot ? 2 : 1));
+    }
     rec.items = items;
     slot = (int)g_trace.recs.size();
     g_trace.recs.push_back(rec);
@@ -121,7 +125,7 @@ bool same_shape(const dr_tensor& a, const dr_tensor& b)
 
 // Validated convolution launch (shared by the single-layer entry points and the composite ones).
 int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias,
-             const void* residual, int res_ctot, const dr_tensor& yd, void* y, int y_c_offset, hipStream_t st)
+             const void* residual, int res_ctot, const dr_tensor& yd, void* y, int y_c_offset, hipStream_t st, int c_logical = 0)
 {
     if (xd.c != cd.c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd.c, cd.c);
     const dr_tensor o = conv_out(xd, cd);
@@ -149,6 +153,7 @@ int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv&
     g.res_ctot = residual ? res_ctot : 0;
     g.w_krsc = cd.filter_layout == DR_KRSC;
     g.nhwc = xd.layout == DR_NHWC;
+    g.c_logical = c_logical;
     if (xd.dtype == DR_F32)
         return launch_conv_f32(g, (const float*)x, (const float*)w, bias, (const float*)residual, (float*)y, st);
     return launch_conv_bf16(g, (const uint16_t*)x, (const uint16_t*)w, bias, (const uint16_t*)residual, (uint16_t*)y, st);
@@ -169,6 +174,33 @@ struct Arena {
         return used <= size ? base + off : nullptr;
     }
 };
+
+// A bf16 channels-last convolution whose channel count is not a multiple of 8 (the 3-channel network input)
+// cannot use the matrix-core kernels, which fetch 16-byte channel groups.  Where a workspace exists
+// (dr_net_fwd) the input and the filters are copied with their channels zero-padded to a multiple of 8
+// first; the zeros add nothing to the sums.  Returns the scratch the layer needs / runs it.
+bool conv_wants_padding(const dr_tensor& xd, const dr_conv& cd)
+{
+    return xd.dtype == DR_BF16 && xd.layout == DR_NHWC && cd.c % 8 != 0 && cd.c < 8;
+}
+int padded_conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias,
+                    const dr_tensor& yd, void* y, Arena& ar, hipStream_t st)
+{
+    const int Cp = (cd.c + 7) / 8 * 8;
+    dr_tensor xp = xd;
+    xp.c = Cp;
+    dr_conv cp = cd;
+    cp.c = Cp;
+    cp.filter_layout = DR_KRSC;
+    void* xbuf = ar.take(tensor_bytes(xp));
+    void* wbuf = ar.take((size_t)cd.k * cd.r * cd.s * Cp * 2);
+    if (ar.measure) return DR_OK;
+    if (!xbuf || !wbuf) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
+    if (!x || !w) return fail(DR_ERR_NULL, "%s: x or w is NULL", who);
+    DR_TRY(launch_pad_channels_bf16(x, xbuf, (size_t)xd.n * xd.h * xd.w, cd.c, Cp, st));
+    DR_TRY(launch_pad_filters_bf16(w, wbuf, cd.k, cd.c, cd.r * cd.s, Cp, cd.filter_layout == DR_KRSC, st));
+    return conv_run(who, xp, xbuf, cp, wbuf, bias, nullptr, 0, yd, y, 0, st, cd.c);
+}
 
 // ---- inception ---------------------------------------------------------------------------------------
 struct ParamCursor {
@@ -399,7 +431,9 @@ int net_plan(const dr_net& net, const dr_tensor& xd, NetPlan* plan)
         if (L.kind == DR_LAYER_SOFTMAX && i + 1 != net.layers.size())
             return fail(DR_ERR_UNSUPPORTED, "dr_net: softmax must be the last layer");
         Arena ar(nullptr, 0, true);
-        if (L.kind == DR_LAYER_INCEPTION) {
+        if (L.kind == DR_LAYER_CONV && conv_wants_padding(t, L.conv)) {
+            DR_TRY(padded_conv_run("dr_net", t, nullptr, L.conv, nullptr, nullptr, o, nullptr, ar, nullptr));
+        } else if (L.kind == DR_LAYER_INCEPTION) {
             ParamCursor w{nullptr, 0}, b{nullptr, 0};
             DR_TRY(inception_run(t, nullptr, L.inception, w, b, o, nullptr, ar, nullptr));
         } else if (L.kind == DR_LAYER_BOTTLENECK) {
@@ -815,7 +849,10 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
         Arena ar(scratch, plan.scratch_bytes, false);
         switch (L.kind) {
         case DR_LAYER_CONV:
-            DR_TRY(conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], nullptr, 0, od, dst, 0, st));
+            if (conv_wants_padding(t, L.conv))
+                DR_TRY(padded_conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], od, dst, ar, st));
+            else
+                DR_TRY(conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], nullptr, 0, od, dst, 0, st));
             break;
         case DR_LAYER_RELU: DR_TRY(launch_relu(t.dtype, cur, dst, tensor_elems(t), st)); break;
         case DR_LAYER_LRN: DR_TRY(launch_lrn(t, cur, dst, L.lrn, st)); break;

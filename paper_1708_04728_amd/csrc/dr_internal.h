@@ -40,6 +40,7 @@ struct ConvGeom {
     int res_ctot;        // channels of the residual tensor (0 = no residual add)
     int w_krsc;          // filters are in KRSC order (else KCRS)
     int nhwc;            // activations (x, y, residual) are channels-last
+    int c_logical;       // channels of the layer when C counts zero padding added by the caller (0: C itself); for trace records
 };
 
 // conv_f32.hip / conv_bf16.hip: y = conv(x, w) + bias [+ residual] [ReLU].
@@ -72,6 +73,9 @@ int launch_pool_nhwc(const dr_tensor& xd, const void* x, const dr_tensor& yd, vo
 int launch_concat_nhwc(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st);
 int launch_bn_nhwc(const dr_tensor& d, const void* x, void* y, const float* gamma, const float* beta, const float* mean,
                    const float* var, float eps, int relu, hipStream_t st);
+// bf16 channel padding to a multiple of 8 (pixels x C -> pixels x Cp; filters KCRS or KRSC -> KRSC with Cp channels)
+int launch_pad_channels_bf16(const void* x, void* y, size_t pixels, int C, int Cp, hipStream_t st);
+int launch_pad_filters_bf16(const void* w, void* y, int K, int C, int RS, int Cp, int krsc, hipStream_t st);
 int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* y, int N, int I, int O, hipStream_t st);
 int launch_softmax(int dtype, const void* x, float* y, int N, int O, hipStream_t st);
 

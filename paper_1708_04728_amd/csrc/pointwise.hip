@@ -469,6 +469,15 @@ int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* 
 {
     TraceScope trace("fc", nullptr, (long long)((size_t)N * O), st);
     if (N == 0 || O == 0) return DR_OK;
+    if (dtype == DR_BF16) {
+        // an inner product is a 1x1 convolution over a one-pixel image: y[n][o] = sum_i w[o][i] x[n][i] runs on
+        // the matrix cores through the streaming convolution kernel when its layout conditions hold
+        ConvGeom g;
+        g.N = N; g.C = I; g.H = g.W = 1; g.K = O; g.R = g.S = 1; g.sh = g.sw = 1; g.ph = g.pw = 0; g.P = g.Q = 1;
+        g.Kg = I; g.Ng = N; g.y_ctot = O; g.y_coff = 0; g.relu = 0; g.res_ctot = 0; g.w_krsc = 1; g.nhwc = 1; g.c_logical = 0;
+        if (conv_bf16_dma_eligible(g, x, w))
+            return launch_conv_bf16_dma(g, (const uint16_t*)x, (const uint16_t*)w, bias, nullptr, (uint16_t*)y, st);
+    }
     const dim3 grid((unsigned)O, (unsigned)(N < 8 ? N : 8));
     if (dtype == DR_BF16)
         hipLaunchKernelGGL((fc_kernel<uint16_t>), grid, dim3(64), 0, st, (const uint16_t*)x, (const uint16_t*)w, bias, (uint16_t*)y, N, I, O);

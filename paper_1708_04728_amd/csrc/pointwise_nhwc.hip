@@ -82,6 +82,72 @@ __global__ __launch_bounds__(256) void pool_nhwc_kernel(const T* __restrict__ x,
     }
 }
 
+// 3x3 max-pooling, the window of every pooling layer of the networks here: separable.  A thread owns
+// one output column q and one channel group and walks down a strip of PR output rows; per input row
+// it takes the maximum of the row's three window pixels (three 16-byte loads), and an output is the
+// maximum of three such row maxima, two of which are kept in registers from the previous outputs.
+// Loads per output: 3 (PR + 2) / PR at stride 1 instead of 9.  Pixels outside the input never win.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void maxpool3_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int H, int W, int P,
+                                                            int Q, int PR, int pstrips, int qgroups, int bx_log2, int stride, int pad)
+{
+    const int CV = C / V;
+    const int bx = 1 << bx_log2, by = 256 >> bx_log2;
+    const int tx = threadIdx.x & (bx - 1), ty = threadIdx.x >> bx_log2;
+    const unsigned qg = blockIdx.x % (unsigned)qgroups, t = blockIdx.x / (unsigned)qgroups;
+    const unsigned strip = t % (unsigned)pstrips, n = t / (unsigned)pstrips;
+    const int q = (int)qg * by + ty;
+    if (q >= Q) return;
+    const int p0 = (int)strip * PR, p1 = min(p0 + PR, P);
+    const int w0 = q * stride - pad;
+    const T* xb = x + (size_t)n * H * W * C;
+    for (int cv = tx; cv < CV; cv += bx) {
+        auto row_max = [&](int h, float* m) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) m[j] = -INFINITY;
+            if ((unsigned)h >= (unsigned)H) return;
+            const T* src = xb + ((size_t)h * W + w0) * C + cv * V;
+            float v[3][V];
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                if ((unsigned)(w0 + c) < (unsigned)W) {
+                    if constexpr (V == 1) v[c][0] = Store<T>::ld(src + (size_t)c * C);
+                    else Store<T>::ldv(src + (size_t)c * C, v[c]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < V; ++j) v[c][j] = -INFINITY;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < V; ++j) m[j] = fmaxf(fmaxf(v[0][j], v[1][j]), v[2][j]);
+        };
+        float r0[V], r1[V], r2[V];
+        int hb = p0 * stride - pad;                 // first input row of the current window
+        row_max(hb, r0);
+        row_max(hb + 1, r1);
+        for (int p = p0; p < p1; ++p, hb += stride) {
+            row_max(hb + 2, r2);
+            float o[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) o[j] = fmaxf(fmaxf(r0[j], r1[j]), r2[j]);
+            T* dst = y + (((size_t)n * P + p) * Q + q) * C + cv * V;
+            if constexpr (V == 1) Store<T>::st(dst, o[0]);
+            else Store<T>::stv(dst, o);
+            if (stride == 1) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) { r0[j] = r1[j]; r1[j] = r2[j]; }
+            } else if (stride == 2) {
+#pragma unroll
+                for (int j = 0; j < V; ++j) r0[j] = r2[j];
+                if (p + 1 < p1) row_max(hb + 3, r1);
+            } else if (p + 1 < p1) {
+                row_max(hb + stride, r0);
+                row_max(hb + stride + 1, r1);
+            }
+        }
+    }
+}
+
 template <typename T>
 int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, bool avg, hipStream_t st)
 {
@@ -94,6 +160,22 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
     const int by = 256 >> bx_log2;
     const int qgroups = (yd.w + by - 1) / by;
     if ((double)yd.n * yd.h * qgroups >= 2147483648.0) return fail(DR_ERR_UNSUPPORTED, "pooling: tensor too large");
+    if (!avg && p.kh == 3 && p.kw == 3 && p.stride_h == p.stride_w && p.pad_h == p.pad_w) {
+        // strips of 4 output rows (best in sweeps over the pooling layers of the networks here), 2 while the
+        // launch would otherwise have fewer than ~2048 workgroups
+        const long per_strip = (long)yd.n * qgroups;
+        int PR = 4;
+        while (PR > 2 && per_strip * ((yd.h + PR - 1) / PR) < 2048) PR >>= 1;
+        const int pstrips = (yd.h + PR - 1) / PR;
+        const dim3 g3((unsigned)(per_strip * pstrips));
+        if (vec)
+            hipLaunchKernelGGL((maxpool3_nhwc_kernel<T, VN>), g3, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, PR,
+                               pstrips, qgroups, bx_log2, p.stride_h, p.pad_h);
+        else
+            hipLaunchKernelGGL((maxpool3_nhwc_kernel<T, 1>), g3, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, PR,
+                               pstrips, qgroups, bx_log2, p.stride_h, p.pad_h);
+        return check_launch("maxpool");
+    }
     const dim3 grid((unsigned)(yd.n * yd.h * qgroups)), block(256);
 #define DR_POOL(V, AVG) hipLaunchKernelGGL((pool_nhwc_kernel<T, V, AVG>), grid, block, 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, qgroups, bx_log2, p)
     if (vec) { if (avg) DR_POOL(VN, true); else DR_POOL(VN, false); }
@@ -295,6 +377,63 @@ int bn_launch(const dr_tensor& d, const void* x, void* y, const float* gamma, co
 }
 
 }  // namespace
+
+namespace {
+
+// ---- channel padding (bf16): lets a convolution whose channel count is not a multiple of 8 (the 3-channel
+// network input) run in the matrix-core kernels, which fetch 16-byte channel groups ---------------------
+// y[pix][0 .. Cp) = x[pix][0 .. C), zeros beyond; one thread per 16-byte group of y.
+__global__ __launch_bounds__(256) void pad_channels_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y, size_t groups,
+                                                           int C, int Cp)
+{
+    const int gp = Cp / 8;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < groups; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t pix = i / gp;
+        const int c0 = (int)(i - pix * gp) * 8;
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t lo = c0 + 2 * e < C ? x[pix * C + c0 + 2 * e] : 0u;
+            const uint32_t hi = c0 + 2 * e + 1 < C ? x[pix * C + c0 + 2 * e + 1] : 0u;
+            w[e] = lo | (hi << 16);
+        }
+        *reinterpret_cast<uint4*>(y + i * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// y[k][r][s][0 .. Cp) = w[k][c][r][s] (KCRS) or w[k][r][s][c] (KRSC), zeros beyond C
+__global__ __launch_bounds__(256) void pad_filters_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ y, int K, int C, int RS,
+                                                          int Cp, int krsc)
+{
+    const size_t total = (size_t)K * RS * Cp;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % Cp);
+        const size_t t = i / Cp;
+        const int rs = (int)(t % RS);
+        const size_t k = t / RS;
+        y[i] = c < C ? (krsc ? w[(k * RS + rs) * C + c] : w[(k * C + c) * RS + rs]) : (uint16_t)0;
+    }
+}
+
+}  // namespace
+
+int launch_pad_channels_bf16(const void* x, void* y, size_t pixels, int C, int Cp, hipStream_t st)
+{
+    TraceScope trace("conv_pad", nullptr, (long long)(pixels * Cp), st);
+    const size_t groups = pixels * (Cp / 8);
+    if (groups == 0) return DR_OK;
+    hipLaunchKernelGGL(pad_channels_kernel, dim3(blocks_for(groups, 256, 256 * 64)), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)y, groups, C, Cp);
+    return check_launch("pad_channels");
+}
+
+int launch_pad_filters_bf16(const void* w, void* y, int K, int C, int RS, int Cp, int krsc, hipStream_t st)
+{
+    TraceScope trace("conv_pad", nullptr, (long long)((size_t)K * RS * Cp), st);
+    const size_t total = (size_t)K * RS * Cp;
+    if (total == 0) return DR_OK;
+    hipLaunchKernelGGL(pad_filters_kernel, dim3(blocks_for(total, 256, 4096)), dim3(256), 0, st, (const uint16_t*)w, (uint16_t*)y, K, C, RS, Cp, krsc);
+    return check_launch("pad_filters");
+}
 
 int launch_pool_nhwc(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, bool avg, hipStream_t st)
 {
