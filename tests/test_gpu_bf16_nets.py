@@ -140,3 +140,41 @@ def test_config5_googlenet(form):
     top = np.sort(ref, axis=1)[:, -2:]
     decided = (top[:, 1] - top[:, 0]) > 0.1 * top[:, 1]
     assert (np.argmax(got, axis=1) == np.argmax(ref, axis=1))[decided].all()
+
+
+# ---- full sizes, in the launch configuration the benchmark times -------------------------------------------
+# The whole batch runs on the GPU; the oracle recomputes a few of the images (images are independent), and
+# properties that hold for every image are checked on all of them.
+
+def test_config5_googlenet_full_batch_sampled():
+    x = workloads.make_input(5)
+    assert x.shape == (128, 3, 224, 224)
+    pick = [0, 77, 127]
+    for form in ("original", "slim"):
+        slim = form == "slim"
+        layers = workloads.CONFIGS[5][form]
+        params = workloads.make_params(5, form)
+        mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT) if slim else 0
+        got = run_net_bf16(layers, params, x, fuse_relu=slim, inception_mode=mode).reshape(128, 1000)
+        assert np.isfinite(got).all() and (got >= 0).all()
+        np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-3)
+        ref = oracle.forward(layers, params, x[pick], mirror_bf16=True).reshape(len(pick), 1000)
+        depth = (3 if slim else 5) + 18 + 2
+        assert rel_err(got[pick], ref) < TOL_BF16 * math.sqrt(depth)
+
+
+def test_config4_resnet_stage_full_batch_sampled():
+    x = workloads.make_input(4)
+    assert x.shape == (128, 64, 56, 56)
+    pick = [0, 127]
+    layers = workloads.CONFIGS[4]["original"]
+    params = workloads.make_params(4)
+    got = run_net_bf16(layers, params, x)
+    assert got.shape == (128, 256, 56, 56) and np.isfinite(got).all() and (got >= 0).all()
+    ref = oracle.forward(layers, params, x[pick], mirror_bf16=True)
+    assert rel_err(got[pick], ref) < TOL_BF16 * math.sqrt(21)
+    fp = folded_params(params)
+    got_f = run_net_bf16(layers, fp, x, folded=True)
+    ref_f = oracle.forward(layers, fp, x[pick], mirror_bf16=True, fold="given")
+    assert np.isfinite(got_f).all() and (got_f >= 0).all()
+    assert rel_err(got_f[pick], ref_f) < TOL_BF16 * math.sqrt(9)

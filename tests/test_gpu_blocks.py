@@ -101,3 +101,16 @@ def test_config2_through_net_fwd_full_batch_sampled():
         ref = oracle.forward(layers, params, x[pick])
         assert rel_err(got[pick], ref) < TOL_F32
         assert np.isfinite(got).all() and (got >= 0).all()
+
+
+def test_config3_alexnet_front_full_batch_sampled():
+    """Config 3 at its full batch of 128 as the benchmark launches it; the oracle recomputes two images."""
+    x = workloads.make_input(3)
+    assert x.shape == (128, 3, 227, 227)
+    pick = [0, 127]
+    for form, fuse in (("original", False), ("slim", True)):
+        layers = workloads.CONFIGS[3][form]
+        params = workloads.make_params(3, form)
+        got = run_net(layers, params, x, fuse_relu=fuse)
+        assert got.shape[0] == 128 and np.isfinite(got).all() and (got >= 0).all()
+        assert rel_err(got[pick], oracle.forward(layers, params, x[pick])) < TOL_F32
