@@ -322,6 +322,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
         if constexpr (TM > 1) fa[KS][1] = ds_read16<4096>(pa);
         if constexpr (TM > 2) fa[KS][2] = ds_read16<8192>(pa);
         if constexpr (TM > 3) fa[KS][3] = ds_read16<12288>(pa);
+        if constexpr (TM > 4) fa[KS][4] = ds_read16<16384>(pa);
+        if constexpr (TM > 5) fa[KS][5] = ds_read16<20480>(pa);
         fb[KS][0] = ds_read16<0>(pb);
         if constexpr (TN > 1) fb[KS][1] = ds_read16<4096>(pb);
         if constexpr (TN > 2) fb[KS][2] = ds_read16<8192>(pb);
@@ -522,6 +524,10 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
         case 10: return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);  // 32 x 128
         case 11: return launch_cfg<2, 1, 1, 4, 2, 2>(a, st);
         case 12: return launch_cfg<4, 2, 1, 4, 2, 1>(a, st);  // 128 x 256, wave tile 128 x 64
+        case 13: return launch_cfg<6, 1, 1, 4, 2, 2>(a, st);  // 192 x 128
+        case 14: return launch_cfg<3, 2, 1, 4, 2, 1>(a, st);  // 96 x 256
+        case 15: return launch_cfg<4, 1, 1, 4, 2, 2>(a, st);  // 128 x 128, wave tile 128 x 32
+        case 16: return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);  // 96 x 128
         default: break;
         }
     }
@@ -532,6 +538,7 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
     // bursts interleave, beat one large tile.
     if (g.K <= 32) return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);       // 32 x 256 tiles, 2 workgroups per CU
     if (g.Ng <= 8192) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);    // few pixels: 32 x 128 tiles, 3 per CU
+    if (g.K >= 192 && g.K % 96 == 0 && g.K % 64 != 0) return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);   // 192, 288 filters: 96 x 128 tiles
     return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                      // 64 x 128 tiles, 2 per CU
 }
 

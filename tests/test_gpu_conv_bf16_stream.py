@@ -65,6 +65,8 @@ CASES = [
     (1, 8, 3, 3, 8, 3, 3, 1, 1),            # tiny
     (2, 96, 70, 70, 72, 3, 3, 1, 1),        # many pixels (64 x 128 tiles) with slices running over filter rows
     (1, 24, 200, 200, 40, 5, 5, 2, 2),      # the same at stride 2, 5x5
+    (1, 64, 100, 100, 192, 3, 3, 1, 1),     # 192 filters: 96 x 128 tiles
+    (1, 32, 96, 96, 288, 5, 5, 1, 2),       # 288 filters, slices running over filter rows
 ]
 
 
