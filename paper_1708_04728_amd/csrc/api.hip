@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <new>
+#include <algorithm>
 #include <vector>
 
 #include "dr_internal.h"
@@ -186,6 +187,39 @@ bool conv_wants_padding(const dr_tensor& xd, const dr_conv& cd)
 int padded_conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias,
                     const dr_tensor& yd, void* y, Arena& ar, hipStream_t st)
 {
+    if (cd.c <= 4 && cd.r <= 8 && cd.s <= 8 && cd.stride_w % 2 == 0 && (double)yd.h * yd.w <= 65536.0 && (double)yd.n * yd.h * yd.w < 16777216.0) {
+        // packed form: 4 channels per pixel, padding laid out physically (launch_conv_bf16_stem)
+        const int hp = std::max(xd.h + 2 * cd.pad_h, (yd.h - 1) * cd.stride_h + 8);
+        const int wp = (std::max(xd.w + 2 * cd.pad_w, (yd.w - 1) * cd.stride_w + 8) + 7) / 8 * 8;
+        const size_t xbytes = (size_t)xd.n * hp * wp * 8;
+        if (xbytes < (1ull << 31)) {
+            void* xbuf = ar.take(xbytes);
+            void* wbuf = ar.take((size_t)cd.k * 512);
+            if (ar.measure) return DR_OK;
+            if (!xbuf || !wbuf) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
+            if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
+            if (xd.c != cd.c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd.c, cd.c);
+            const dr_tensor o = conv_out(xd, cd);
+            if (yd.n != o.n || yd.h != o.h || yd.w != o.w || yd.c != cd.k || yd.dtype != xd.dtype || yd.layout != xd.layout)
+                return fail(DR_ERR_SHAPE, "%s: output descriptor does not match the layer", who);
+            ConvGeom g;
+            g.N = xd.n; g.C = xd.c; g.H = xd.h; g.W = xd.w;
+            g.K = cd.k; g.R = cd.r; g.S = cd.s;
+            g.sh = cd.stride_h; g.sw = cd.stride_w; g.ph = cd.pad_h; g.pw = cd.pad_w;
+            g.P = o.h; g.Q = o.w;
+            g.Kg = cd.c * cd.r * cd.s;
+            g.Ng = o.n * o.h * o.w;
+            g.y_ctot = yd.c; g.y_coff = 0;
+            g.relu = cd.relu != 0;
+            g.res_ctot = 0;
+            g.w_krsc = cd.filter_layout == DR_KRSC;
+            g.nhwc = 1;
+            g.c_logical = 0;
+            DR_TRY(launch_stem_pack_bf16(x, xbuf, xd.n, xd.c, xd.h, xd.w, cd.pad_h, cd.pad_w, hp, wp, st));
+            DR_TRY(launch_stem_filters_bf16(w, wbuf, cd.k, cd.c, cd.r, cd.s, g.w_krsc, st));
+            return launch_conv_bf16_stem(g, (const uint16_t*)xbuf, hp, wp, (const uint16_t*)wbuf, bias, (uint16_t*)y, st);
+        }
+    }
     const int Cp = (cd.c + 7) / 8 * 8;
     dr_tensor xp = xd;
     xp.c = Cp;

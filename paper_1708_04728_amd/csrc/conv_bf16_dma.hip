@@ -67,6 +67,7 @@ struct DArgs {
     int vec_ok;               // 16-byte stores / bias / residual accesses are aligned
     int pointwise;            // 1x1 filter, stride 1, no padding
     int step_img, step_p, step_q;   // 32 pixels as (images, rows, columns) of the output
+    int stem_hp, stem_wp;     // rows / pixels per row of the padded 4-channel input copy (0: ordinary input)
 };
 
 // Workgroup barrier between the slices.  A fence would make the compiler wait for every outstanding
@@ -232,11 +233,18 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
 #pragma unroll
         for (int i = 0; i < B_PER; ++i) {
             const int n = n_first + i * 32;
-            const int ih0 = p * g.sh - g.ph, iw0 = q * g.sw - g.pw;
-            b_base[i] = (((img * g.H + ih0) * g.W + iw0) * g.C + lc * 8) * 2;
-            const unsigned wv = bit_range(max(0, -iw0), min(g.S - 1, g.W - 1 - iw0));
-            const unsigned hv = n < g.Ng ? bit_range(max(0, -ih0), min(g.R - 1, g.H - 1 - ih0)) : 0u;   // no row of a pixel beyond the tensor
-            b_mask[i] = (~wv & 0xFFFFu) | (hv << 16);
+            if (a.stem_wp) {
+                // packed small-channel input (see launch_conv_bf16_stem): chunk lc of a slice is pixel pair lc & 3 of
+                // window row lc >> 2; nothing is ever outside the padded copy
+                b_base[i] = ((img * a.stem_hp + p * g.sh + (lc >> 2)) * a.stem_wp + q * g.sw + 2 * (lc & 3)) * 8;
+                b_mask[i] = n < g.Ng ? 0xFFFFEu : 0xFFFFu;
+            } else {
+                const int ih0 = p * g.sh - g.ph, iw0 = q * g.sw - g.pw;
+                b_base[i] = (((img * g.H + ih0) * g.W + iw0) * g.C + lc * 8) * 2;
+                const unsigned wv = bit_range(max(0, -iw0), min(g.S - 1, g.W - 1 - iw0));
+                const unsigned hv = n < g.Ng ? bit_range(max(0, -ih0), min(g.R - 1, g.H - 1 - ih0)) : 0u;   // no row of a pixel beyond the tensor
+                b_mask[i] = (~wv & 0xFFFFu) | (hv << 16);
+            }
             q += a.step_q;
             if (q >= g.Q) { q -= g.Q; ++p; }
             p += a.step_p;
@@ -508,6 +516,7 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
     a.step_img = 32 / (g.P * g.Q);
     a.step_p = (32 % (g.P * g.Q)) / g.Q;
     a.step_q = 32 % g.Q;
+    a.stem_hp = a.stem_wp = 0;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y) && (!residual || (g.res_ctot % 8 == 0 && aligned16(residual)));
 #ifdef DR_TUNE
     if (const char* e = getenv("DR_BF16_CFG")) {
@@ -540,6 +549,48 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
     if (g.Ng <= 8192) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);    // few pixels: 32 x 128 tiles, 3 per CU
     if (g.K >= 192 && g.K % 96 == 0 && g.K % 64 != 0) return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);   // 192, 288 filters: 96 x 128 tiles
     return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                      // 64 x 128 tiles, 2 per CU
+}
+
+// Convolution of an input with at most 4 channels (the 3-channel network input), even column stride,
+// filters of at most 8x8 taps.  The caller has copied the input into xp[N][hp][wp][4]: zero padding laid
+// out physically (the original pixel (y, x) sits at (y + pad_h, x + pad_w)), channels padded to 4,
+// hp >= (P-1) stride_h + 8, wp >= (Q-1) stride_w + 8 and a multiple of 8; and the filters into
+// wp8[K][8][8][4] with zeros beyond R, S, C.  One pixel is 8 bytes, so a 16-byte chunk is a pixel pair
+// and, with an even stride, every window starts on a chunk.  A slice of 64 contraction elements is
+// two window rows of 8 taps x 4 channels: 4 slices per tile, no padding tests, all loads aligned.  The
+// streaming kernel runs it as a 4-"tap" convolution over 64 "channels" whose per-lane chunk offsets
+// come from the stem branch of its tile setup.
+int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias,
+                          uint16_t* y, hipStream_t st)
+{
+    TraceScope trace("conv_bf16", &real, real.Ng, st);
+    ConvGeom g = real;
+    g.C = 64; g.R = 4; g.S = 1; g.Kg = 256;
+    g.W = wp / 8;                 // so that one "tap row" of W * C * 2 bytes is two rows of the padded copy
+    g.ph = g.pw = 0;
+    g.w_krsc = 1; g.nhwc = 1;
+    DArgs a;
+    a.x = xp; a.w = wp8; a.bias = bias; a.res = nullptr; a.y = y; a.g = g;
+    a.grid_m = a.grid_n = 0;
+    a.x_bytes = (int)((size_t)real.N * hp * wp * 8);
+    a.w_bytes = (int)((size_t)real.K * 256 * 2);
+    a.c8 = 8; a.run_chunks = 8; a.slices_per_run = 1; a.magic_c8 = (unsigned)((0x100000000ull + 7) / 8);
+    a.m_pq = ((1ull << 40) + (unsigned)(g.P * g.Q) - 1) / (unsigned)(g.P * g.Q);
+    a.m_q = ((1ull << 40) + (unsigned)g.Q - 1) / (unsigned)g.Q;
+    a.pointwise = 0;
+    a.step_img = 32 / (g.P * g.Q);
+    a.step_p = (32 % (g.P * g.Q)) / g.Q;
+    a.step_q = 32 % g.Q;
+    a.stem_hp = hp; a.stem_wp = wp;
+    a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y);
+    if (g.K <= 32) return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);
+    if (g.Ng <= 8192) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);
+    return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);
+}
+
+bool conv_bf16_stem_eligible(const ConvGeom& g)
+{
+    return g.nhwc && g.C <= 4 && g.R <= 8 && g.S <= 8 && g.sw % 2 == 0 && g.Ng < (1 << 24) && (long)g.P * g.Q <= 65536;
 }
 
 }  // namespace dr

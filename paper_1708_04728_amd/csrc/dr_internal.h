@@ -55,6 +55,11 @@ bool conv_bf16_dma_eligible(const ConvGeom& g, const void* x, const void* w);
 int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
                          const uint16_t* residual, uint16_t* y, hipStream_t st);
 
+// conv_bf16_dma.hip: inputs of at most 4 channels through a padded 4-channel copy (see the definition)
+bool conv_bf16_stem_eligible(const ConvGeom& g);
+int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias,
+                          uint16_t* y, hipStream_t st);
+
 // pointwise.hip
 int launch_pack_filters(int dtype, const void* w_kcrs, void* w_krsc, int K, int C, int RS, hipStream_t st);
 int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st);
@@ -76,6 +81,9 @@ int launch_bn_nhwc(const dr_tensor& d, const void* x, void* y, const float* gamm
 // bf16 channel padding to a multiple of 8 (pixels x C -> pixels x Cp; filters KCRS or KRSC -> KRSC with Cp channels)
 int launch_pad_channels_bf16(const void* x, void* y, size_t pixels, int C, int Cp, hipStream_t st);
 int launch_pad_filters_bf16(const void* w, void* y, int K, int C, int RS, int Cp, int krsc, hipStream_t st);
+// the copies launch_conv_bf16_stem takes: xp[N][hp][wp][4] and wp8[K][8][8][4]
+int launch_stem_pack_bf16(const void* x, void* xp, int N, int C, int H, int W, int pad_h, int pad_w, int hp, int wp, hipStream_t st);
+int launch_stem_filters_bf16(const void* w, void* wp8, int K, int C, int R, int S, int krsc, hipStream_t st);
 int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* y, int N, int I, int O, hipStream_t st);
 int launch_softmax(int dtype, const void* x, float* y, int N, int O, hipStream_t st);
 

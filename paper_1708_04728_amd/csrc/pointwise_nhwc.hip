@@ -415,7 +415,59 @@ __global__ __launch_bounds__(256) void pad_filters_kernel(const uint16_t* __rest
     }
 }
 
+// xp[n][yy][xx][0..3] = x[n][yy - pad_h][xx - pad_w][0..C) where that pixel exists, else 0: one thread per pixel of xp
+__global__ __launch_bounds__(256) void stem_pack_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ xp, int C, int H, int W,
+                                                        int pad_h, int pad_w, int hp, int wp, size_t total)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int xx = (int)(i % wp);
+        const size_t t = i / wp;
+        const int yy = (int)(t % hp);
+        const size_t n = t / hp;
+        const int yi = yy - pad_h, xi = xx - pad_w;
+        uint32_t e[4] = {0u, 0u, 0u, 0u};
+        if ((unsigned)yi < (unsigned)H && (unsigned)xi < (unsigned)W) {
+            const uint16_t* src = x + ((n * H + yi) * W + xi) * C;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) e[c] = c < C ? src[c] : 0u;
+        }
+        *reinterpret_cast<uint2*>(xp + i * 4) = make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
+    }
+}
+
+// wp8[k][r][s][c] (8 x 8 x 4 per filter) = w[k][c][r][s] (KCRS) or w[k][r][s][c] (KRSC) inside R x S x C, else 0
+__global__ __launch_bounds__(256) void stem_filters_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ y, int K, int C, int R,
+                                                           int S, int krsc)
+{
+    const int total = K * 256;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        const int c = i & 3, s = (i >> 2) & 7, r = (i >> 5) & 7, k = i >> 8;
+        uint16_t v = 0;
+        if (c < C && r < R && s < S) v = krsc ? w[((k * R + r) * S + s) * C + c] : w[((k * C + c) * R + r) * S + s];
+        y[i] = v;
+    }
+}
+
 }  // namespace
+
+int launch_stem_pack_bf16(const void* x, void* xp, int N, int C, int H, int W, int pad_h, int pad_w, int hp, int wp, hipStream_t st)
+{
+    TraceScope trace("conv_pad", nullptr, (long long)((size_t)N * hp * wp * 4), st);
+    const size_t total = (size_t)N * hp * wp;
+    if (total == 0) return DR_OK;
+    hipLaunchKernelGGL(stem_pack_kernel, dim3(blocks_for(total, 256, 256 * 64)), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)xp, C, H, W,
+                       pad_h, pad_w, hp, wp, total);
+    return check_launch("stem_pack");
+}
+
+int launch_stem_filters_bf16(const void* w, void* wp8, int K, int C, int R, int S, int krsc, hipStream_t st)
+{
+    TraceScope trace("conv_pad", nullptr, (long long)K * 256, st);
+    if (K == 0) return DR_OK;
+    hipLaunchKernelGGL(stem_filters_kernel, dim3(blocks_for((size_t)K * 256, 256, 1024)), dim3(256), 0, st, (const uint16_t*)w, (uint16_t*)wp8, K, C,
+                       R, S, krsc);
+    return check_launch("stem_filters");
+}
 
 int launch_pad_channels_bf16(const void* x, void* y, size_t pixels, int C, int Cp, hipStream_t st)
 {

@@ -178,3 +178,30 @@ def test_config4_resnet_stage_full_batch_sampled():
     ref_f = oracle.forward(layers, fp, x[pick], mirror_bf16=True, fold="given")
     assert np.isfinite(got_f).all() and (got_f >= 0).all()
     assert rel_err(got_f[pick], ref_f) < TOL_BF16 * math.sqrt(9)
+
+
+@pytest.mark.parametrize("case", [
+    # N, C, H, W, K, R, stride, pad
+    (2, 3, 32, 30, 64, 7, 2, 3),     # the GoogLeNet / ResNet stem shape class: packed 4-channel form
+    (1, 3, 41, 37, 24, 7, 4, 3),     # stride 4 (slim stem), ragged sizes, 24 filters
+    (2, 1, 17, 19, 40, 3, 2, 0),     # one channel, no padding
+    (1, 4, 20, 20, 72, 5, 2, 2),     # four channels, 5x5
+    (2, 3, 12, 14, 16, 3, 1, 1),     # odd column stride: channels padded to 8 instead
+    (1, 6, 9, 9, 32, 3, 2, 1),       # six channels: padded to 8
+])
+def test_small_channel_first_layer_through_net(case):
+    """Convolutions on inputs with fewer than 8 channels take copies with padded channels inside dr_net_fwd
+    (the zeros add nothing): parity against the oracle on the unpadded problem, ReLU in the store."""
+    N, C, H, W, K, R, stride, pad = case
+    rng = np.random.default_rng(1234 + C * 100 + R)
+    x = workloads.round_to_bf16(rng.standard_normal((N, C, H, W)).astype(np.float32))
+    w = workloads.round_to_bf16(rng.standard_normal((K, C, R, R)).astype(np.float32) * np.float32(np.sqrt(2.0 / (C * R * R))))
+    b = (rng.standard_normal(K) * 0.1).astype(np.float32)
+    layers = [workloads.conv(K, R, stride, pad), workloads.relu()]
+    params = [{"w": w, "b": b}]
+    ref = oracle.forward(layers, params, x)
+    got = run_net_bf16(layers, params, x, fuse_relu=True)
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) < TOL_BF16
+    got2 = run_net_bf16(layers, params, x, fuse_relu=False)
+    assert np.array_equal(got, got2)
