@@ -164,6 +164,11 @@ typedef struct { int n_steps; dr_step steps[DR_MAX_STEPS]; } dr_branch;
                               (that convolution then also applies its ReLU in the store) */
 #define DR_FUSE_STACK  4   /* Eq. (12): first-step 1x1 convolutions that read the module input run as
                               one convolution with stacked filters (needs DR_FUSE_RELU) */
+#define DR_SERIAL_BRANCHES 8 /* run the branches one after another on the caller's stream.  Without it
+                              branches 1.. run on streams the library owns (per host thread and device,
+                              created on first use, default priority), forked from the caller's stream
+                              by an event before the module and joined to it by events before the
+                              concat: to the caller the module is still one piece of work on `stream` */
 typedef struct { int n_branches; dr_branch branches[DR_MAX_BRANCHES]; int mode; } dr_inception;
 
 /* Bytes of workspace dr_inception_fwd needs for input xd. */

@@ -22,7 +22,7 @@ DR_KCRS, DR_KRSC = 0, 1
 DR_NCHW, DR_NHWC = 0, 1
 DR_MAX_BRANCHES, DR_MAX_STEPS = 8, 4
 DR_STEP_CONV, DR_STEP_MAXPOOL = 0, 1
-DR_FUSE_RELU, DR_FUSE_CONCAT, DR_FUSE_STACK = 1, 2, 4
+DR_FUSE_RELU, DR_FUSE_CONCAT, DR_FUSE_STACK, DR_SERIAL_BRANCHES = 1, 2, 4, 8
 (DR_LAYER_CONV, DR_LAYER_RELU, DR_LAYER_LRN, DR_LAYER_MAXPOOL, DR_LAYER_INCEPTION, DR_LAYER_BOTTLENECK,
  DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX) = range(9)
 

@@ -274,18 +274,60 @@ int inception_validate(const dr_tensor& xd, const dr_inception& d, dr_tensor* ou
     return DR_OK;
 }
 
+// Streams and events for running the branches of a module side by side.  Branch 0 stays on the caller's
+// stream; the others run on these streams between a fork event (recorded on the caller's stream before
+// the module) and one join event per branch (awaited by the caller's stream before the concat, or before
+// whatever the caller enqueues next).  One set per host thread and device, created on first use, default
+// priority, never destroyed.  Events are handed out round-robin: a wait refers to the record that
+// preceded it, so an event can be recorded again once its wait has been enqueued.
+struct BranchStreams {
+    int dev = -1;
+    hipStream_t s[DR_MAX_BRANCHES - 1];
+    hipEvent_t ev[64];
+    unsigned next = 0;
+    hipEvent_t event() { return ev[next++ & 63]; }
+};
+BranchStreams* branch_streams()
+{
+    static thread_local BranchStreams pool;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    if (pool.dev != dev) {
+        for (auto& s : pool.s)
+            if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        for (auto& e : pool.ev)
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        pool.dev = dev;
+    }
+    return &pool;
+}
+
 // Runs (or, with a measuring arena, only plans) one module.  y may be NULL when measuring.
 int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, ParamCursor& wts, ParamCursor& bss,
-                  const dr_tensor& yd, void* y, Arena& ar, hipStream_t st)
+                  const dr_tensor& yd, void* y, Arena& ar, hipStream_t main_st)
 {
     const char* who = "dr_inception_fwd";
     const bool fuse_relu = d.mode & DR_FUSE_RELU, fuse_cat = d.mode & DR_FUSE_CONCAT;
     ConcatSeg segs[DR_MAX_BRANCHES];
     int nseg = 0, c_off = 0;
+    // A trace of every kernel (no label filter) is there to time each kernel on its own: it runs the
+    // branches in turn.
+    BranchStreams* bs = nullptr;
+    hipEvent_t fork = nullptr;
+    const bool full_trace = g_trace.active && !g_trace.filter[0];
+    if (!(d.mode & DR_SERIAL_BRANCHES) && d.n_branches > 1 && !ar.measure && !full_trace) {
+        bs = branch_streams();
+        if (!bs) return fail(DR_ERR_HIP, "%s: cannot create the branch streams", who);
+        fork = bs->event();
+        if (hipEventRecord(fork, main_st) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipEventRecord failed", who);
+    }
     for (int b = 0; b < d.n_branches; ++b) {
         const dr_branch& br = d.branches[b];
         dr_tensor t = xd;
         const void* cur = x;
+        const bool side = bs && b > 0;
+        const hipStream_t st = side ? bs->s[b - 1] : main_st;
+        if (side && hipStreamWaitEvent(st, fork, 0) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipStreamWaitEvent failed", who);
         for (int s = 0; s < br.n_steps; ++s) {
             const dr_step& stp = br.steps[s];
             const bool last = s == br.n_steps - 1;
@@ -319,8 +361,13 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
             }
         }
         c_off += t.c;
+        if (side) {
+            const hipEvent_t done = bs->event();
+            if (hipEventRecord(done, st) != hipSuccess || hipStreamWaitEvent(main_st, done, 0) != hipSuccess)
+                return fail(DR_ERR_HIP, "%s: joining branch %d failed", who, b);
+        }
     }
-    if (nseg && !ar.measure) DR_TRY(launch_concat(yd, nseg, segs, y, st));
+    if (nseg && !ar.measure) DR_TRY(launch_concat(yd, nseg, segs, y, main_st));
     return DR_OK;
 }
 

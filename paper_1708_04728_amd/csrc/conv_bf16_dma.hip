@@ -24,7 +24,7 @@
 // tiles nt, nt + stride, ... so that the store of one tile overlaps the loads of the next.  One barrier
 // per slice.  The compiler makes every LDS read it knows of wait for ALL outstanding loads that write
 // LDS, which would empty the ring once per slice; the operand reads are therefore issued as inline
-// assembly with their own lgkmcnt waits, and the bias lives in registers rather than in LDS.
+// assembly with their own lgkmcnt waits, and the bias is copied from LDS into registers once.
 //
 // Store.  Accumulator register v of a 32x32 tile holds row 8 (v / 4) + 4 half + v % 4 of column
 // lane % 32.  One v_permlane32_swap per register pair gives every lane 8 consecutive output channels
@@ -102,6 +102,14 @@ __device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t r, unsigned
 #endif
 }
 
+// The same with 4 bytes per lane: lane l fills bytes [4 l, 4 l + 4) of the 256-byte block at `lds`.
+__device__ __forceinline__ void load_to_lds4(__amdgpu_buffer_rsrc_t r, void* lds, int voff)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)lds, 4, voff, 0, 0, 0);
+#endif
+}
+
 // LDS reads the compiler does not see (see the header): the data is valid after wait_lgkm + touch.
 template <int OFF>
 __device__ __forceinline__ u32x4 ds_read16(unsigned addr)
@@ -143,9 +151,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
     constexpr int WM = TM * 32, WN = TN * 32, BM = WGM * WM, BN = WGN * WN;
     constexpr int A_PER = BM / 32, B_PER = BN / 32, L = A_PER + B_PER;   // loads per lane and slice
     constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
-    static_assert(WGM * WGN == 4 && NS >= 2 && (NS - 1) * L < 64, "bad configuration");
+    static_assert(WGM * WGN == 4 && NS >= 2 && (NS - 1) * L < 63 && BM <= 256, "bad configuration");
 
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
+    __shared__ __attribute__((aligned(1024))) float bias_lds[256];
     const unsigned ring_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)ring;
 
     const ConvGeom& g = a.g;
@@ -165,14 +174,15 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, a.w_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rbias = __builtin_amdgcn_make_buffer_rsrc((void*)a.bias, 0, a.bias ? g.K * 4 : 0, 0x00020000);
 
     // ---- persistent walk: workgroup b keeps channel block mt = b % grid_m and visits the pixel tiles
     // nt0, nt0 + gn, ... (gn = workgroups per channel block).  Consecutive workgroup ids are dealt
     // round-robin to the 8 XCDs; the remap gives each XCD a contiguous range of b, so that the
     // workgroups sharing a pixel tile share an L2.
     const int G = gridDim.x;
-    int bid = blockIdx.x;
-    if ((G & 7) == 0) bid = (bid & 7) * (G >> 3) + (bid >> 3);
+    const int xcd = blockIdx.x & 7;
+    const int bid = xcd * (G >> 3) + min(xcd, G & 7) + (blockIdx.x >> 3);
     const int mt = bid % a.grid_m, nt0 = bid / a.grid_m, gn = G / a.grid_m;
     const int my_tiles = (a.grid_n - nt0 + gn - 1) / gn;
     const int nslices = g.R * a.slices_per_run;
@@ -185,26 +195,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
         const int m = mt * BM + i * 32 + lrow;
         a_voff[i] = m < g.K ? (m * g.Kg + lc * 8) * 2 : OOB;
     }
+    // The bias of the channel block travels like the operands, ahead of them: 4 bytes per lane straight
+    // into LDS (zeros beyond the last filter and without a bias), so that nothing in the prologue waits
+    // for a load of its own.  After the first barrier every lane copies its share into registers.
+    {
+        const int ml = wave * 64 + lane, m = mt * BM + ml;
+        load_to_lds4(rbias, bias_lds + wave * 64, (ml < BM && m < g.K) ? m * 4 : OOB);
+    }
     // after the store's lane exchange a lane owns channels mb .. mb + 7, mb = m_lane + 32 i + 16 qp
     const int m_lane = mt * BM + wm * WM + half * 8;
     float bias_r[TM][2][8];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int qp = 0; qp < 2; ++qp)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int m = m_lane + i * 32 + qp * 16 + e;
-                bias_r[i][qp][e] = (a.bias && m < g.K) ? a.bias[m] : 0.f;
-            }
-    // Use the bias values here, so that the compiler waits for their loads now: left alone it waits at the
-    // first use, in the store of every tile, with a vmcnt(0) that would also drain the operand ring.
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int qp = 0; qp < 2; ++qp)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(bias_r[i][qp][e]));
 
     // ---- loader state of the pixel tile being fetched
     int b_base[B_PER];            // byte offset of x[img][ih0][iw0][lc * 8] (may lie outside the tensor)
@@ -418,9 +418,31 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
 #pragma unroll
     for (int s = 0; s < NS; ++s)
         if (issued < total) { issue_slice(s); ++issued; }
-    if (NS - 1 < total) wait_vmcnt<(NS - 1) * L>();     // slice 0 has landed (this wave's part)
+    if (NS - 1 < total) wait_vmcnt<(NS - 1) * L>();     // the bias and slice 0 have landed (this wave's part)
     else wait_vmcnt<0>();
     ring_barrier();
+    {
+        const unsigned bl = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)bias_lds + (wm * WM + half * 8) * 4;
+        u32x4 bv[TM][2][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            bv[i][0][0] = ds_read16<0>(bl + i * 128);
+            bv[i][0][1] = ds_read16<16>(bl + i * 128);
+            bv[i][1][0] = ds_read16<64>(bl + i * 128);
+            bv[i][1][1] = ds_read16<80>(bl + i * 128);
+        }
+        wait_lgkm<0>();
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int qp = 0; qp < 2; ++qp)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    touch(bv[i][qp][h]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) bias_r[i][qp][4 * h + e] = __uint_as_float(bv[i][qp][h][e]);
+                }
+    }
     fetch_step(0, IC<0>{});
     fetch_step(0, IC<1>{});
     fetch_step(0, IC<2>{});
@@ -467,24 +489,42 @@ template <int TM, int TN, int WGM, int WGN, int NS, int OCC>
 int launch_cfg(DArgs a, hipStream_t st)
 {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    constexpr int LDS = NS * (BM + BN) * 128;
+    constexpr int LDS = NS * (BM + BN) * 128 + 1024;
     static_assert(LDS <= 160 * 1024, "LDS ring too large");
     a.grid_m = (a.g.K + BM - 1) / BM;
     a.grid_n = (a.g.Ng + BN - 1) / BN;
-    // workgroups per channel block: what the device holds at once, at most one per pixel tile, a
-    // multiple of 8 when possible (the XCD remap needs it)
+    // workgroups per channel block: what the device holds at once, at most one per pixel tile (a layer
+    // with fewer tiles than that runs in a single round)
     static_assert(OCC * LDS <= 160 * 1024, "the ring does not fit OCC times");
-    const int per_cu = OCC;
-    int gn = device_cus() * per_cu / a.grid_m;
+    int gn = device_cus() * OCC / a.grid_m;
     if (gn < 1) gn = 1;
     if (gn > a.grid_n) gn = a.grid_n;
-    if (gn >= 8) gn &= ~7;
     const unsigned G = (unsigned)(gn * a.grid_m);
     if (a.g.C % 64 == 0)
         hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true, OCC>), dim3(G), dim3(NT), 0, st, a);
     else
         hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, false, OCC>), dim3(G), dim3(NT), 0, st, a);
     return check_launch("conv_bf16");
+}
+
+// Tile choice, from sweeps over the ResNet / GoogLeNet layer shapes at batch 128.  The kernel is limited by
+// instruction issue and by how fast a compute unit's vector memory path feeds LDS, not by the matrix
+// cores: two workgroups of 64 or 96 filters x 128 pixels per compute unit beat one large tile.  Between
+// the two, the cost of a tile grows with its filter count (measured: about 0.44 + filters / 32) and the
+// number of rounds is tiles / resident workgroups, rounded up while it is small (a persistent workgroup
+// walks a whole number of tiles).
+inline float tile_rounds(int K, int Ng, int bm)
+{
+    const float r = (float)((K + bm - 1) / bm) * (float)((Ng + 127) / 128) / (float)(device_cus() * 2);
+    return r <= 1.f ? 1.f : (r < 3.f ? ceilf(r) : r);
+}
+int launch_auto(DArgs a, hipStream_t st)
+{
+    const int K = a.g.K, Ng = a.g.Ng;
+    if (K <= 32) return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);       // 32 x 256 tiles
+    const float c64 = tile_rounds(K, Ng, 64) * (0.44f + 2.f), c96 = tile_rounds(K, Ng, 96) * (0.44f + 3.f);
+    if (c96 < c64) return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);     // 96 x 128 tiles
+    return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                    // 64 x 128 tiles
 }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -524,7 +564,7 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
         case 1: return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);   // 32 x 256
         case 2: return launch_cfg<1, 2, 1, 4, 3, 1>(a, st);
         case 3: return launch_cfg<2, 2, 1, 4, 3, 1>(a, st);   // 64 x 256
-        case 4: return launch_cfg<2, 2, 1, 4, 2, 2>(a, st);
+        case 4: return launch_cfg<2, 2, 1, 4, 2, 1>(a, st);
         case 5: return launch_cfg<2, 4, 2, 2, 3, 1>(a, st);   // 128 x 256
         case 6: return launch_cfg<2, 2, 2, 2, 4, 1>(a, st);   // 128 x 128
         case 7: return launch_cfg<2, 2, 2, 2, 2, 2>(a, st);
@@ -533,22 +573,23 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
         case 10: return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);  // 32 x 128
         case 11: return launch_cfg<2, 1, 1, 4, 2, 2>(a, st);
         case 12: return launch_cfg<4, 2, 1, 4, 2, 1>(a, st);  // 128 x 256, wave tile 128 x 64
-        case 13: return launch_cfg<6, 1, 1, 4, 2, 2>(a, st);  // 192 x 128
+        case 13: return launch_cfg<6, 1, 1, 4, 2, 1>(a, st);  // 192 x 128
         case 14: return launch_cfg<3, 2, 1, 4, 2, 1>(a, st);  // 96 x 256
         case 15: return launch_cfg<4, 1, 1, 4, 2, 2>(a, st);  // 128 x 128, wave tile 128 x 32
         case 16: return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);  // 96 x 128
+        case 17: return launch_cfg<1, 1, 1, 4, 3, 2>(a, st);  // 32 x 128, deeper rings
+        case 18: return launch_cfg<1, 1, 1, 4, 6, 1>(a, st);
+        case 19: return launch_cfg<1, 1, 2, 2, 4, 2>(a, st);  // 64 x 64
+        case 20: return launch_cfg<1, 1, 2, 2, 3, 3>(a, st);
+        case 21: return launch_cfg<1, 1, 2, 2, 6, 1>(a, st);
+        case 22: return launch_cfg<2, 1, 1, 4, 4, 1>(a, st);  // 64 x 128, deeper rings
+        case 23: return launch_cfg<2, 1, 1, 4, 6, 1>(a, st);
+        case 24: return launch_cfg<1, 2, 1, 4, 4, 1>(a, st);  // 32 x 256, deeper ring
         default: break;
         }
     }
 #endif
-    // Tile choice, from sweeps over the ResNet / GoogLeNet layer shapes at batch 128.  The kernel is limited
-    // by how fast a compute unit's vector memory path feeds LDS (about 50-64 bytes per clock) and by
-    // instruction issue, not by the matrix cores: several small workgroups per compute unit, whose load
-    // bursts interleave, beat one large tile.
-    if (g.K <= 32) return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);       // 32 x 256 tiles, 2 workgroups per CU
-    if (g.Ng <= 8192) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);    // few pixels: 32 x 128 tiles, 3 per CU
-    if (g.K >= 192 && g.K % 96 == 0 && g.K % 64 != 0) return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);   // 192, 288 filters: 96 x 128 tiles
-    return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                      // 64 x 128 tiles, 2 per CU
+    return launch_auto(a, st);
 }
 
 // Convolution of an input with at most 4 channels (the 3-channel network input), even column stride,
@@ -583,9 +624,7 @@ int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int 
     a.step_q = 32 % g.Q;
     a.stem_hp = hp; a.stem_wp = wp;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y);
-    if (g.K <= 32) return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);
-    if (g.Ng <= 8192) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);
-    return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);
+    return launch_auto(a, st);
 }
 
 bool conv_bf16_stem_eligible(const ConvGeom& g)
