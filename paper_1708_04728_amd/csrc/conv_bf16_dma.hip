@@ -509,22 +509,28 @@ int launch_cfg(DArgs a, hipStream_t st)
 
 // Tile choice, from sweeps over the ResNet / GoogLeNet layer shapes at batch 128.  The kernel is limited by
 // instruction issue and by how fast a compute unit's vector memory path feeds LDS, not by the matrix
-// cores: two workgroups of 64 or 96 filters x 128 pixels per compute unit beat one large tile.  Between
-// the two, the cost of a tile grows with its filter count (measured: about 0.44 + filters / 32) and the
+// cores: two workgroups of 64, 96 or 128 filters x 128 pixels per compute unit beat one large tile.  Among
+// them, the cost of a tile grows with its filter count (measured: about 0.44 + filters / 32) and the
 // number of rounds is tiles / resident workgroups, rounded up while it is small (a persistent workgroup
 // walks a whole number of tiles).
-inline float tile_rounds(int K, int Ng, int bm)
+inline float tile_rounds(int K, int Ng, int bm, int bn)
 {
-    const float r = (float)((K + bm - 1) / bm) * (float)((Ng + 127) / 128) / (float)(device_cus() * 2);
+    const float r = (float)((K + bm - 1) / bm) * (float)((Ng + bn - 1) / bn) / (float)(device_cus() * 2);
     return r <= 1.f ? 1.f : (r < 3.f ? ceilf(r) : r);
 }
 int launch_auto(DArgs a, hipStream_t st)
 {
     const int K = a.g.K, Ng = a.g.Ng;
-    if (K <= 32) return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);       // 32 x 256 tiles
-    const float c64 = tile_rounds(K, Ng, 64) * (0.44f + 2.f), c96 = tile_rounds(K, Ng, 96) * (0.44f + 3.f);
-    if (c96 < c64) return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);     // 96 x 128 tiles
-    return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                    // 64 x 128 tiles
+    if (K <= 32) {
+        // fewer 256-pixel tiles than compute units: halve the tiles
+        if ((Ng + 255) / 256 < device_cus()) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);   // 32 x 128 tiles
+        return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);                                        // 32 x 256 tiles
+    }
+    const float c64 = tile_rounds(K, Ng, 64, 128) * (0.44f + 2.f), c96 = tile_rounds(K, Ng, 96, 128) * (0.44f + 3.f);
+    const float r128 = tile_rounds(K, Ng, 128, 128), c128 = r128 * (0.44f + 4.f);   // pays only when it saves a round
+    if (r128 <= 1.f && c128 < c64 && c128 < c96) return launch_cfg<2, 2, 2, 2, 2, 2>(a, st);   // 128 x 128 tiles, 64 x 64 per wave
+    if (c96 < c64) return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);                  // 96 x 128 tiles
+    return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                                 // 64 x 128 tiles
 }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
