@@ -82,6 +82,55 @@ __global__ __launch_bounds__(256) void pool_nhwc_kernel(const T* __restrict__ x,
     }
 }
 
+// Average over the whole image (the 7x7 pooling in front of the classifier): 32 channel vectors x 8 pixel
+// groups per workgroup; a thread sums every 8th pixel with up to 8 loads in flight, the 8 partial sums
+// of a channel vector meet in LDS.
+template <typename T>
+__global__ __launch_bounds__(256) void global_avgpool_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int HW, int cgroups)
+{
+    constexpr int V = Store<T>::VN;
+    __shared__ float part[8][32][V + 1];
+    const int CV = C / V;
+    const int n = blockIdx.x / cgroups, cg = blockIdx.x - n * cgroups;
+    const int cl = threadIdx.x & 31, pg = threadIdx.x >> 5;
+    const int cv = cg * 32 + cl;
+    float s[V];
+#pragma unroll
+    for (int j = 0; j < V; ++j) s[j] = 0.f;
+    if (cv < CV) {
+        const T* xb = x + (size_t)n * HW * C + (size_t)cv * V;
+        for (int p0 = pg; p0 < HW; p0 += 64) {
+            float v[8][V];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                if (p0 + 8 * t < HW) Store<T>::ldv(xb + (size_t)(p0 + 8 * t) * C, v[t]);
+                else {
+#pragma unroll
+                    for (int j = 0; j < V; ++j) v[t][j] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int j = 0; j < V; ++j) s[j] += v[t][j];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) part[pg][cl][j] = s[j];
+    __syncthreads();
+    if (pg == 0 && cv < CV) {
+        float o[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            float a = 0.f;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) a += part[g][cl][j];
+            o[j] = a / (float)HW;
+        }
+        Store<T>::stv(y + (size_t)n * C + (size_t)cv * V, o);
+    }
+}
+
 // 3x3 max-pooling, the window of every pooling layer of the networks here: separable.  A thread owns
 // one output column q and one channel group and walks down a strip of PR output rows; per input row
 // it takes the maximum of the row's three window pixels (three 16-byte loads), and an output is the
@@ -148,6 +197,74 @@ __global__ __launch_bounds__(256) void maxpool3_nhwc_kernel(const T* __restrict_
     }
 }
 
+// The same for strides 1 and 2 with 16-byte vectors, all loads first: a thread fetches the 3 x NR input
+// vectors its strip of PR outputs needs (NR = (PR - 1) STRIDE + 3 rows) before it uses any of them, so
+// that it waits for memory once instead of once per input row.
+template <typename T> struct NegInfWord;
+template <> struct NegInfWord<float> { static constexpr uint32_t v = 0xFF800000u; };
+template <> struct NegInfWord<uint16_t> { static constexpr uint32_t v = 0xFF80FF80u; };
+template <typename T> __device__ __forceinline__ void unpack16(const uint4& r, float* v);
+template <> __device__ __forceinline__ void unpack16<float>(const uint4& r, float* v)
+{
+    v[0] = __uint_as_float(r.x); v[1] = __uint_as_float(r.y); v[2] = __uint_as_float(r.z); v[3] = __uint_as_float(r.w);
+}
+template <> __device__ __forceinline__ void unpack16<uint16_t>(const uint4& r, float* v)
+{
+    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+    }
+}
+
+template <typename T, int PR, int STRIDE>
+__global__ __launch_bounds__(256) void maxpool3_front_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int H, int W, int P,
+                                                             int Q, int pstrips, int qgroups, int bx_log2, int pad)
+{
+    constexpr int V = Store<T>::VN, NR = (PR - 1) * STRIDE + 3;
+    const int CV = C / V;
+    const int bx = 1 << bx_log2, by = 256 >> bx_log2;
+    const int tx = threadIdx.x & (bx - 1), ty = threadIdx.x >> bx_log2;
+    const unsigned qg = blockIdx.x % (unsigned)qgroups, t = blockIdx.x / (unsigned)qgroups;
+    const unsigned strip = t % (unsigned)pstrips, n = t / (unsigned)pstrips;
+    const int q = (int)qg * by + ty;
+    if (q >= Q) return;
+    const int p0 = (int)strip * PR;
+    const int w0 = q * STRIDE - pad, h0 = p0 * STRIDE - pad;
+    const T* xb = x + (size_t)n * H * W * C;
+    constexpr uint32_t NEG = NegInfWord<T>::v;
+    for (int cv = tx; cv < CV; cv += bx) {
+        uint4 raw[NR][3];
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                raw[r][c] = make_uint4(NEG, NEG, NEG, NEG);
+                if ((unsigned)(h0 + r) < (unsigned)H && (unsigned)(w0 + c) < (unsigned)W)
+                    raw[r][c] = *reinterpret_cast<const uint4*>(xb + ((size_t)(h0 + r) * W + (w0 + c)) * C + cv * V);
+            }
+        float rm[NR][V];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            float a[V], b[V], c[V];
+            unpack16<T>(raw[r][0], a);
+            unpack16<T>(raw[r][1], b);
+            unpack16<T>(raw[r][2], c);
+#pragma unroll
+            for (int j = 0; j < V; ++j) rm[r][j] = fmaxf(fmaxf(a[j], b[j]), c[j]);
+        }
+#pragma unroll
+        for (int i = 0; i < PR; ++i) {
+            if (p0 + i >= P) break;
+            float o[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) o[j] = fmaxf(fmaxf(rm[i * STRIDE][j], rm[i * STRIDE + 1][j]), rm[i * STRIDE + 2][j]);
+            Store<T>::stv(y + (((size_t)n * P + p0 + i) * Q + q) * C + cv * V, o);
+        }
+    }
+}
+
 template <typename T>
 int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, bool avg, hipStream_t st)
 {
@@ -164,6 +281,17 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
         // strips of 4 output rows (best in sweeps over the pooling layers of the networks here), 2 while the
         // launch would otherwise have fewer than ~2048 workgroups
         const long per_strip = (long)yd.n * qgroups;
+        if (vec && (p.stride_h == 1 || p.stride_h == 2)) {
+            const int PRF = p.stride_h == 1 ? 4 : 2, strips = (yd.h + PRF - 1) / PRF;
+            const dim3 gf((unsigned)(per_strip * strips));
+            if (p.stride_h == 1)
+                hipLaunchKernelGGL((maxpool3_front_kernel<T, 4, 1>), gf, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w,
+                                   strips, qgroups, bx_log2, p.pad_h);
+            else
+                hipLaunchKernelGGL((maxpool3_front_kernel<T, 2, 2>), gf, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w,
+                                   strips, qgroups, bx_log2, p.pad_h);
+            return check_launch("maxpool");
+        }
         int PR = 4;
         while (PR > 2 && per_strip * ((yd.h + PR - 1) / PR) < 2048) PR >>= 1;
         const int pstrips = (yd.h + PR - 1) / PR;
@@ -175,6 +303,12 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
             hipLaunchKernelGGL((maxpool3_nhwc_kernel<T, 1>), g3, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, PR,
                                pstrips, qgroups, bx_log2, p.stride_h, p.pad_h);
         return check_launch("maxpool");
+    }
+    if (avg && vec && yd.h == 1 && yd.w == 1 && p.kh == xd.h && p.kw == xd.w && p.pad_h == 0 && p.pad_w == 0) {
+        const int cgroups = (cv + 31) / 32;
+        hipLaunchKernelGGL((global_avgpool_nhwc_kernel<T>), dim3((unsigned)(yd.n * cgroups)), dim3(256), 0, st, (const T*)x, (T*)y, xd.c,
+                           xd.h * xd.w, cgroups);
+        return check_launch("avgpool");
     }
     const dim3 grid((unsigned)(yd.n * yd.h * qgroups)), block(256);
 #define DR_POOL(V, AVG) hipLaunchKernelGGL((pool_nhwc_kernel<T, V, AVG>), grid, block, 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, qgroups, bx_log2, p)

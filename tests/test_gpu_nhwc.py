@@ -150,9 +150,11 @@ def test_concat_bn_avgpool_nhwc(dtype):
         B.bn_fwd(xg, gpu(g), gpu(be), gpu(mu), gpu(var), eps, True, xg)
         torch.cuda.synchronize()
         assert rel_err(host_nhwc(xg), np.maximum(ref, 0)) < _tol(dtype)
-    x = _vals(rng, (4, 1024, 7, 7), dtype)
-    ref = oracle.avgpool(x, 7)
-    y = empty_nhwc(ref.shape, dtype)
-    B.avgpool_fwd(gpu_nhwc(x, dtype), B.pool_desc(7, 1), y)
-    torch.cuda.synchronize()
-    assert rel_err(host_nhwc(y), ref) < _tol(dtype)
+    # whole-image averages (the classifier's 7x7), also with a ragged last channel group and more than 64 pixels
+    for shape, win in (((4, 1024, 7, 7), 7), ((3, 72, 9, 9), 9), ((2, 264, 8, 8), 8)):
+        x = _vals(rng, shape, dtype)
+        ref = oracle.avgpool(x, win)
+        y = empty_nhwc(ref.shape, dtype)
+        B.avgpool_fwd(gpu_nhwc(x, dtype), B.pool_desc(win, 1), y)
+        torch.cuda.synchronize()
+        assert rel_err(host_nhwc(y), ref) < _tol(dtype)
