@@ -122,12 +122,15 @@ class Workload:
                     params_host.append({"w": workloads.round_to_bf16(wf) if bf16 else wf, "b": bf})
             else:
                 params_host = workloads.make_params(cfg_id, form)
-            net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT) if slim else 0,
+            net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if slim else 0,
                                     fuse_relu=slim, folded=folded, pack=self.dtype))
             xd = B.desc(self.x)
             y = G.empty_like_desc(net.output_desc(xd))
             ws = torch.empty(max(net.workspace_bytes(xd), 256), dtype=torch.uint8, device="cuda")
-            self.forms[form] = dict(net=net, y=y, ws=ws, params=G.flat_params(params_host, self.dtype, pack=True),
+            flat = G.flat_params(params_host, self.dtype, pack=True)
+            if slim and not folded and any(kind == "inception" for kind, _ in layers):
+                flat = G.stack_first_steps(layers, flat)      # the layout DR_FUSE_STACK takes (Eq. (12))
+            self.forms[form] = dict(net=net, y=y, ws=ws, params=flat,
                                     layers=layers, params_host=params_host, folded=folded)
 
     def run(self, form):

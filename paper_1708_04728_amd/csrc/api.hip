@@ -302,6 +302,73 @@ BranchStreams* branch_streams()
     return &pool;
 }
 
+// The stacked first steps of a module (see inception_run).  Marks the branches it has served in `stacked`
+// and leaves their step-0 outputs in `dst` (workspace buffers; NULL for a one-step branch that wrote y).
+// Serves nothing, without error, when the parameters are not laid out for it.
+int run_stacked_first_steps(const dr_tensor& xd, const void* x, const dr_inception& d, const ParamCursor& wts, const ParamCursor& bss,
+                            const dr_tensor& yd, void* y, Arena& ar, hipStream_t st, bool* stacked, void** dst)
+{
+    const char* who = "dr_inception_fwd";
+    const bool fuse_cat = d.mode & DR_FUSE_CONCAT;
+    int pidx = wts.i, c_off = 0, nb = 0, members[DR_MAX_BRANCHES], coffs[DR_MAX_BRANCHES], pidxs[DR_MAX_BRANCHES];
+    for (int b = 0; b < d.n_branches; ++b) {
+        const dr_branch& br = d.branches[b];
+        const dr_conv& c0 = br.steps[0].conv;
+        if (br.steps[0].kind == DR_STEP_CONV && c0.r == 1 && c0.s == 1 && c0.stride_h == 1 && c0.stride_w == 1 && c0.pad_h == 0 &&
+            c0.pad_w == 0 && c0.relu && nb < 4) {
+            members[nb] = b; coffs[nb] = c_off; pidxs[nb] = pidx; ++nb;
+        }
+        int c = xd.c;
+        for (int s = 0; s < br.n_steps; ++s)
+            if (br.steps[s].kind == DR_STEP_CONV) { c = br.steps[s].conv.k; ++pidx; }
+        c_off += c;
+    }
+    if (nb < 2) return DR_OK;
+    // back to back in memory, in branch order; every bank but the last a multiple of 8 filters
+    const char* w0 = (const char*)wts.p[pidxs[0]];
+    const char* b0 = bss.p ? (const char*)bss.p[pidxs[0]] : nullptr;
+    if (!w0) return DR_OK;
+    size_t woff = 0, boff = 0;
+    int ktot = 0;
+    for (int i = 0; i < nb; ++i) {
+        const dr_conv& c0 = d.branches[members[i]].steps[0].conv;
+        const char* bi = bss.p ? (const char*)bss.p[pidxs[i]] : nullptr;
+        if ((const char*)wts.p[pidxs[i]] != w0 + woff) return DR_OK;
+        if ((b0 == nullptr) != (bi == nullptr) || (b0 && bi != b0 + boff)) return DR_OK;
+        if (i + 1 < nb && c0.k % 8 != 0) return DR_OK;
+        woff += (size_t)c0.k * xd.c * 2;
+        boff += (size_t)c0.k * 4;
+        ktot += c0.k;
+    }
+    ConvGeom g;
+    g.N = xd.n; g.C = xd.c; g.H = xd.h; g.W = xd.w;
+    g.K = ktot; g.R = 1; g.S = 1;
+    g.sh = g.sw = 1; g.ph = g.pw = 0;
+    g.P = xd.h; g.Q = xd.w;
+    g.Kg = xd.c;
+    g.Ng = xd.n * xd.h * xd.w;
+    g.relu = 1;
+    g.res_ctot = 0;
+    g.w_krsc = 1;           // a 1x1 filter bank is the same array in both orders
+    g.nhwc = 1;
+    g.c_logical = 0;
+    if (g.Ng == 0 || !x || !conv_bf16_dma_eligible(g, x, w0)) return DR_OK;
+    ConvSplit sp;
+    sp.n = nb;
+    for (int i = 0; i < nb; ++i) {
+        const dr_branch& br = d.branches[members[i]];
+        const bool direct = br.n_steps == 1 && fuse_cat;
+        const int k = br.steps[0].conv.k;
+        void* buf = direct ? y : ar.take((size_t)g.Ng * k * 2);
+        if (!buf) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
+        sp.dst[i] = ConvDest{buf, direct ? yd.c : k, direct ? coffs[i] : 0, k};
+        dst[members[i]] = direct ? nullptr : buf;
+        stacked[members[i]] = true;
+    }
+    g.y_ctot = sp.dst[0].ctot; g.y_coff = sp.dst[0].c_offset;
+    return launch_conv_bf16_dma(g, (const uint16_t*)x, (const uint16_t*)w0, (const float*)b0, nullptr, (uint16_t*)sp.dst[0].y, st, &sp);
+}
+
 // Runs (or, with a measuring arena, only plans) one module.  y may be NULL when measuring.
 int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, ParamCursor& wts, ParamCursor& bss,
                   const dr_tensor& yd, void* y, Arena& ar, hipStream_t main_st)
@@ -310,6 +377,13 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
     const bool fuse_relu = d.mode & DR_FUSE_RELU, fuse_cat = d.mode & DR_FUSE_CONCAT;
     ConcatSeg segs[DR_MAX_BRANCHES];
     int nseg = 0, c_off = 0;
+    // DR_FUSE_STACK (Eq. (12)): first-step 1x1 convolutions on the module input run as one convolution
+    // when their filters (and biases) lie back to back in memory in branch order, so that they form the
+    // stacked filter bank as they are; each keeps its own destination.  bf16 channels-last only.
+    void* stacked_dst[DR_MAX_BRANCHES] = {};
+    bool stacked[DR_MAX_BRANCHES] = {};
+    if ((d.mode & DR_FUSE_STACK) && !ar.measure && xd.dtype == DR_BF16 && xd.layout == DR_NHWC && wts.p)
+        DR_TRY(run_stacked_first_steps(xd, x, d, wts, bss, yd, y, ar, main_st, stacked, stacked_dst));
     // A trace of every kernel (no label filter) is there to time each kernel on its own: it runs the
     // branches in turn.
     BranchStreams* bs = nullptr;
@@ -340,9 +414,9 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
                 const float* bias = (const float*)bss.next();
                 const bool direct = last && fuse_cat;   // writes its channel range of y, ReLU in the store
                 if (direct) cd.relu = relu_after;
-                void* dst = direct ? y : ar.take(tensor_bytes(o));
+                void* dst = direct ? y : (s == 0 && stacked[b]) ? stacked_dst[b] : ar.take(tensor_bytes(o));
                 if (!dst && !ar.measure) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
-                if (!ar.measure) {
+                if (!ar.measure && !(s == 0 && stacked[b])) {
                     if (!w) return fail(DR_ERR_NULL, "%s: missing weights of branch %d step %d", who, b, s);
                     DR_TRY(conv_run(who, t, cur, cd, w, bias, nullptr, 0, direct ? yd : o, dst, direct ? c_off : 0, st));
                     if (relu_after && !cd.relu) DR_TRY(launch_relu(o.dtype, dst, dst, tensor_elems(o), st));

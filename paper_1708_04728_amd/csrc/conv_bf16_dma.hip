@@ -68,6 +68,14 @@ struct DArgs {
     int pointwise;            // 1x1 filter, stride 1, no padding
     int step_img, step_p, step_q;   // 32 pixels as (images, rows, columns) of the output
     int stem_hp, stem_wp;     // rows / pixels per row of the padded 4-channel input copy (0: ordinary input)
+    // Stacked convolution (several filter banks on one input, Eq. (12)) whose channel ranges go to different
+    // tensors: channel m < split_end[0] goes to destination 0, m < split_end[1] to destination 1, ...
+    // (unused ends hold INT_MAX).  y_seg[d] is offset by the host so that channel m of pixel n lands at
+    // y_seg[d][n * ctot_seg[d] + m]; every range starts at a multiple of 8.  nsplit <= 1: everything goes to y.
+    int nsplit;
+    int split_end[3];
+    uint16_t* y_seg[4];
+    int ctot_seg[4];
 };
 
 // Workgroup barrier between the slices.  A fence would make the compiler wait for every outstanding
@@ -356,7 +364,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int n = nt * BN + wn * WN + j * 32 + l32;
-            uint16_t* yb = a.y + (size_t)n * g.y_ctot + g.y_coff;
+            uint16_t* yb = a.y + (size_t)n * g.y_ctot + g.y_coff;     // (replaced per channel group in a stacked convolution)
             const uint16_t* rb = a.res + (size_t)n * g.res_ctot;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -374,6 +382,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
                     }
                     const int mb = m_lane + i * 32 + qp * 16;     // first of this lane's 8 channels
                     if (n >= g.Ng || mb >= g.K) continue;
+                    if (a.nsplit > 1) {                           // (wave-uniform) pick this lane's destination
+                        const bool s1 = mb >= a.split_end[0], s2 = mb >= a.split_end[1], s3 = mb >= a.split_end[2];
+                        uint16_t* base = s3 ? a.y_seg[3] : s2 ? a.y_seg[2] : s1 ? a.y_seg[1] : a.y_seg[0];
+                        const int ct = s3 ? a.ctot_seg[3] : s2 ? a.ctot_seg[2] : s1 ? a.ctot_seg[1] : a.ctot_seg[0];
+                        yb = base + (size_t)n * ct;
+                    }
 #pragma unroll
                     for (int e = 0; e < 8; ++e) o[e] += bias_r[i][qp][e];
                     if (a.vec_ok && mb + 7 < g.K) {
@@ -545,7 +559,7 @@ bool conv_bf16_dma_eligible(const ConvGeom& g, const void* x, const void* w)
 }
 
 int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
-                         const uint16_t* residual, uint16_t* y, hipStream_t st)
+                         const uint16_t* residual, uint16_t* y, hipStream_t st, const ConvSplit* split)
 {
     DArgs a;
     a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g;
@@ -564,6 +578,25 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
     a.step_q = 32 % g.Q;
     a.stem_hp = a.stem_wp = 0;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y) && (!residual || (g.res_ctot % 8 == 0 && aligned16(residual)));
+    a.nsplit = 0;
+    if (split && split->n > 1) {
+        a.nsplit = split->n;
+        int start = 0;
+        for (int d = 0; d < 4; ++d) {
+            if (d < split->n) {
+                const ConvDest& s = split->dst[d];
+                a.y_seg[d] = (uint16_t*)s.y + s.c_offset - start;
+                a.ctot_seg[d] = s.ctot;
+                a.vec_ok = a.vec_ok && s.ctot % 8 == 0 && s.c_offset % 8 == 0 && aligned16(s.y);
+                start += s.k;
+                if (d < 3) a.split_end[d] = d + 1 < split->n ? start : 0x7FFFFFFF;
+            } else {
+                a.y_seg[d] = nullptr;
+                a.ctot_seg[d] = 0;
+                if (d < 3) a.split_end[d] = 0x7FFFFFFF;
+            }
+        }
+    }
 #ifdef DR_TUNE
     if (const char* e = getenv("DR_BF16_CFG")) {
         switch (atoi(e)) {
@@ -629,6 +662,7 @@ int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int 
     a.step_p = (32 % (g.P * g.Q)) / g.Q;
     a.step_q = 32 % g.Q;
     a.stem_hp = hp; a.stem_wp = wp;
+    a.nsplit = 0;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y);
     return launch_auto(a, st);
 }

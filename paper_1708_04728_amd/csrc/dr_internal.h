@@ -52,8 +52,14 @@ int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, co
 
 // conv_bf16_dma.hip: the main bf16 kernel (NHWC, KRSC filters, C % 8 == 0, 16-byte aligned tensors)
 bool conv_bf16_dma_eligible(const ConvGeom& g, const void* x, const void* w);
+// Destinations of a stacked convolution (Eq. (12)): the first k filters write channels [c_offset, c_offset + k)
+// of tensor y (ctot channels per pixel), the next destination takes the following filters, and so on.
+// Every k but the last is a multiple of 8, there is no residual, g.K is the sum of the k.  split = NULL or
+// n <= 1: the ordinary single destination (y, g.y_ctot, g.y_coff).
+struct ConvDest { void* y; int ctot, c_offset, k; };
+struct ConvSplit { int n; ConvDest dst[4]; };
 int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
-                         const uint16_t* residual, uint16_t* y, hipStream_t st);
+                         const uint16_t* residual, uint16_t* y, hipStream_t st, const ConvSplit* split = nullptr);
 
 // conv_bf16_dma.hip: inputs of at most 4 channels through a padded 4-channel copy (see the definition)
 bool conv_bf16_stem_eligible(const ConvGeom& g);

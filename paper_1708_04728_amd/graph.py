@@ -130,6 +130,37 @@ def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False, pac
     return out
 
 
+def stack_first_steps(layers, flat):
+    """Lays the filters (and biases) of every inception module's first-step 1x1 convolutions back to back
+    in one device buffer, in branch order, and returns the parameter list with views into those buffers.
+    That is the layout DR_FUSE_STACK looks for (Eq. (12): the stacked filter bank is then simply the
+    buffer).  `flat` is the list flat_params returned for `layers` (w, bias per convolution / fc)."""
+    out, i = list(flat), 0
+    for kind, p in layers:
+        if kind in ("conv", "fc"):
+            i += 2
+        elif kind == "inception":
+            first, j = [], i
+            for br in p["branches"]:
+                convs = [q for k_, q in br if k_ == "conv"]
+                if br and br[0][0] == "conv" and br[0][1]["r"] == 1 and br[0][1]["s"] == 1 and br[0][1]["stride"] == 1 and br[0][1]["pad"] == 0:
+                    first.append(j)
+                j += 2 * len(convs)
+            if len(first) > 1:
+                wbig = torch.cat([out[f].reshape(out[f].shape[0], -1) for f in first], dim=0).contiguous()
+                bbig = torch.cat([out[f + 1] for f in first], dim=0).contiguous()
+                k0 = 0
+                for f in first:
+                    k = out[f].shape[0]
+                    out[f] = wbig[k0:k0 + k].view(out[f].shape)
+                    out[f + 1] = bbig[k0:k0 + k]
+                    k0 += k
+            i = j
+        elif kind == "bottleneck":
+            raise NotImplementedError("stack_first_steps: layer lists with bottlenecks")
+    return out
+
+
 def flat_params(params, dtype="f32", device="cuda", pack=False):
     """Device tensors in the order dr_net_fwd expects: conv/fc -> w, bias; bn -> gamma, beta,
     mean, var (all fp32 except w).  pack: convolution filters whose channel count allows it are

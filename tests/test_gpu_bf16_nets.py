@@ -24,12 +24,16 @@ torch = pytest.importorskip("torch")
 
 
 def run_net_bf16(layers, params, x, fuse_relu=False, inception_mode=0, folded=False):
+    """inception_mode with DR_FUSE_STACK: the parameters are laid out for it (graph.stack_first_steps)."""
     xg = G.to_device(x, "bf16", nhwc=True)
     net = B.Net(G.net_descs(layers, x.shape[1], inception_mode=inception_mode, fuse_relu=fuse_relu, folded=folded, pack="bf16"))
     yd = net.output_desc(B.desc(xg))
     y = G.empty_like_desc(yd)
     ws = torch.empty(max(net.workspace_bytes(B.desc(xg)), 256), dtype=torch.uint8, device="cuda")
-    net.fwd(xg, G.flat_params(params, "bf16", pack=True), y, ws)
+    flat = G.flat_params(params, "bf16", pack=True)
+    if inception_mode & B.DR_FUSE_STACK:
+        flat = G.stack_first_steps(layers, flat)
+    net.fwd(xg, flat, y, ws)
     torch.cuda.synchronize()
     return G.to_host(y)
 
@@ -127,7 +131,7 @@ def test_config5_googlenet(form):
     params = workloads.make_params(5, form)
     x = workloads.make_input(5, 2)
     slim = form == "slim"
-    mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT) if slim else 0
+    mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if slim else 0
     worst, ref = teacher_forced(layers, params, x, fuse_relu=slim, inception_mode=mode)
     got = run_net_bf16(layers, params, x, fuse_relu=slim, inception_mode=mode)
     assert got.shape == (2, 1000, 1, 1)
@@ -142,6 +146,40 @@ def test_config5_googlenet(form):
     assert (np.argmax(got, axis=1) == np.argmax(ref, axis=1))[decided].all()
 
 
+@pytest.mark.parametrize("form", ["original", "slim"])
+@pytest.mark.parametrize("module", [3, 7, 11])
+def test_inception_stacked_first_steps(form, module):
+    """DR_FUSE_STACK (Eq. (12)): the first-step 1x1 convolutions of a module run as one convolution over the
+    stacked filter bank, each writing its own destination (the concat output for a one-step branch, a
+    workspace tensor otherwise).  Same result as one convolution per branch, bit for bit (every output
+    element accumulates the same products in the same order), with and without the fused concat; and
+    parameters that are not laid out back to back simply run branch by branch."""
+    layers_all = workloads.CONFIGS[5][form]
+    idx = [i for i, (k, _) in enumerate(layers_all) if k == "inception"][module % 9]
+    layer = layers_all[idx]
+    c_in = G._out_channels(layers_all[:idx], 3)
+    hw = 28 if module % 9 < 2 else (14 if module % 9 < 7 else 7)
+    rng = np.random.default_rng(100 + module)
+    x = workloads.round_to_bf16(np.abs(rng.standard_normal((3, c_in, hw, hw))).astype(np.float32))
+    counts = params_per_layer(layers_all)
+    params = workloads.make_params(5, form)[sum(counts[:idx]):sum(counts[:idx + 1])]
+    ref = oracle.forward([layer], params, x, mirror_bf16=True)
+    base = B.DR_FUSE_RELU | B.DR_FUSE_CONCAT
+    plain = run_net_bf16([layer], params, x, inception_mode=base)
+    assert rel_err(plain, ref) < TOL_BF16 * math.sqrt(2)
+    for mode in (base | B.DR_FUSE_STACK, B.DR_FUSE_RELU | B.DR_FUSE_STACK):
+        got = run_net_bf16([layer], params, x, inception_mode=mode)
+        assert np.array_equal(got, plain), (form, module, mode)
+    # the flag without the layout: falls back to one convolution per branch
+    xg = G.to_device(x, "bf16", nhwc=True)
+    net = B.Net(G.net_descs([layer], c_in, inception_mode=base | B.DR_FUSE_STACK, pack="bf16"))
+    y = G.empty_like_desc(net.output_desc(B.desc(xg)))
+    ws = torch.empty(max(net.workspace_bytes(B.desc(xg)), 256), dtype=torch.uint8, device="cuda")
+    net.fwd(xg, G.flat_params(params, "bf16", pack=True), y, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(G.to_host(y), plain)
+
+
 # ---- full sizes, in the launch configuration the benchmark times -------------------------------------------
 # The whole batch runs on the GPU; the oracle recomputes a few of the images (images are independent), and
 # properties that hold for every image are checked on all of them.
@@ -154,7 +192,7 @@ def test_config5_googlenet_full_batch_sampled():
         slim = form == "slim"
         layers = workloads.CONFIGS[5][form]
         params = workloads.make_params(5, form)
-        mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT) if slim else 0
+        mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if slim else 0
         got = run_net_bf16(layers, params, x, fuse_relu=slim, inception_mode=mode).reshape(128, 1000)
         assert np.isfinite(got).all() and (got >= 0).all()
         np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-3)
