@@ -366,6 +366,7 @@ int run_stacked_first_steps(const dr_tensor& xd, const void* x, const dr_incepti
         stacked[members[i]] = true;
     }
     g.y_ctot = sp.dst[0].ctot; g.y_coff = sp.dst[0].c_offset;
+    TraceScope trace("conv_bf16", &g, g.Ng, st);
     return launch_conv_bf16_dma(g, (const uint16_t*)x, (const uint16_t*)w0, (const float*)b0, nullptr, (uint16_t*)sp.dst[0].y, st, &sp);
 }
 
