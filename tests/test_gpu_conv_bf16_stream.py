@@ -1,6 +1,6 @@
 """GPU parity of the streaming bf16 convolution kernel (NHWC, KRSC filters, operands loaded straight
 into LDS, persistent workgroups) against the fp64 oracle, on shapes chosen to reach every code path:
-both slice modes (C a multiple of 64 or not), every tile configuration, several tiles per
+both slice modes (C a multiple of 64 or not), every tile configuration the launcher picks, several tiles per
 workgroup, ragged filter counts / pixel counts / channel runs, strides and paddings on every
 border, and the scalar store path (channel offsets that are not multiples of 8)."""
 import numpy as np
@@ -40,10 +40,10 @@ def _run(case, relu=False, bias=True, seed=0):
 # N, C, H, W, K, R, S, stride, pad
 CASES = [
     # --- slices inside one tap (C % 64 == 0)
-    (1, 64, 12, 12, 24, 1, 1, 1, 0),        # K <= 32: 32 x 256 tiles, one slice per tile
-    (2, 64, 30, 30, 64, 3, 3, 1, 1),        # few pixels: 32 x 128 tiles, two channel blocks, 9 slices
+    (1, 64, 12, 12, 24, 1, 1, 1, 0),        # K <= 32 and few pixels: 32 x 128 tiles, one slice per tile
+    (2, 64, 30, 30, 64, 3, 3, 1, 1),        # one round of 64 x 128 tiles, 9 slices
     (1, 128, 40, 40, 72, 3, 3, 1, 1),       # ragged filter block
-    (1, 64, 190, 190, 136, 1, 1, 1, 0),     # many pixels: 64 x 128 tiles, three channel blocks, ragged last pixel tile
+    (1, 64, 190, 190, 136, 1, 1, 1, 0),     # many pixels: several channel blocks, ragged last pixel tile, grid not a multiple of 8
     (3, 128, 17, 19, 40, 3, 3, 2, 1),       # stride 2, odd sizes
     (1, 192, 9, 9, 200, 5, 5, 1, 2),        # 5x5 at 192 channels, 75 slices
     (2, 64, 8, 8, 16, 3, 3, 1, 0),          # no padding
@@ -65,7 +65,11 @@ CASES = [
     (1, 8, 3, 3, 8, 3, 3, 1, 1),            # tiny
     (2, 96, 70, 70, 72, 3, 3, 1, 1),        # many pixels (64 x 128 tiles) with slices running over filter rows
     (1, 24, 200, 200, 40, 5, 5, 2, 2),      # the same at stride 2, 5x5
-    (1, 64, 100, 100, 192, 3, 3, 1, 1),     # 192 filters: 96 x 128 tiles
+    (1, 64, 100, 100, 192, 3, 3, 1, 1),     # 192 filters, three channel blocks
+    (8, 64, 56, 56, 256, 1, 1, 1, 0),       # 256 filters, 25 088 pixels: one round of 128 x 128 tiles (64 x 64 per wave)
+    (8, 16, 56, 56, 256, 3, 3, 1, 1),       # the same with slices running over filter rows
+    (2, 16, 160, 160, 96, 3, 3, 1, 1),      # 96 filters, 51 200 pixels: one round of 96 x 128 tiles instead of two of 64 x 128
+    (2, 64, 160, 160, 96, 1, 1, 1, 0),      # the same with slices inside one tap
     (1, 32, 96, 96, 288, 5, 5, 1, 2),       # 288 filters, slices running over filter rows
 ]
 
