@@ -47,7 +47,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr;
 template <int V> using IC = std::integral_constant<int, V>;
 
-constexpr int NT = 256;
 constexpr int OOB = (int)0x80000000;
 
 struct DArgs {
@@ -66,7 +65,7 @@ struct DArgs {
     unsigned long long m_pq, m_q;   // ceil(2^40 / (P*Q)), ceil(2^40 / Q)
     int vec_ok;               // 16-byte stores / bias / residual accesses are aligned
     int pointwise;            // 1x1 filter, stride 1, no padding
-    int step_img, step_p, step_q;   // 32 pixels as (images, rows, columns) of the output
+    int step_img, step_p, step_q;   // the pixels one pass of loads covers (8 per wave) as (images, rows, columns) of the output
     int stem_hp, stem_wp;     // rows / pixels per row of the padded 4-channel input copy (0: ordinary input)
     // Stacked convolution (several filter banks on one input, Eq. (12)) whose channel ranges go to different
     // tensors: channel m < split_end[0] goes to destination 0, m < split_end[1] to destination 1, ...
@@ -152,14 +151,18 @@ __device__ __forceinline__ int div_small(int v, unsigned long long m)
 // bits lo..hi set (hi < lo: none); lo, hi in 0..15
 __device__ __forceinline__ unsigned bit_range(int lo, int hi) { return hi >= lo ? (2u << hi) - (1u << lo) : 0u; }
 
-// OCC: waves per SIMD the register allocation must leave room for (512 / OCC registers per lane)
+// A workgroup is WGM x WGN waves (4 or 8), each with a tile of TM x TN blocks of 32 x 32.  OCC: workgroups per
+// compute unit the register allocation must leave room for (512 / (OCC * waves / 4) registers per lane).
 template <int TM, int TN, int WGM, int WGN, int NS, bool TAP, int OCC>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) void conv_bf16_dma_kernel(const DArgs a)
+__global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(OCC * WGM * WGN / 4, OCC * WGM * WGN / 4)))
+void conv_bf16_dma_kernel(const DArgs a)
 {
+    constexpr int WAVES = WGM * WGN, RP = WAVES * 8;                     // rows one pass of loads covers (8 per wave)
     constexpr int WM = TM * 32, WN = TN * 32, BM = WGM * WM, BN = WGN * WN;
-    constexpr int A_PER = BM / 32, B_PER = BN / 32, L = A_PER + B_PER;   // loads per lane and slice
-    constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128;
-    static_assert(WGM * WGN == 4 && NS >= 2 && (NS - 1) * L < 63 && BM <= 256, "bad configuration");
+    constexpr int A_PER = BM / RP, B_PER = BN / RP, L = A_PER + B_PER;   // loads per lane and slice
+    constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128, PASS = RP * 128;
+    static_assert((WAVES == 4 || WAVES == 8) && BM % RP == 0 && BN % RP == 0 && NS >= 2 && (NS - 1) * L < 63 && BM <= 256,
+                  "bad configuration");
 
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
     __shared__ __attribute__((aligned(1024))) float bias_lds[256];
@@ -200,19 +203,19 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
     int a_voff[A_PER];            // byte offset of (filter m, chunk lc) or OOB
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
-        const int m = mt * BM + i * 32 + lrow;
+        const int m = mt * BM + i * RP + lrow;
         a_voff[i] = m < g.K ? (m * g.Kg + lc * 8) * 2 : OOB;
     }
     // The bias of the channel block travels like the operands, ahead of them: 4 bytes per lane straight
     // into LDS (zeros beyond the last filter and without a bias), so that nothing in the prologue waits
     // for a load of its own.  After the first barrier every lane copies its share into registers.
-    {
+    if (wave * 64 < BM) {
         const int ml = wave * 64 + lane, m = mt * BM + ml;
         load_to_lds4(rbias, bias_lds + wave * 64, (ml < BM && m < g.K) ? m * 4 : OOB);
     }
     // after the store's lane exchange a lane owns channels mb .. mb + 7, mb = m_lane + 32 i + 16 qp
     const int m_lane = mt * BM + wm * WM + half * 8;
-    float bias_r[TM][2][8];
+    const unsigned bias_rd = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)bias_lds + (wm * WM + half * 8) * 4;
 
     // ---- loader state of the pixel tile being fetched
     int b_base[B_PER];            // byte offset of x[img][ih0][iw0][lc * 8] (may lie outside the tensor)
@@ -222,14 +225,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
 
     // Per-lane state of pixel tile nt.  A 1x1 filter at stride 1 without padding reads input pixel n for
     // output pixel n: no decoding.  Otherwise the first fetched pixel is decoded into (image, p, q) by
-    // exact division and the others follow by stepping 32 pixels at a time (32 = step_img P Q + step_p Q +
+    // exact division and the others follow by stepping RP pixels at a time (RP = step_img P Q + step_p Q +
     // step_q, so each coordinate wraps at most once per step).
     auto tile_setup = [&](int nt) __attribute__((always_inline)) {
         const int n_first = nt * BN + lrow;
         if (a.pointwise) {
 #pragma unroll
             for (int i = 0; i < B_PER; ++i) {
-                const int n = n_first + i * 32;
+                const int n = n_first + i * RP;
                 b_base[i] = (n * g.C + lc * 8) * 2;
                 b_mask[i] = n < g.Ng ? 0x1FFFEu : 0xFFFFu;
             }
@@ -240,7 +243,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
         int p = div_small(pix, a.m_q), q = pix - p * g.Q;
 #pragma unroll
         for (int i = 0; i < B_PER; ++i) {
-            const int n = n_first + i * 32;
+            const int n = n_first + i * RP;
             if (a.stem_wp) {
                 // packed small-channel input (see launch_conv_bf16_stem): chunk lc of a slice is pixel pair lc & 3 of
                 // window row lc >> 2; nothing is ever outside the padded copy
@@ -280,10 +283,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
             const int soff_b = ld_c * 16;
 #pragma unroll
             for (int i = 0; i < A_PER; ++i)
-                load_to_lds16(rw, sa + i * 4096, a_voff[i], soff_a);
+                load_to_lds16(rw, sa + i * PASS, a_voff[i], soff_a);
 #pragma unroll
             for (int i = 0; i < B_PER; ++i)
-                load_to_lds16(rx, sb + i * 4096, (int)b_cur[i], soff_b);
+                load_to_lds16(rx, sb + i * PASS, (int)b_cur[i], soff_b);
             ld_c += 8;
             if (ld_c == a.c8) {
                 ld_c = 0;
@@ -302,11 +305,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
             const int run_off = ld_r * g.W * g.C * 2 + ld_j0 * 16;
 #pragma unroll
             for (int i = 0; i < A_PER; ++i)
-                load_to_lds16(rw, sa + i * 4096, a_ok ? a_voff[i] : OOB, soff_a);
+                load_to_lds16(rw, sa + i * PASS, a_ok ? a_voff[i] : OOB, soff_a);
 #pragma unroll
             for (int i = 0; i < B_PER; ++i) {
                 const unsigned off = ((b_cur[i] << sh) & 0x80000000u) | (unsigned)(b_base[i] + run_off);
-                load_to_lds16(rx, sb + i * 4096, (int)off, 0);
+                load_to_lds16(rx, sb + i * PASS, (int)off, 0);
             }
             ld_j0 += 8;
             if (ld_j0 >= a.run_chunks) {
@@ -362,12 +365,20 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
 
     auto epilogue = [&](int nt) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = nt * BN + wn * WN + j * 32 + l32;
-            uint16_t* yb = a.y + (size_t)n * g.y_ctot + g.y_coff;     // (replaced per channel group in a stacked convolution)
-            const uint16_t* rb = a.res + (size_t)n * g.res_ctot;
+        for (int i = 0; i < TM; ++i) {
+            // this lane's 16 bias values of block row i, from LDS: read and awaited before the first branch
+            u32x4 bv[2][2];
+            bv[0][0] = ds_read16<0>(bias_rd + i * 128);
+            bv[0][1] = ds_read16<16>(bias_rd + i * 128);
+            bv[1][0] = ds_read16<64>(bias_rd + i * 128);
+            bv[1][1] = ds_read16<80>(bias_rd + i * 128);
+            wait_lgkm<0>();
+            touch(bv[0][0]); touch(bv[0][1]); touch(bv[1][0]); touch(bv[1][1]);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int j = 0; j < TN; ++j) {
+                const int n = nt * BN + wn * WN + j * 32 + l32;
+                uint16_t* yb = a.y + (size_t)n * g.y_ctot + g.y_coff;     // (replaced per channel group in a stacked convolution)
+                const uint16_t* rb = a.res + (size_t)n * g.res_ctot;
 #pragma unroll
                 for (int qp = 0; qp < 2; ++qp) {
                     // registers 8 qp .. 8 qp + 3 hold channels +0..3 (lower half-wave) / +4..7 (upper);
@@ -389,7 +400,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
                         yb = base + (size_t)n * ct;
                     }
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) o[e] += bias_r[i][qp][e];
+                    for (int e = 0; e < 8; ++e) o[e] += __uint_as_float(bv[qp][e >> 2][e & 3]);
                     if (a.vec_ok && mb + 7 < g.K) {
                         if (a.res) {
                             const u32x4 rv = *reinterpret_cast<const u32x4*>(rb + mb);
@@ -420,6 +431,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
                         }
                     }
                 }
+            }
         }
     };
 
@@ -435,28 +447,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
     if (NS - 1 < total) wait_vmcnt<(NS - 1) * L>();     // the bias and slice 0 have landed (this wave's part)
     else wait_vmcnt<0>();
     ring_barrier();
-    {
-        const unsigned bl = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)bias_lds + (wm * WM + half * 8) * 4;
-        u32x4 bv[TM][2][2];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            bv[i][0][0] = ds_read16<0>(bl + i * 128);
-            bv[i][0][1] = ds_read16<16>(bl + i * 128);
-            bv[i][1][0] = ds_read16<64>(bl + i * 128);
-            bv[i][1][1] = ds_read16<80>(bl + i * 128);
-        }
-        wait_lgkm<0>();
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int qp = 0; qp < 2; ++qp)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    touch(bv[i][qp][h]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) bias_r[i][qp][4 * h + e] = __uint_as_float(bv[i][qp][h][e]);
-                }
-    }
     fetch_step(0, IC<0>{});
     fetch_step(0, IC<1>{});
     fetch_step(0, IC<2>{});
@@ -468,18 +458,29 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(OCC, OCC))) 
             const int next_stage = stage + 1 == NS ? 0 : stage + 1;
             multiply_step(IC<0>{});
             fetch_step(stage, IC<3>{});
+            // With three or more stages a slice's loads have a whole further iteration to land, and the waves of the
+            // workgroup take turns: wave w sends its loads after k-step w (slot), so that the four bursts do not queue up
+            // behind one another in the compute unit's address path while every wave waits.
+            int slot = -1;
             if (gi + 1 < total) {
                 // this wave's loads of slice gi + 1 have landed once at most the NS - 2 slices behind it are pending
                 if (gi + NS - 1 < total) wait_vmcnt<(NS - 2) * L>();
                 else wait_vmcnt<0>();
                 ring_barrier();
-                if (issued < total) { issue_slice(stage); ++issued; }
+                if (issued < total) {
+                    slot = NS >= 3 ? (wave & 3) : 0;
+                    ++issued;
+                    if (slot == 0) issue_slice(stage);
+                }
             }
             multiply_step(IC<1>{});
+            if (NS >= 3 && slot == 1) issue_slice(stage);
             fetch_step(next_stage, IC<0>{});      // (after the last slice: reads nobody uses)
             multiply_step(IC<2>{});
+            if (NS >= 3 && slot == 2) issue_slice(stage);
             fetch_step(next_stage, IC<1>{});
             multiply_step(IC<3>{});
+            if (NS >= 3 && slot == 3) issue_slice(stage);
             fetch_step(next_stage, IC<2>{});
             stage = next_stage;
         }
@@ -502,8 +503,11 @@ int device_cus()
 template <int TM, int TN, int WGM, int WGN, int NS, int OCC>
 int launch_cfg(DArgs a, hipStream_t st)
 {
-    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, NTH = WGM * WGN * 64, RP = WGM * WGN * 8;
     constexpr int LDS = NS * (BM + BN) * 128 + 1024;
+    a.step_img = RP / (a.g.P * a.g.Q);
+    a.step_p = (RP % (a.g.P * a.g.Q)) / a.g.Q;
+    a.step_q = RP % a.g.Q;
     static_assert(LDS <= 160 * 1024, "LDS ring too large");
     a.grid_m = (a.g.K + BM - 1) / BM;
     a.grid_n = (a.g.Ng + BN - 1) / BN;
@@ -515,9 +519,9 @@ int launch_cfg(DArgs a, hipStream_t st)
     if (gn > a.grid_n) gn = a.grid_n;
     const unsigned G = (unsigned)(gn * a.grid_m);
     if (a.g.C % 64 == 0)
-        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true, OCC>), dim3(G), dim3(NT), 0, st, a);
+        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true, OCC>), dim3(G), dim3(NTH), 0, st, a);
     else
-        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, false, OCC>), dim3(G), dim3(NT), 0, st, a);
+        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, false, OCC>), dim3(G), dim3(NTH), 0, st, a);
     return check_launch("conv_bf16");
 }
 
@@ -542,6 +546,13 @@ int launch_auto(DArgs a, hipStream_t st)
     }
     const float c64 = tile_rounds(K, Ng, 64, 128) * (0.44f + 2.f), c96 = tile_rounds(K, Ng, 96, 128) * (0.44f + 3.f);
     const float r128 = tile_rounds(K, Ng, 128, 128), c128 = r128 * (0.44f + 4.f);   // pays only when it saves a round
+    // 192 x 256 tiles on eight waves (one workgroup per compute unit, 96 x 64 per wave): fewer loads, LDS reads
+    // and instructions per FLOP; a round of them costs about 6.4 on the same scale
+    if (K % 192 == 0) {
+        const float t = (float)(K / 192) * (float)((Ng + 255) / 256) / (float)device_cus();
+        const float c192 = (t <= 1.f ? 1.f : (t < 3.f ? ceilf(t) : t)) * 6.4f;
+        if (c192 < c64 && c192 < c96) return launch_cfg<3, 2, 2, 4, 2, 1>(a, st);
+    }
     if (r128 <= 1.f && c128 < c64 && c128 < c96) return launch_cfg<2, 2, 2, 2, 2, 2>(a, st);   // 128 x 128 tiles, 64 x 64 per wave
     if (c96 < c64) return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);                  // 96 x 128 tiles
     return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                                 // 64 x 128 tiles
@@ -573,9 +584,6 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
     a.m_pq = ((1ull << 40) + (unsigned)(g.P * g.Q) - 1) / (unsigned)(g.P * g.Q);
     a.m_q = ((1ull << 40) + (unsigned)g.Q - 1) / (unsigned)g.Q;
     a.pointwise = g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
-    a.step_img = 32 / (g.P * g.Q);
-    a.step_p = (32 % (g.P * g.Q)) / g.Q;
-    a.step_q = 32 % g.Q;
     a.stem_hp = a.stem_wp = 0;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y) && (!residual || (g.res_ctot % 8 == 0 && aligned16(residual)));
     a.nsplit = 0;
@@ -624,6 +632,13 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
         case 22: return launch_cfg<2, 1, 1, 4, 4, 1>(a, st);  // 64 x 128, deeper rings
         case 23: return launch_cfg<2, 1, 1, 4, 6, 1>(a, st);
         case 24: return launch_cfg<1, 2, 1, 4, 4, 1>(a, st);  // 32 x 256, deeper ring
+        case 30: return launch_cfg<3, 2, 2, 4, 2, 1>(a, st);  // 8 waves: 192 x 256, 96 x 64 per wave
+        case 31: return launch_cfg<2, 2, 2, 4, 2, 1>(a, st);  // 8 waves: 128 x 256, 64 x 64 per wave
+        case 32: return launch_cfg<2, 2, 4, 2, 2, 1>(a, st);  // 8 waves: 256 x 128
+        case 33: return launch_cfg<3, 1, 2, 4, 2, 1>(a, st);  // 8 waves: 192 x 128, 96 x 32 per wave
+        case 34: return launch_cfg<2, 2, 2, 4, 3, 1>(a, st);  // 8 waves: 128 x 256, three stages
+        case 35: return launch_cfg<1, 2, 2, 4, 2, 1>(a, st);  // 8 waves: 64 x 256, 32 x 64 per wave
+        case 36: return launch_cfg<2, 1, 2, 4, 2, 1>(a, st);  // 8 waves: 128 x 128, 64 x 32 per wave
         default: break;
         }
     }
@@ -658,9 +673,6 @@ int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int 
     a.m_pq = ((1ull << 40) + (unsigned)(g.P * g.Q) - 1) / (unsigned)(g.P * g.Q);
     a.m_q = ((1ull << 40) + (unsigned)g.Q - 1) / (unsigned)g.Q;
     a.pointwise = 0;
-    a.step_img = 32 / (g.P * g.Q);
-    a.step_p = (32 % (g.P * g.Q)) / g.Q;
-    a.step_q = 32 % g.Q;
     a.stem_hp = hp; a.stem_wp = wp;
     a.nsplit = 0;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y);
