@@ -546,13 +546,6 @@ int launch_auto(DArgs a, hipStream_t st)
     }
     const float c64 = tile_rounds(K, Ng, 64, 128) * (0.44f + 2.f), c96 = tile_rounds(K, Ng, 96, 128) * (0.44f + 3.f);
     const float r128 = tile_rounds(K, Ng, 128, 128), c128 = r128 * (0.44f + 4.f);   // pays only when it saves a round
-    // 192 x 256 tiles on eight waves (one workgroup per compute unit, 96 x 64 per wave): fewer loads, LDS reads
-    // and instructions per FLOP; a round of them costs about 6.4 on the same scale
-    if (K % 192 == 0) {
-        const float t = (float)(K / 192) * (float)((Ng + 255) / 256) / (float)device_cus();
-        const float c192 = (t <= 1.f ? 1.f : (t < 3.f ? ceilf(t) : t)) * 6.4f;
-        if (c192 < c64 && c192 < c96) return launch_cfg<3, 2, 2, 4, 2, 1>(a, st);
-    }
     if (r128 <= 1.f && c128 < c64 && c128 < c96) return launch_cfg<2, 2, 2, 2, 2, 2>(a, st);   // 128 x 128 tiles, 64 x 64 per wave
     if (c96 < c64) return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);                  // 96 x 128 tiles
     return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                                 // 64 x 128 tiles
