@@ -272,7 +272,18 @@ def main():
         return conv, other, fl
     co, oo, fo = split(recs)
     cs, os_, fs = split(recs_slim)
-    nontensor_bytes = sum(2.0 * r[5] * esz for r in recs if not is_tensor(r))
+    # non-tensor layers: algorithmic bytes (each layer's input and output once) over HIP-event time, for all
+    # launches of the original form and for those that move at least 32 MB (below that a launch is bound by
+    # its start-up, not by bandwidth: the event pair around an empty launch already spans several microseconds)
+    def nt_bytes(r):
+        return float(r[7]) if r[7] > 0 else 2.0 * r[5] * esz
+    nontensor_bytes = sum(nt_bytes(r) for r in recs if not is_tensor(r))
+    big = [r for r in recs if not is_tensor(r) and nt_bytes(r) >= 32e6]
+    by_kind = {}
+    for r in recs:
+        if not is_tensor(r):
+            k = by_kind.setdefault(r[0], [0.0, 0.0, 0])
+            k[0] += nt_bytes(r); k[1] += r[6]; k[2] += 1
 
     out = {
         "metric": "images/sec fwd (orig vs slim GoogLeNet), conv MFMA util %, non-tensor HBM GB/s",
@@ -295,6 +306,8 @@ def main():
         "conv_mfma_util_pct": {"original": round(100.0 * fo / max(co, 1e-9) / 1e9 / MI355X_MFMA_TFLOPS[dtype], 1),
                                "slim": round(100.0 * fs / max(cs, 1e-9) / 1e9 / MI355X_MFMA_TFLOPS[dtype], 1)},
         "non_tensor_hbm_gbs": round(nontensor_bytes / max(oo, 1e-9) / 1e6, 1) if oo > 0 else None,
+        "non_tensor_hbm_gbs_launches_over_32MB": round(sum(nt_bytes(r) for r in big) / max(sum(r[6] for r in big), 1e-9) / 1e6, 1) if big else None,
+        "non_tensor_by_kind": {k: {"launches": v[2], "ms": round(v[1], 4), "gbs": round(v[0] / max(v[1], 1e-9) / 1e6, 1)} for k, v in sorted(by_kind.items())},
         "roofline": roofline,
         "paper_context": "GoogLeNet 651.4 ms -> GoogLeNet-Slim 210.6 ms on Samsung Galaxy S5 CPU; 10.17 -> 6.57 ms on "
                          "Titan X (batch 1, Table 4/5); inception_3a 55.23 -> 21.17 ms on S5",

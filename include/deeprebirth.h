@@ -246,8 +246,9 @@ int dr_net_layer_times(dr_net* net, float* ms_per_layer, int n);
 /* One traced kernel launch.  label: kernel family ("conv_f32", "conv_bf16", "relu", "lrn", "maxpool",
  * "concat", "bn", "add_relu", "avgpool", "fc", "softmax").  For convolutions k, c, r, s are the
  * filter dimensions and items = N*P*Q (the GEMM n extent); otherwise items = elements written.  bytes:
- * for convolutions, the bytes the layer must move at least (input + filters + output + residual, each
- * once); 0 for the other kernels (they move the tensors they are given once each). */
+ * the bytes the launch must move at least: convolutions input + filters + output + residual, each once;
+ * the other layers their input(s) and output once each (pooling: whole input + output); 0 for the
+ * library's own repacking kernels. */
 typedef struct { char label[24]; int k, c, r, s; long long items; float ms; long long bytes; } dr_trace_record;
 
 /* Starts recording one HIP event pair around every kernel launch the library makes (on the stream

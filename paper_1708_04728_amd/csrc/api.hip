@@ -41,7 +41,7 @@ static struct {
     size_t capacity = 0;
 } g_trace;
 
-TraceScope::TraceScope(const char* label, const ConvGeom* g, long long items, hipStream_t s) : slot(-1), st(s)
+TraceScope::TraceScope(const char* label, const ConvGeom* g, long long items, hipStream_t s, long long bytes) : slot(-1), st(s)
 {
     if (!g_trace.active || g_trace.recs.size() >= g_trace.capacity) return;
     if (g_trace.filter[0] && !strstr(label, g_trace.filter)) return;
@@ -54,6 +54,7 @@ TraceScope::TraceScope(const char* label, const ConvGeom* g, long long items, hi
         rec.k = g->K; rec.c = (int)c; rec.r = g->R; rec.s = g->S;
         rec.bytes = esz * ((long long)g->N * c * g->H * g->W + (long long)g->K * c * g->R * g->S + (long long)g->Ng * g->K * (g->res_ctot ? 2 : 1));
     }
+    else rec.bytes = bytes;
     rec.items = items;
     slot = (int)g_trace.recs.size();
     g_trace.recs.push_back(rec);

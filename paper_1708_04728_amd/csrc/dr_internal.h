@@ -21,7 +21,8 @@ inline size_t tensor_bytes(const dr_tensor& t) { return tensor_elems(t) * elem_s
 struct ConvGeom;
 // Brackets one kernel launch with an event pair when tracing is on (see dr_trace_begin).
 struct TraceScope {
-    TraceScope(const char* label, const ConvGeom* g, long long items, hipStream_t st);
+    // bytes: what the launch must move (convolutions: computed from g)
+    TraceScope(const char* label, const ConvGeom* g, long long items, hipStream_t st, long long bytes = 0);
     ~TraceScope();
     int slot;
     hipStream_t st;

@@ -413,20 +413,20 @@ int launch_pack_filters(int dtype, const void* w_kcrs, void* w_krsc, int K, int 
 
 int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st)
 {
-    TraceScope trace("relu", nullptr, (long long)(count), st);
+    TraceScope trace("relu", nullptr, (long long)(count), st, 2ll * count * elem_size(dtype));
     return DR_BY_DTYPE(dtype, (relu_launch<float, false>(x, nullptr, y, count, st)),
                        (relu_launch<uint16_t, false>(x, nullptr, y, count, st)));
 }
 
 int launch_add_relu(int dtype, const void* a, const void* b, void* y, size_t count, hipStream_t st)
 {
-    TraceScope trace("add_relu", nullptr, (long long)(count), st);
+    TraceScope trace("add_relu", nullptr, (long long)(count), st, 3ll * count * elem_size(dtype));
     return DR_BY_DTYPE(dtype, (relu_launch<float, true>(a, b, y, count, st)), (relu_launch<uint16_t, true>(a, b, y, count, st)));
 }
 
 int launch_lrn(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipStream_t st)
 {
-    TraceScope trace("lrn", nullptr, (long long)tensor_elems(d), st);
+    TraceScope trace("lrn", nullptr, (long long)tensor_elems(d), st, 2ll * tensor_bytes(d));
     if (tensor_elems(d) == 0) return DR_OK;
     if (d.layout == DR_NHWC) return launch_lrn_nhwc(d, x, y, p, st);
     return DR_BY_DTYPE(d.dtype, lrn_launch<float>(x, y, d.n, d.c, d.h * d.w, p, st), lrn_launch<uint16_t>(x, y, d.n, d.c, d.h * d.w, p, st));
@@ -434,7 +434,7 @@ int launch_lrn(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipS
 
 int launch_maxpool(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, hipStream_t st)
 {
-    TraceScope trace("maxpool", nullptr, (long long)tensor_elems(yd), st);
+    TraceScope trace("maxpool", nullptr, (long long)tensor_elems(yd), st, (long long)(tensor_bytes(xd) + tensor_bytes(yd)));
     if (xd.layout == DR_NHWC) return launch_pool_nhwc(xd, x, yd, y, p, false, st);
     return DR_BY_DTYPE(xd.dtype, (pool_launch<float, false>(x, y, xd.n * xd.c, xd.h, xd.w, yd.h, yd.w, p, st)),
                        (pool_launch<uint16_t, false>(x, y, xd.n * xd.c, xd.h, xd.w, yd.h, yd.w, p, st)));
@@ -442,7 +442,7 @@ int launch_maxpool(const dr_tensor& xd, const void* x, const dr_tensor& yd, void
 
 int launch_avgpool(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, hipStream_t st)
 {
-    TraceScope trace("avgpool", nullptr, (long long)tensor_elems(yd), st);
+    TraceScope trace("avgpool", nullptr, (long long)tensor_elems(yd), st, (long long)(tensor_bytes(xd) + tensor_bytes(yd)));
     if (xd.layout == DR_NHWC) return launch_pool_nhwc(xd, x, yd, y, p, true, st);
     return DR_BY_DTYPE(xd.dtype, (pool_launch<float, true>(x, y, xd.n * xd.c, xd.h, xd.w, yd.h, yd.w, p, st)),
                        (pool_launch<uint16_t, true>(x, y, xd.n * xd.c, xd.h, xd.w, yd.h, yd.w, p, st)));
@@ -450,7 +450,7 @@ int launch_avgpool(const dr_tensor& xd, const void* x, const dr_tensor& yd, void
 
 int launch_concat(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st)
 {
-    TraceScope trace("concat", nullptr, (long long)tensor_elems(yd), st);
+    TraceScope trace("concat", nullptr, (long long)tensor_elems(yd), st, 2ll * tensor_bytes(yd));
     if (yd.layout == DR_NHWC) return launch_concat_nhwc(yd, nb, segs, y, st);
     return DR_BY_DTYPE(yd.dtype, concat_launch<float>(nb, segs, y, yd.n, yd.c, yd.h * yd.w, st),
                        concat_launch<uint16_t>(nb, segs, y, yd.n, yd.c, yd.h * yd.w, st));
@@ -459,7 +459,7 @@ int launch_concat(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, h
 int launch_bn(const dr_tensor& d, const void* x, void* y, const float* gamma, const float* beta, const float* mean,
               const float* var, float eps, int relu, hipStream_t st)
 {
-    TraceScope trace("bn", nullptr, (long long)tensor_elems(d), st);
+    TraceScope trace("bn", nullptr, (long long)tensor_elems(d), st, 2ll * tensor_bytes(d));
     if (d.layout == DR_NHWC) return launch_bn_nhwc(d, x, y, gamma, beta, mean, var, eps, relu, st);
     return DR_BY_DTYPE(d.dtype, bn_launch<float>(x, y, d.n, d.c, d.h * d.w, gamma, beta, mean, var, eps, relu, st),
                        bn_launch<uint16_t>(x, y, d.n, d.c, d.h * d.w, gamma, beta, mean, var, eps, relu, st));
@@ -488,7 +488,7 @@ int launch_fc(int dtype, const void* x, const void* w, const float* bias, void* 
 
 int launch_softmax(int dtype, const void* x, float* y, int N, int O, hipStream_t st)
 {
-    TraceScope trace("softmax", nullptr, (long long)((size_t)N * O), st);
+    TraceScope trace("softmax", nullptr, (long long)((size_t)N * O), st, (long long)((size_t)N * O * (elem_size(dtype) + 4)));
     if (N == 0 || O == 0) return DR_OK;
     if (dtype == DR_BF16) hipLaunchKernelGGL((softmax_kernel<uint16_t>), dim3(N), dim3(256), 0, st, (const uint16_t*)x, y, O);
     else hipLaunchKernelGGL((softmax_kernel<float>), dim3(N), dim3(256), 0, st, (const float*)x, y, O);
