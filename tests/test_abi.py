@@ -130,3 +130,44 @@ def test_slim_transforms_reproduce_the_configurations():
         assert len(br) == 2
         assert br[0][2][1]["k"] + br[1][2][1]["k"] == wd[1] + wd[3] + wd[5] + wd[6]
         assert br[1][2][1]["r"] == 5
+
+
+def test_stack_first_steps_lays_reducers_back_to_back():
+    """graph.stack_first_steps (the parameter layout DR_FUSE_STACK looks for, Eq. (12)): the first-step 1x1
+    convolutions of every module end up adjacent in memory in branch order, values unchanged, everything
+    else untouched."""
+    layers = workloads.CONFIGS[5]["original"][10:12] + [workloads.CONFIGS[5]["slim"][6]]     # 3a, 3b, slim 3a
+    assert all(kind == "inception" for kind, _ in layers)
+    per = [sum(1 for br in p["branches"] for k, _ in br if k == "conv") for _, p in layers]
+    # any parameter dicts of the right shapes will do: build them from the layer lists
+    rng = np.random.default_rng(0)
+    dicts, c = [], 192
+    for kind, p in layers:
+        outc = 0
+        for br in p["branches"]:
+            ci = c
+            for k, q in br:
+                if k == "conv":
+                    dicts.append({"w": rng.standard_normal((q["k"], ci, q["r"], q["s"])).astype(np.float32), "b": rng.standard_normal(q["k"]).astype(np.float32)})
+                    ci = q["k"]
+            outc += ci
+        c = outc if kind == "inception" else c
+        c = 192 if layers.index((kind, p)) == 1 else c          # the third module is another 3a: 192 channels in again
+    flat = G.flat_params(dicts, "f32", device="cpu", pack=False)
+    stacked = G.stack_first_steps(layers, flat)
+    assert len(stacked) == len(flat) == 2 * sum(per)
+    for a, b in zip(flat, stacked):
+        assert a.shape == b.shape and bool((a == b).all())
+    pos = 0
+    for (kind, p), n in zip(layers, per):
+        first, j = [], pos
+        for br in p["branches"]:
+            if br[0][0] == "conv" and br[0][1]["r"] == 1:
+                first.append(j)
+            j += 2 * sum(1 for k, _ in br if k == "conv")
+        assert len(first) >= 2
+        for f0, f1 in zip(first, first[1:]):
+            w0, w1, b0, b1 = stacked[f0], stacked[f1], stacked[f0 + 1], stacked[f1 + 1]
+            assert w1.data_ptr() == w0.data_ptr() + w0.numel() * w0.element_size()
+            assert b1.data_ptr() == b0.data_ptr() + b0.numel() * b0.element_size()
+        pos = j
