@@ -136,9 +136,14 @@ class Workload:
         self.x = G.to_device(self.x_host, self.dtype, nhwc=bf16)
         self.stream = torch.cuda.current_stream()
         self.forms = {}
-        for form in ("original", "slim"):
-            slim = form == "slim"
-            layers = cfg["original"] if isinstance(cfg[form], str) else cfg[form]
+        # "fused": the original structure with every fusion that leaves the function unchanged (ReLU, concat and
+        # stacked first steps in the convolution stores, LRN + pooling in one pass): how much of the slim form's
+        # gain fusion alone recovers.  Not part of a step; absent where the slim form is itself such a fusion.
+        forms = ("original", "slim") if isinstance(cfg["slim"], str) else ("original", "slim", "fused")
+        for form in forms:
+            slim, fused = form == "slim", form == "fused"
+            src_form = "original" if fused else form
+            layers = cfg["original"] if isinstance(cfg[src_form], str) else cfg[src_form]
             folded = slim and isinstance(cfg[form], str)
             if folded:      # Lemma 2: BatchNorm folded into the filters by the library's host routine
                 src = workloads.make_params(cfg_id, "original")
@@ -149,14 +154,14 @@ class Workload:
                                        float(np.float32(workloads.BN_EPS)))
                     params_host.append({"w": workloads.round_to_bf16(wf) if bf16 else wf, "b": bf})
             else:
-                params_host = workloads.make_params(cfg_id, form)
-            net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if slim else 0,
-                                    fuse_relu=slim, folded=folded, pack=self.dtype))
+                params_host = workloads.make_params(cfg_id, src_form)
+            net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if (slim or fused) else B.DR_CONCURRENT_BRANCHES,
+                                    fuse_relu=slim or fused, folded=folded, pack=self.dtype, fuse_nontensor=fused and bf16))
             xd = B.desc(self.x)
             y = G.empty_like_desc(net.output_desc(xd))
             ws = torch.empty(max(net.workspace_bytes(xd), 256), dtype=torch.uint8, device="cuda")
             flat = G.flat_params(params_host, self.dtype, pack=True)
-            if slim and not folded and any(kind == "inception" for kind, _ in layers):
+            if (slim or fused) and bf16 and not folded and any(kind == "inception" for kind, _ in layers):
                 flat = G.stack_first_steps(layers, flat)      # the layout DR_FUSE_STACK takes (Eq. (12))
             self.forms[form] = dict(net=net, y=y, ws=ws, params=flat,
                                     layers=layers, params_host=params_host, folded=folded)
@@ -176,7 +181,7 @@ class Workload:
 
     def form_times(self, reps):
         out = {}
-        for form in ("original", "slim"):
+        for form in self.forms:
             ts = []
             for _ in range(reps):
                 e0, e1 = self.torch.cuda.Event(enable_timing=True), self.torch.cuda.Event(enable_timing=True)
@@ -209,6 +214,7 @@ class Workload:
             out[form] = {"workspace_mb": round(f["net"].workspace_bytes(xd) / 1e6, 2), "params_mb": round(params / 1e6, 2),
                          "per_image_mb": round(per_image / 1e6, 3),
                          "max_batch_288GB": int((288e9 - params) // per_image)}
+        out.pop("fused", None)
         out["slim_saving"] = round(out["original"]["per_image_mb"] / out["slim"]["per_image_mb"], 2)
         return out
 
@@ -225,6 +231,7 @@ class Workload:
                 "original_images_per_s": round(self.batch / (fm["original"][0] * 1e-3), 1),
                 "slim_images_per_s": round(self.batch / (fm["slim"][0] * 1e-3), 1),
                 "slim_speedup": round(fm["original"][0] / fm["slim"][0], 3),
+                "fused_original_ms": round(fm["fused"][0], 4) if "fused" in fm else None,
                 "pct_latency_non_tensor_original": round(100.0 * other / max(tens + other, 1e-9), 1)}
 
 
@@ -352,6 +359,9 @@ def main():
         "original_images_per_s": round(batch / (form_ms["original"][0] * 1e-3), 1),
         "slim_images_per_s": round(batch / (form_ms["slim"][0] * 1e-3), 1),
         "slim_speedup": round(form_ms["original"][0] / form_ms["slim"][0], 3),
+        "fused_original_ms": {"best": round(form_ms["fused"][0], 4), "median": round(form_ms["fused"][1], 4)} if "fused" in form_ms else None,
+        "fusion_share_of_slim_gain": round((form_ms["original"][0] - form_ms["fused"][0]) / max(form_ms["original"][0] - form_ms["slim"][0], 1e-9), 3)
+        if "fused" in form_ms else None,
         "kernel_split_ms": {"original_tensor": round(co, 4), "original_non_tensor": round(oo, 4),
                             "slim_tensor": round(cs, 4), "slim_non_tensor": round(os_, 4)},
         "pct_latency_non_tensor_original": round(100.0 * oo / max(co + oo, 1e-9), 1),

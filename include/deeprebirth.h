@@ -114,6 +114,15 @@ int dr_lrn_fwd(const dr_tensor* d, const void* x, const dr_lrn* p, void* y, void
  * yd->h/w must equal dr_pool_out_size; yd->n/c == xd->n/c. */
 int dr_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream);
 
+/* The non-tensor tail of a streamlined block (Sec. 3.1: conv - ReLU - LRN - pool, or pool - LRN as in the first
+ * block of GoogLeNet) in one pass over the tensor, without changing the function: y = maxpool(lrn(x)) resp.
+ * y = lrn(maxpool(x)), the intermediate tensor never stored (and never rounded to the storage type).  Same
+ * descriptors and shape rules as dr_lrn_fwd and dr_maxpool_fwd.  DR_ERR_UNSUPPORTED unless: channels-last
+ * tensors whose channel count is a multiple of 8 (bf16) / 4 (fp32) and at most 512 / 256, 16-byte aligned
+ * pointers, a 3x3 pooling window of stride 1 or 2 with padding 0 or 1, local_size 5. */
+int dr_lrn_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_lrn* l, const dr_pool* p, const dr_tensor* yd, void* y, void* stream);
+int dr_maxpool_lrn_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_lrn* l, const dr_tensor* yd, void* y, void* stream);
+
 /* Concatenation along channels, Eq. (11): y = [x_0; x_1; ...; x_{nb-1}].  xds/xs are host arrays
  * of nb descriptors / device pointers; all inputs share n, h, w and dtype; yd->c = sum of x_i c.
  * nb <= DR_MAX_BRANCHES. */
@@ -170,11 +179,13 @@ typedef struct { int n_steps; dr_step steps[DR_MAX_STEPS]; } dr_branch;
                               where the previous one's k*c elements end; the same for the fp32 biases, or
                               all biases NULL) and every bank but the last has a multiple of 8 filters;
                               otherwise the convolutions run one by one, with the same result */
-#define DR_SERIAL_BRANCHES 8 /* run the branches one after another on the caller's stream.  Without it
-                              branches 1.. run on streams the library owns (per host thread and device,
-                              created on first use, default priority), forked from the caller's stream
-                              by an event before the module and joined to it by events before the
-                              concat: to the caller the module is still one piece of work on `stream` */
+#define DR_CONCURRENT_BRANCHES 8 /* branches 1.. run on streams the library owns (per host thread and
+                              device, created on first use, default priority), forked from the caller's
+                              stream by an event before the module and joined to it by events before the
+                              concat: to the caller the module is still one piece of work on `stream`.
+                              Without it the branches run one after another on the caller's stream.
+                              Pays when a module's kernels are long next to the cost of the events
+                              (several microseconds per fork / join) and leave compute units idle */
 typedef struct { int n_branches; dr_branch branches[DR_MAX_BRANCHES]; int mode; } dr_inception;
 
 /* Bytes of workspace dr_inception_fwd needs for input xd. */
@@ -193,7 +204,9 @@ int dr_inception_fwd(const dr_tensor* xd, const void* x, const dr_inception* des
 
 typedef enum {
     DR_LAYER_CONV = 0, DR_LAYER_RELU, DR_LAYER_LRN, DR_LAYER_MAXPOOL, DR_LAYER_INCEPTION,
-    DR_LAYER_BOTTLENECK, DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX
+    DR_LAYER_BOTTLENECK, DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX,
+    DR_LAYER_LRN_MAXPOOL,    /* dr_lrn_maxpool_fwd: uses .lrn and .pool */
+    DR_LAYER_MAXPOOL_LRN     /* dr_maxpool_lrn_fwd: uses .pool and .lrn */
 } dr_layer_kind;
 
 /* ResNet bottleneck (Sec. 4.2): 1x1 (mid) - 3x3 (mid) - 1x1 (out), each followed by BatchNorm
@@ -205,8 +218,8 @@ typedef struct { int mid, out, project, folded; float eps; int filter_layout; /*
 typedef struct {
     int kind;
     dr_conv conv;            /* DR_LAYER_CONV */
-    dr_lrn lrn;              /* DR_LAYER_LRN */
-    dr_pool pool;            /* DR_LAYER_MAXPOOL, DR_LAYER_AVGPOOL */
+    dr_lrn lrn;              /* DR_LAYER_LRN, DR_LAYER_LRN_MAXPOOL, DR_LAYER_MAXPOOL_LRN */
+    dr_pool pool;            /* DR_LAYER_MAXPOOL, DR_LAYER_AVGPOOL, DR_LAYER_LRN_MAXPOOL, DR_LAYER_MAXPOOL_LRN */
     dr_inception inception;  /* DR_LAYER_INCEPTION */
     dr_bottleneck bottleneck;/* DR_LAYER_BOTTLENECK */
     int fc_out;              /* DR_LAYER_FC */

@@ -22,9 +22,9 @@ DR_KCRS, DR_KRSC = 0, 1
 DR_NCHW, DR_NHWC = 0, 1
 DR_MAX_BRANCHES, DR_MAX_STEPS = 8, 4
 DR_STEP_CONV, DR_STEP_MAXPOOL = 0, 1
-DR_FUSE_RELU, DR_FUSE_CONCAT, DR_FUSE_STACK, DR_SERIAL_BRANCHES = 1, 2, 4, 8
+DR_FUSE_RELU, DR_FUSE_CONCAT, DR_FUSE_STACK, DR_CONCURRENT_BRANCHES = 1, 2, 4, 8
 (DR_LAYER_CONV, DR_LAYER_RELU, DR_LAYER_LRN, DR_LAYER_MAXPOOL, DR_LAYER_INCEPTION, DR_LAYER_BOTTLENECK,
- DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX) = range(9)
+ DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX, DR_LAYER_LRN_MAXPOOL, DR_LAYER_MAXPOOL_LRN) = range(11)
 
 
 class dr_tensor(C.Structure):
@@ -91,6 +91,8 @@ _SIGNATURES = {
     "dr_lrn_fwd": ([_P(dr_tensor), _vp, _P(dr_lrn), _vp, _vp], _i),
     "dr_maxpool_fwd": ([_P(dr_tensor), _vp, _P(dr_pool), _P(dr_tensor), _vp, _vp], _i),
     "dr_avgpool_fwd": ([_P(dr_tensor), _vp, _P(dr_pool), _P(dr_tensor), _vp, _vp], _i),
+    "dr_lrn_maxpool_fwd": ([_P(dr_tensor), _vp, _P(dr_lrn), _P(dr_pool), _P(dr_tensor), _vp, _vp], _i),
+    "dr_maxpool_lrn_fwd": ([_P(dr_tensor), _vp, _P(dr_pool), _P(dr_lrn), _P(dr_tensor), _vp, _vp], _i),
     "dr_concat": ([_i, _P(dr_tensor), _P(_vp), _P(dr_tensor), _vp, _vp], _i),
     "dr_bn_fwd": ([_P(dr_tensor), _vp, _vp, _vp, _vp, _vp, _f, _i, _vp, _vp], _i),
     "dr_add_relu": ([_P(dr_tensor), _vp, _vp, _vp, _vp], _i),
@@ -241,6 +243,18 @@ def lrn_fwd(x, y, local_size=5, alpha=1e-4, beta=0.75, k=1.0, stream=None):
 
 def maxpool_fwd(x, pd, y, stream=None):
     _check(lib().dr_maxpool_fwd(desc(x), _ptr(x), pd, desc(y), _ptr(y), _stream(stream)))
+    return y
+
+
+def lrn_maxpool_fwd(x, ld, pd, y, stream=None):
+    """y = maxpool(lrn(x)) in one pass; ld: dr_lrn, pd: dr_pool."""
+    _check(lib().dr_lrn_maxpool_fwd(desc(x), _ptr(x), ld, pd, desc(y), _ptr(y), _stream(stream)))
+    return y
+
+
+def maxpool_lrn_fwd(x, pd, ld, y, stream=None):
+    """y = lrn(maxpool(x)) in one pass."""
+    _check(lib().dr_maxpool_lrn_fwd(desc(x), _ptr(x), pd, ld, desc(y), _ptr(y), _stream(stream)))
     return y
 
 

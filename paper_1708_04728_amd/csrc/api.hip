@@ -391,7 +391,7 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
     BranchStreams* bs = nullptr;
     hipEvent_t fork = nullptr;
     const bool full_trace = g_trace.active && !g_trace.filter[0];
-    if (!(d.mode & DR_SERIAL_BRANCHES) && d.n_branches > 1 && !ar.measure && !full_trace) {
+    if ((d.mode & DR_CONCURRENT_BRANCHES) && d.n_branches > 1 && !ar.measure && !full_trace) {
         bs = branch_streams();
         if (!bs) return fail(DR_ERR_HIP, "%s: cannot create the branch streams", who);
         fork = bs->event();
@@ -548,6 +548,12 @@ int layer_out(const dr_layer_desc& L, const dr_tensor& t, dr_tensor* o)
         *o = t;
         return DR_OK;
     case DR_LAYER_MAXPOOL: DR_TRY(check_pool_desc(who, &L.pool)); *o = pool_out(t, L.pool); return DR_OK;
+    case DR_LAYER_LRN_MAXPOOL:
+    case DR_LAYER_MAXPOOL_LRN:
+        if (L.lrn.local_size < 1) return fail(DR_ERR_SHAPE, "%s: LRN local_size %d", who, L.lrn.local_size);
+        DR_TRY(check_pool_desc(who, &L.pool));
+        *o = pool_out(t, L.pool);
+        return DR_OK;
     case DR_LAYER_AVGPOOL:
         DR_TRY(check_pool_desc(who, &L.pool));
         if (L.pool.pad_h || L.pool.pad_w) return fail(DR_ERR_UNSUPPORTED, "%s: padded average pooling", who);
@@ -752,6 +758,35 @@ int dr_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const d
     return launch_maxpool(*xd, x, o, y, *p, (hipStream_t)stream);
 }
 
+static int lrn_pool_entry(const char* who, const dr_tensor* xd, const void* x, const dr_lrn* l, const dr_pool* p, const dr_tensor* yd, void* y,
+                          bool lrn_first, void* stream)
+{
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    if (!l) return fail(DR_ERR_NULL, "%s: the LRN descriptor is NULL", who);
+    if (l->local_size < 1) return fail(DR_ERR_SHAPE, "%s: LRN local_size %d", who, l->local_size);
+    DR_TRY(check_pool_desc(who, p));
+    const dr_tensor o = pool_out(*xd, *p);
+    if (!same_shape(o, *yd)) return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%dx%d, the layer produces %dx%dx%dx%d", who, yd->n, yd->c, yd->h, yd->w, o.n, o.c, o.h, o.w);
+    if (yd->dtype != xd->dtype || yd->layout != xd->layout) return fail(DR_ERR_UNSUPPORTED, "%s: input and output differ in dtype or layout", who);
+    if (tensor_elems(o) == 0) return DR_OK;
+    if (!x || !y) return fail(DR_ERR_NULL, "%s: x or y is NULL", who);
+    if (!pool_lrn_nhwc_supported(*xd, x, y, *p, *l))
+        return fail(DR_ERR_UNSUPPORTED, "%s: needs channels-last tensors with 16-byte aligned channel groups (at most 64 of them), a 3x3 "
+                    "window of stride 1 or 2 with padding 0 or 1, and an LRN window of 5", who);
+    return launch_pool_lrn_nhwc(*xd, x, o, y, *p, *l, lrn_first, (hipStream_t)stream);
+}
+
+int dr_lrn_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_lrn* l, const dr_pool* p, const dr_tensor* yd, void* y, void* stream)
+{
+    return lrn_pool_entry("dr_lrn_maxpool_fwd", xd, x, l, p, yd, y, true, stream);
+}
+
+int dr_maxpool_lrn_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_lrn* l, const dr_tensor* yd, void* y, void* stream)
+{
+    return lrn_pool_entry("dr_maxpool_lrn_fwd", xd, x, l, p, yd, y, false, stream);
+}
+
 int dr_avgpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream)
 {
     const char* who = "dr_avgpool_fwd";
@@ -891,7 +926,7 @@ int dr_net_create(const dr_layer_desc* layers, int n_layers, dr_net** out)
     if (!net) return fail(DR_ERR_HIP, "%s: out of host memory", who);
     net->layers.assign(layers, layers + n_layers);
     for (const dr_layer_desc& L : net->layers) {
-        if (L.kind < DR_LAYER_CONV || L.kind > DR_LAYER_SOFTMAX) {
+        if (L.kind < DR_LAYER_CONV || L.kind > DR_LAYER_MAXPOOL_LRN) {
             delete net;
             return fail(DR_ERR_UNSUPPORTED, "%s: unknown layer kind %d", who, L.kind);
         }
@@ -1014,6 +1049,13 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
         case DR_LAYER_RELU: DR_TRY(launch_relu(t.dtype, cur, dst, tensor_elems(t), st)); break;
         case DR_LAYER_LRN: DR_TRY(launch_lrn(t, cur, dst, L.lrn, st)); break;
         case DR_LAYER_MAXPOOL: DR_TRY(launch_maxpool(t, cur, od, dst, L.pool, st)); break;
+        case DR_LAYER_LRN_MAXPOOL:
+        case DR_LAYER_MAXPOOL_LRN:
+            if (!pool_lrn_nhwc_supported(t, cur, dst, L.pool, L.lrn))
+                return fail(DR_ERR_UNSUPPORTED, "%s: layer %zu: fused LRN / pooling needs channels-last tensors, a 3x3 window of stride 1 or 2, "
+                            "an LRN window of 5 and at most 64 16-byte channel groups", who, i);
+            DR_TRY(launch_pool_lrn_nhwc(t, cur, od, dst, L.pool, L.lrn, L.kind == DR_LAYER_LRN_MAXPOOL, st));
+            break;
         case DR_LAYER_AVGPOOL: DR_TRY(launch_avgpool(t, cur, od, dst, L.pool, st)); break;
         case DR_LAYER_INCEPTION: {
             const int np = param_count(L) / 2;

@@ -82,6 +82,11 @@ int launch_add_relu(int dtype, const void* a, const void* b, void* y, size_t cou
 // pointwise_nhwc.hip: the channels-last versions (called by the launchers above)
 int launch_lrn_nhwc(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipStream_t st);
 int launch_pool_nhwc(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, bool avg, hipStream_t st);
+// LRN (window of 5 channels) and 3x3 max-pooling (stride 1 or 2) in one pass, in either order; channels-last,
+// 16-byte channel groups, at most 64 of them
+bool pool_lrn_nhwc_supported(const dr_tensor& xd, const void* x, const void* y, const dr_pool& p, const dr_lrn& l);
+int launch_pool_lrn_nhwc(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, const dr_lrn& l, bool lrn_first,
+                         hipStream_t st);
 int launch_concat_nhwc(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st);
 int launch_bn_nhwc(const dr_tensor& d, const void* x, void* y, const float* gamma, const float* beta, const float* mean,
                    const float* var, float eps, int relu, hipStream_t st);

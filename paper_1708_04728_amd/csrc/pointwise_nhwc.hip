@@ -3,6 +3,9 @@
 // group of channels (8 bf16 or 4 fp32) of one pixel and consecutive lanes walk the channel axis:
 // every access is a coalesced 16-byte vector, window neighbours are whole vectors, and the
 // cross-channel LRN window is completed with wavefront shuffles from the neighbouring lanes.
+#include <type_traits>
+#include <utility>
+
 #include "dr_internal.h"
 #include "dr_store.h"
 
@@ -407,6 +410,242 @@ int lrn_launch(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipS
     return check_launch("lrn");
 }
 
+// ---- LRN and 3x3 max-pooling in one pass (the non-tensor tail of a conv - ReLU - LRN - pool block, Sec. 3.1) ------
+// Same decomposition as maxpool3_front_kernel: a thread owns one output column, one 16-byte channel group and
+// a strip of PR output rows, and fetches its 3 x NR input vectors first.  The lanes of a pixel are
+// consecutive lanes of one wave (at most 64 channel groups), so the two channels on either side of a
+// lane's vector arrive by shuffle, as in lrn5_nhwc_kernel.
+//   LRN_FIRST: y = maxpool(lrn(x)): every fetched vector is normalised (a pixel of the input is normalised
+//              by each of the up to 4 threads whose windows hold it), pixels outside the input never win;
+//   else:      y = lrn(maxpool(x)): the pooled vector is normalised.
+// The intermediate tensor is never rounded to the storage type.
+// f(integral_constant<int, LO>{}), ..., f(integral_constant<int, HI - 1>{})
+template <int LO, typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F& f, std::integer_sequence<int, Is...>) { (f(std::integral_constant<int, LO + Is>{}), ...); }
+template <int LO, int HI, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (HI > LO) static_for_impl<LO>(f, std::make_integer_sequence<int, HI - LO>{});
+}
+
+template <typename T, int PR, int STRIDE, bool LRN_FIRST>
+__global__ __launch_bounds__(256) void pool_lrn_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int H, int W, int P, int Q,
+                                                       int pstrips, int qgroups, int bx_log2, int pad, float a_over_n, float beta, float k,
+                                                       int b075)
+{
+    constexpr int V = Store<T>::VN, NR = (PR - 1) * STRIDE + 3;
+    const int CV = C / V;
+    const int bx = 1 << bx_log2, by = 256 >> bx_log2;
+    const int cv = threadIdx.x & (bx - 1), ty = threadIdx.x >> bx_log2;
+    const unsigned qg = blockIdx.x % (unsigned)qgroups, t = blockIdx.x / (unsigned)qgroups;
+    const unsigned strip = t % (unsigned)pstrips, n = t / (unsigned)pstrips;
+    const int q = (int)qg * by + ty;
+    const bool on = q < Q && cv < CV;                     // idle lanes still take part in the shuffles, with zeros
+    const bool has_l = cv > 0, has_r = cv < CV - 1;
+    const int p0 = (int)strip * PR;
+    const int w0 = q * STRIDE - pad, h0 = p0 * STRIDE - pad;
+    const T* xb = x + (size_t)n * H * W * C;
+    constexpr uint32_t NEG = NegInfWord<T>::v;
+
+    auto lrn_vec = [&](const float* v, float* o) __attribute__((always_inline)) {
+        float sq[V + 4];
+#pragma unroll
+        for (int j = 0; j < V; ++j) sq[j + 2] = v[j] * v[j];
+        const float l0 = __shfl_up(sq[V], 1, 64), l1 = __shfl_up(sq[V + 1], 1, 64);
+        const float r0 = __shfl_down(sq[2], 1, 64), r1 = __shfl_down(sq[3], 1, 64);
+        sq[0] = has_l ? l0 : 0.f; sq[1] = has_l ? l1 : 0.f;
+        sq[V + 2] = has_r ? r0 : 0.f; sq[V + 3] = has_r ? r1 : 0.f;
+#pragma unroll
+        for (int j = 0; j < V; ++j) {
+            const float ss = ((sq[j] + sq[j + 1]) + sq[j + 2]) + (sq[j + 3] + sq[j + 4]);
+            o[j] = v[j] * pow_neg_beta(fmaf(a_over_n, ss, k), beta, b075);
+        }
+    };
+
+    uint4 raw[NR][3];
+    bool ok[NR][3];
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            ok[r][c] = on && (unsigned)(h0 + r) < (unsigned)H && (unsigned)(w0 + c) < (unsigned)W;
+            raw[r][c] = make_uint4(NEG, NEG, NEG, NEG);
+            if (ok[r][c]) raw[r][c] = *reinterpret_cast<const uint4*>(xb + ((size_t)(h0 + r) * W + (w0 + c)) * C + cv * V);
+        }
+    float rm[NR][V];
+    // (one instantiation per window pixel: the body with its shuffles is too large for the loop unroller)
+    static_for<0, NR * 3>([&](auto rc_c) __attribute__((always_inline)) {
+        constexpr int r = decltype(rc_c)::value / 3, c = decltype(rc_c)::value % 3;
+        if constexpr (c == 0) {
+#pragma unroll
+            for (int j = 0; j < V; ++j) rm[r][j] = -INFINITY;
+        }
+        float v[V];
+        unpack16<T>(raw[r][c], v);
+        if constexpr (LRN_FIRST) {
+            // whether a window pixel exists is the same for every lane of the pixel, so the lanes agree
+            // on what they exchange; a missing pixel is normalised as zeros and then discarded
+            float z[V], o[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) z[j] = ok[r][c] ? v[j] : 0.f;
+            lrn_vec(z, o);
+#pragma unroll
+            for (int j = 0; j < V; ++j) rm[r][j] = fmaxf(rm[r][j], ok[r][c] ? o[j] : -INFINITY);
+            __builtin_amdgcn_sched_barrier(0);     // one pixel at a time: interleaving all of them needs > 256 registers
+        } else {
+#pragma unroll
+            for (int j = 0; j < V; ++j) rm[r][j] = fmaxf(rm[r][j], v[j]);
+        }
+    });
+#pragma unroll
+    for (int i = 0; i < PR; ++i) {
+        const bool row_on = p0 + i < P;                    // (the same for the whole workgroup)
+        float o[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) o[j] = fmaxf(fmaxf(rm[i * STRIDE][j], rm[i * STRIDE + 1][j]), rm[i * STRIDE + 2][j]);
+        if constexpr (!LRN_FIRST) {
+            float z[V], res[V];
+#pragma unroll
+            for (int j = 0; j < V; ++j) z[j] = (on && row_on) ? o[j] : 0.f;
+            lrn_vec(z, res);
+#pragma unroll
+            for (int j = 0; j < V; ++j) o[j] = res[j];
+        }
+        if (on && row_on) Store<T>::stv(y + (((size_t)n * P + p0 + i) * Q + q) * C + cv * V, o);
+    }
+}
+
+// y = maxpool(lrn(x)) through LDS: a workgroup normalises the input patch of a TP x TQ tile of outputs once
+// (pixel by pixel, the lanes of a pixel exchanging their edge channels by shuffle), keeps it in LDS as fp32,
+// and then takes the 3x3 maxima from there.  An input pixel is normalised once per tile that holds it
+// (1.2 - 1.5 times on average) instead of once per window.  PH x PW = patch size, LP = lanes per pixel (a
+// power of two >= C / V).
+template <typename T, int STRIDE, int TP, int TQ>
+__global__ __launch_bounds__(256) void lrn_pool_lds_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int H, int W, int P, int Q,
+                                                           int ptiles, int qtiles, int lp_log2, int pad, float a_over_n, float beta, float k,
+                                                           int b075)
+{
+    constexpr int V = Store<T>::VN, PH = (TP - 1) * STRIDE + 3, PW = (TQ - 1) * STRIDE + 3;
+    extern __shared__ __attribute__((aligned(16))) float patch[];       // [PH * PW][C]
+    const int CV = C / V;
+    const int lp = 1 << lp_log2, slots = 256 >> lp_log2;
+    const int cv = threadIdx.x & (lp - 1), slot = threadIdx.x >> lp_log2;
+    const unsigned qt = blockIdx.x % (unsigned)qtiles, t = blockIdx.x / (unsigned)qtiles;
+    const unsigned pt = t % (unsigned)ptiles, n = t / (unsigned)ptiles;
+    const int p0 = (int)pt * TP, q0 = (int)qt * TQ;
+    const int h0 = p0 * STRIDE - pad, w0 = q0 * STRIDE - pad;
+    const bool lane_on = cv < CV, has_l = cv > 0, has_r = cv < CV - 1;
+    const T* xb = x + (size_t)n * H * W * C;
+
+    // ---- normalise the patch, NB pixels per thread at a time with their loads issued together (every lane
+    // runs every iteration: the shuffles need whole waves)
+    constexpr int NB = 6;
+    for (int pp0 = 0; pp0 < PH * PW; pp0 += NB * slots) {
+        uint4 raw[NB];
+        bool px_on[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int pp = pp0 + u * slots + slot;
+            const int pr = pp / PW, pc = pp - pr * PW;
+            const int h = h0 + pr, w = w0 + pc;
+            px_on[u] = pp < PH * PW && (unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W;
+            raw[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (px_on[u] && lane_on) raw[u] = *reinterpret_cast<const uint4*>(xb + ((size_t)h * W + w) * C + cv * V);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int pp = pp0 + u * slots + slot;
+            float v[V];
+            unpack16<T>(raw[u], v);
+            float sq[V + 4];
+#pragma unroll
+            for (int j = 0; j < V; ++j) sq[j + 2] = v[j] * v[j];
+            const float l0 = __shfl_up(sq[V], 1, 64), l1 = __shfl_up(sq[V + 1], 1, 64);
+            const float r0 = __shfl_down(sq[2], 1, 64), r1 = __shfl_down(sq[3], 1, 64);
+            sq[0] = has_l ? l0 : 0.f; sq[1] = has_l ? l1 : 0.f;
+            sq[V + 2] = has_r ? r0 : 0.f; sq[V + 3] = has_r ? r1 : 0.f;
+            if (pp < PH * PW && lane_on) {
+                float o[V];
+#pragma unroll
+                for (int j = 0; j < V; ++j) {
+                    const float ss = ((sq[j] + sq[j + 1]) + sq[j + 2]) + (sq[j + 3] + sq[j + 4]);
+                    o[j] = px_on[u] ? v[j] * pow_neg_beta(fmaf(a_over_n, ss, k), beta, b075) : -INFINITY;   // outside the input: never wins
+                }
+                float* dst = patch + (size_t)pp * C + cv * V;
+#pragma unroll
+                for (int j = 0; j < V; j += 4) *reinterpret_cast<float4*>(dst + j) = make_float4(o[j], o[j + 1], o[j + 2], o[j + 3]);
+            }
+        }
+    }
+    __syncthreads();
+    // ---- 3x3 maxima from LDS
+    for (int item = threadIdx.x; item < TP * TQ * CV; item += 256) {
+        const int op = item / CV, c = item - op * CV;
+        const int i = op / TQ, j = op - i * TQ;
+        const int p = p0 + i, q = q0 + j;
+        if (p >= P || q >= Q) continue;
+        float m[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) m[e] = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const float* src = patch + (size_t)((i * STRIDE + r) * PW + j * STRIDE + s) * C + c * V;
+#pragma unroll
+                for (int e = 0; e < V; e += 4) {
+                    const float4 f = *reinterpret_cast<const float4*>(src + e);
+                    m[e] = fmaxf(m[e], f.x); m[e + 1] = fmaxf(m[e + 1], f.y); m[e + 2] = fmaxf(m[e + 2], f.z); m[e + 3] = fmaxf(m[e + 3], f.w);
+                }
+            }
+        Store<T>::stv(y + (((size_t)n * P + p) * Q + q) * C + c * V, m);
+    }
+}
+
+template <typename T>
+int pool_lrn_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, const dr_lrn& l, bool lrn_first,
+                    hipStream_t st)
+{
+    constexpr int VN = Store<T>::VN;
+    if (tensor_elems(yd) == 0) return DR_OK;
+    const int cv = xd.c / VN;
+    int bx_log2 = 0;
+    while ((1 << bx_log2) < cv) ++bx_log2;
+    const int by = 256 >> bx_log2;
+    const int qgroups = (yd.w + by - 1) / by;
+    const int PRF = p.stride_h == 1 ? 4 : 2, strips = (yd.h + PRF - 1) / PRF;
+    if ((double)yd.n * strips * qgroups >= 2147483648.0) return fail(DR_ERR_UNSUPPORTED, "lrn + pooling: tensor too large");
+    if (lrn_first) {
+        // through LDS where the fp32 patch of a tile fits 64 KB (two workgroups per compute unit)
+        constexpr int TP1 = 4, TQ1 = 8, TP2 = 2, TQ2 = 8;
+        const int s = p.stride_h;
+        const int ph = s == 1 ? TP1 + 2 : (TP2 - 1) * 2 + 3, pw = s == 1 ? TQ1 + 2 : (TQ2 - 1) * 2 + 3;
+        const size_t lds = (size_t)ph * pw * xd.c * sizeof(float);
+        if (lds <= 64 * 1024) {
+            const int tp = s == 1 ? TP1 : TP2, tq = s == 1 ? TQ1 : TQ2;
+            const int ptiles = (yd.h + tp - 1) / tp, qtiles = (yd.w + tq - 1) / tq;
+            const dim3 g2((unsigned)((long)yd.n * ptiles * qtiles));
+            const float aon = l.alpha / (float)l.local_size;
+            if (s == 1)
+                hipLaunchKernelGGL((lrn_pool_lds_kernel<T, 1, TP1, TQ1>), g2, dim3(256), lds, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h,
+                                   yd.w, ptiles, qtiles, bx_log2, p.pad_h, aon, l.beta, l.k, (int)(l.beta == 0.75f));
+            else
+                hipLaunchKernelGGL((lrn_pool_lds_kernel<T, 2, TP2, TQ2>), g2, dim3(256), lds, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h,
+                                   yd.w, ptiles, qtiles, bx_log2, p.pad_h, aon, l.beta, l.k, (int)(l.beta == 0.75f));
+            return check_launch("lrn_maxpool");
+        }
+    }
+    const dim3 grid((unsigned)((long)yd.n * qgroups * strips));
+    const float a_over_n = l.alpha / (float)l.local_size;
+    const int b075 = (int)(l.beta == 0.75f);
+#define DR_PL(PR, S, F) hipLaunchKernelGGL((pool_lrn_kernel<T, PR, S, F>), grid, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, \
+                                           strips, qgroups, bx_log2, p.pad_h, a_over_n, l.beta, l.k, b075)
+    if (p.stride_h == 1) { if (lrn_first) DR_PL(4, 1, true); else DR_PL(4, 1, false); }
+    else { if (lrn_first) DR_PL(2, 2, true); else DR_PL(2, 2, false); }
+#undef DR_PL
+    return check_launch(lrn_first ? "lrn_maxpool" : "maxpool_lrn");
+}
+
 // ---- concat ----------------------------------------------------------------------------------------------
 struct ConcatArgs {
     const void* src[DR_MAX_BRANCHES];
@@ -629,6 +868,22 @@ int launch_pool_nhwc(const dr_tensor& xd, const void* x, const dr_tensor& yd, vo
 int launch_lrn_nhwc(const dr_tensor& d, const void* x, void* y, const dr_lrn& p, hipStream_t st)
 {
     return d.dtype == DR_BF16 ? lrn_launch<uint16_t>(d, x, y, p, st) : lrn_launch<float>(d, x, y, p, st);
+}
+
+bool pool_lrn_nhwc_supported(const dr_tensor& xd, const void* x, const void* y, const dr_pool& p, const dr_lrn& l)
+{
+    const int vn = xd.dtype == DR_BF16 ? 8 : 4;
+    return xd.layout == DR_NHWC && xd.c % vn == 0 && xd.c / vn <= 64 && aligned16(x) && aligned16(y) && p.kh == 3 && p.kw == 3 &&
+           p.stride_h == p.stride_w && (p.stride_h == 1 || p.stride_h == 2) && p.pad_h == p.pad_w && p.pad_h <= 1 && l.local_size == 5;
+}
+
+int launch_pool_lrn_nhwc(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y, const dr_pool& p, const dr_lrn& l, bool lrn_first,
+                         hipStream_t st)
+{
+    TraceScope trace(lrn_first ? "lrn_maxpool" : "maxpool_lrn", nullptr, (long long)tensor_elems(yd), st,
+                     (long long)(tensor_bytes(xd) + tensor_bytes(yd)));
+    return xd.dtype == DR_BF16 ? pool_lrn_launch<uint16_t>(xd, x, yd, y, p, l, lrn_first, st)
+                               : pool_lrn_launch<float>(xd, x, yd, y, p, l, lrn_first, st);
 }
 
 int launch_concat_nhwc(const dr_tensor& yd, int nb, const ConcatSeg* segs, void* y, hipStream_t st)

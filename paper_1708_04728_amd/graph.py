@@ -86,8 +86,13 @@ def _out_channels(layers, c_in):
     return c
 
 
-def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False, pack=False):
+def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False, pack=False, fuse_nontensor=False):
     """List of dr_layer_desc for a layer list.
+
+    fuse_nontensor: a maxpool directly followed by an lrn becomes one layer that makes a single pass over the
+               tensor (channels-last tensors only); "all": so does an lrn directly followed by a maxpool
+               (measured slower than the two layers on their own at stride 2: every input pixel is
+               normalised, four per output, and that arithmetic, not memory, bounds it).
 
     fuse_relu: a conv directly followed by a relu becomes one conv with the ReLU in its store
                (the slim form always runs this way; for the original form it is the "fused"
@@ -106,8 +111,16 @@ def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False, pac
             L.kind = B.DR_LAYER_RELU
         elif kind == "lrn":
             L.kind, L.lrn = B.DR_LAYER_LRN, B.dr_lrn(p["n"], p["alpha"], p["beta"], p["k"])
+            if fuse_nontensor == "all" and i + 1 < len(layers) and layers[i + 1][0] == "maxpool":
+                q = layers[i + 1][1]
+                L.kind, L.pool = B.DR_LAYER_LRN_MAXPOOL, B.pool_desc(q["k"], q["stride"], q["pad"])
+                i += 1
         elif kind == "maxpool":
             L.kind, L.pool = B.DR_LAYER_MAXPOOL, B.pool_desc(p["k"], p["stride"], p["pad"])
+            if fuse_nontensor and i + 1 < len(layers) and layers[i + 1][0] == "lrn":
+                q = layers[i + 1][1]
+                L.kind, L.lrn = B.DR_LAYER_MAXPOOL_LRN, B.dr_lrn(q["n"], q["alpha"], q["beta"], q["k"])
+                i += 1
         elif kind == "avgpool":
             L.kind, L.pool = B.DR_LAYER_AVGPOOL, B.pool_desc(p["k"], 1, 0)
         elif kind == "inception":

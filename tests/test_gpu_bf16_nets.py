@@ -23,10 +23,11 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def run_net_bf16(layers, params, x, fuse_relu=False, inception_mode=0, folded=False):
+def run_net_bf16(layers, params, x, fuse_relu=False, inception_mode=0, folded=False, fuse_nontensor=False):
     """inception_mode with DR_FUSE_STACK: the parameters are laid out for it (graph.stack_first_steps)."""
     xg = G.to_device(x, "bf16", nhwc=True)
-    net = B.Net(G.net_descs(layers, x.shape[1], inception_mode=inception_mode, fuse_relu=fuse_relu, folded=folded, pack="bf16"))
+    net = B.Net(G.net_descs(layers, x.shape[1], inception_mode=inception_mode, fuse_relu=fuse_relu, folded=folded, pack="bf16",
+                            fuse_nontensor=fuse_nontensor))
     yd = net.output_desc(B.desc(xg))
     y = G.empty_like_desc(yd)
     ws = torch.empty(max(net.workspace_bytes(B.desc(xg)), 256), dtype=torch.uint8, device="cuda")
@@ -178,6 +179,22 @@ def test_inception_stacked_first_steps(form, module):
     net.fwd(xg, G.flat_params(params, "bf16", pack=True), y, ws)
     torch.cuda.synchronize()
     assert np.array_equal(G.to_host(y), plain)
+
+
+def test_config5_googlenet_original_structure_fused():
+    """The original structure with every fusion that leaves the function unchanged: ReLU and concat in the
+    convolution stores, stacked first steps, LRN and pooling of the stem in one pass each.  Same network,
+    same parameters, same oracle as the layer-by-layer form; fewer intermediate roundings."""
+    layers = workloads.CONFIGS[5]["original"]
+    params = workloads.make_params(5, "original")
+    x = workloads.make_input(5, 2)
+    ref = oracle.forward(layers, params, x, mirror_bf16=True).reshape(2, 1000)
+    mode = B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK
+    got = run_net_bf16(layers, params, x, fuse_relu=True, inception_mode=mode, fuse_nontensor="all").reshape(2, 1000)
+    np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-3)
+    assert rel_err(got, ref) < TOL_BF16 * math.sqrt(5 + 18 + 2)
+    plain = run_net_bf16(layers, params, x).reshape(2, 1000)
+    assert rel_err(got, plain) < TOL_BF16 * math.sqrt(5 + 18 + 2)
 
 
 # ---- full sizes, in the launch configuration the benchmark times -------------------------------------------

@@ -42,17 +42,17 @@ def test_inception_3a(form, mode, pack):
 @pytest.mark.parametrize("form", ["original", "slim"])
 def test_inception_branches_side_by_side_equal_branches_in_turn(form):
     """The branches of a module run on the library's own streams between a fork and a join on the caller's
-    stream.  The result must be bit-identical to running them in turn (DR_SERIAL_BRANCHES) and match the
+    stream (DR_CONCURRENT_BRANCHES).  The result must be bit-identical to running them in turn and match the
     oracle, call after call on the same workspace, with work of the caller queued before and after it."""
     layer = workloads.CONFIGS[2][form][0]
     params = workloads.make_params(2, form)
     x = workloads.make_input(2, 8)
     ref = oracle.forward([layer], params, x)
     for mode in (0, B.DR_FUSE_RELU | B.DR_FUSE_CONCAT):
-        serial = run_inception(layer, params, x, mode | B.DR_SERIAL_BRANCHES)
+        serial = run_inception(layer, params, x, mode)
         assert rel_err(serial, ref) < TOL_F32
         xg = G.to_device(x, "f32")
-        d = G.inception_desc(layer[1], x.shape[1], mode, False)
+        d = G.inception_desc(layer[1], x.shape[1], mode | B.DR_CONCURRENT_BRANCHES, False)
         ws = torch.empty(max(B.inception_workspace_bytes(xg, d), 256), dtype=torch.uint8, device="cuda")
         flat = G.flat_params(params, "f32", pack=False)
         side = torch.cuda.Stream()

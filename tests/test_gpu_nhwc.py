@@ -158,3 +158,48 @@ def test_concat_bn_avgpool_nhwc(dtype):
         B.avgpool_fwd(gpu_nhwc(x, dtype), B.pool_desc(win, 1), y)
         torch.cuda.synchronize()
         assert rel_err(host_nhwc(y), ref) < _tol(dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("order", ["lrn_maxpool", "maxpool_lrn"])
+@pytest.mark.parametrize("case", [(2, 64, 23, 23, 2, 0), (2, 192, 28, 28, 2, 0), (1, 24, 9, 11, 1, 1), (2, 8, 5, 7, 2, 1),
+                                  (1, 256, 6, 6, 1, 1), (1, 40, 14, 14, 2, 0), (1, 256, 9, 9, 2, 0), (1, 512, 5, 5, 1, 1)])
+def test_lrn_and_maxpool_in_one_pass(dtype, order, case):
+    """The non-tensor tail of a streamlined block in one kernel, in either order, against the composition of the
+    oracle's two layers (LRN window clipped at the first / last channel, pooling windows clipped at the
+    borders, ceil-mode sizes with ragged last windows).  Large values make the normalisation matter; mixed
+    signs make the maximum differ before and after it."""
+    N, C, H, W, s, pad = case
+    if C // (4 if dtype == "f32" else 8) > 64:
+        pytest.skip("more than 64 channel groups per pixel")
+    x = _vals(np.random.default_rng(11), (N, C, H, W), dtype) * np.float32(40.0)
+    if dtype == "bf16":
+        x = workloads.round_to_bf16(x)
+    ld, pd = B.dr_lrn(5, 1e-4, 0.75, 1.0), B.pool_desc(3, s, pad)
+    if order == "lrn_maxpool":
+        ref = oracle.maxpool(oracle.lrn(x, 5, 1e-4, 0.75, 1.0), 3, s, pad)
+        y = empty_nhwc(ref.shape, dtype)
+        B.lrn_maxpool_fwd(gpu_nhwc(x, dtype), ld, pd, y)
+    else:
+        ref = oracle.lrn(oracle.maxpool(x, 3, s, pad), 5, 1e-4, 0.75, 1.0)
+        y = empty_nhwc(ref.shape, dtype)
+        B.maxpool_lrn_fwd(gpu_nhwc(x, dtype), pd, ld, y)
+    torch.cuda.synchronize()
+    got = host_nhwc(y)
+    assert not np.isnan(got).any()
+    assert rel_err(got, ref) < _tol(dtype)
+
+
+def test_lrn_and_maxpool_in_one_pass_rejects_what_it_cannot_run():
+    x = gpu_nhwc(np.zeros((1, 12, 8, 8), np.float32), "bf16")          # 12 channels: not a multiple of 8
+    y = empty_nhwc((1, 12, 4, 4), "bf16")
+    with pytest.raises(B.DeepRebirthError):
+        B.lrn_maxpool_fwd(x, B.dr_lrn(5, 1e-4, 0.75, 1.0), B.pool_desc(3, 2, 0), y)
+    x = gpu(np.zeros((1, 16, 8, 8), np.float32), "f32")                # NCHW
+    y = torch.empty((1, 16, 4, 4), device="cuda")
+    with pytest.raises(B.DeepRebirthError):
+        B.maxpool_lrn_fwd(x, B.pool_desc(3, 2, 0), B.dr_lrn(5, 1e-4, 0.75, 1.0), y)
+    x = gpu_nhwc(np.zeros((1, 16, 8, 8), np.float32), "bf16")          # LRN window of 3
+    y = empty_nhwc((1, 16, 4, 4), "bf16")
+    with pytest.raises(B.DeepRebirthError):
+        B.lrn_maxpool_fwd(x, B.dr_lrn(3, 1e-4, 0.75, 1.0), B.pool_desc(3, 2, 0), y)
