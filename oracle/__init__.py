@@ -40,8 +40,9 @@ def _L():
         _lib.orc_conv_out_size.restype = ctypes.c_int
         _lib.orc_pool_out_size.restype = ctypes.c_int
         for name in ("orc_conv2d", "orc_relu", "orc_lrn", "orc_maxpool", "orc_avgpool", "orc_concat_into",
-                     "orc_bn", "orc_fold_bn", "orc_add_relu", "orc_fc", "orc_softmax", "orc_round_bf16"):
+                     "orc_bn", "orc_fold_bn", "orc_add_relu", "orc_fc", "orc_softmax", "orc_round_bf16", "orc_conv2d_bwd_params"):
             getattr(_lib, name).restype = None
+        _lib.orc_regression_loss_grad.restype = ctypes.c_double
     return _lib
 
 
@@ -168,6 +169,41 @@ def softmax(x):
     y = np.empty_like(x)
     _L().orc_softmax(_p(x), _i(N), _i(O), _p(y))
     return y
+
+
+def regression_loss_grad(f, y):
+    """Sec. 3.1, the optimisation goal of the slim layer: L = sum (f - y)^2 for the layer's output f (after its
+    ReLU) and the target feature map y; returns (L, dL/dz) with z the layer's pre-activation."""
+    f, y = _f64(f), _f64(y)
+    assert f.shape == y.shape
+    dz = np.empty_like(f)
+    loss = _L().orc_regression_loss_grad(_p(f), _p(y), _z(f.size), _p(dz))
+    return float(loss), dz
+
+
+def conv2d_bwd_params(x, dz, r, s=None, stride=1, pad=0):
+    """Gradient of a convolution's parameters given dL/dz of its output (chain rule through Eq. (7)):
+    returns (dw of shape (k, c, r, s), db of shape (k,))."""
+    x, dz = _f64(x), _f64(dz)
+    s = r if s is None else s
+    N, C, H, W = x.shape
+    K = dz.shape[1]
+    sh, sw = (stride, stride) if np.isscalar(stride) else stride
+    ph, pw = (pad, pad) if np.isscalar(pad) else pad
+    assert dz.shape == (N, K, conv_out_size(H, r, sh, ph), conv_out_size(W, s, sw, pw)), dz.shape
+    dw, db = np.empty((K, C, r, s)), np.empty(K)
+    _L().orc_conv2d_bwd_params(_p(x), _i(N), _i(C), _i(H), _i(W), _p(dz), _i(K), _i(r), _i(s), _i(sh), _i(sw), _i(ph), _i(pw),
+                               _p(dw), _p(db))
+    return dw, db
+
+
+def regression_step(x, w, b, y, stride, pad, lr):
+    """One step of gradient descent on L(w, b) = sum || y - max(conv(x; w, b), 0) ||^2 (Lemma 1: the slim layer is
+    learned with SGD on Eq. (5)'s objective): returns (L at (w, b), w - lr dL/dw, b - lr dL/db)."""
+    f = conv2d(x, w, b, stride, pad, relu=True)
+    loss, dz = regression_loss_grad(f, y)
+    dw, db = conv2d_bwd_params(x, dz, w.shape[2], w.shape[3], stride, pad)
+    return loss, _f64(w) - lr * dw, _f64(b) - lr * db
 
 
 def round_bf16(x):

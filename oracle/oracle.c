@@ -223,3 +223,53 @@ void orc_round_bf16(double *x, size_t count)
         x[i] = x[i] < 0 ? -v : v;
     }
 }
+
+/* ---- layer-wise regression of a slim layer (Sec. 3.1, the optimisation goal below Eq. (4) and Lemma 1) ----
+ * The slim layer f~(W, b; X) = max(conv(X; W, b), 0) is fitted to the feature map Y of the block it replaces
+ * by minimising  L(W, b) = sum_i || Y^i - f~(W, b; X^i) ||_F^2  with gradient descent. */
+
+/* L and dL/dz for the pre-activation z of the slim layer, given its output f = max(z, 0) and the target y:
+ *   L = sum (f - y)^2,   dz = 2 (f - y) where f > 0 (there z = f and df/dz = 1), else 0. */
+double orc_regression_loss_grad(const double *f, const double *y, size_t count, double *dz)
+{
+    double loss = 0.0;
+    for (size_t i = 0; i < count; ++i) {
+        const double d = f[i] - y[i];
+        loss += d * d;
+        dz[i] = f[i] > 0.0 ? 2.0 * d : 0.0;
+    }
+    return loss;
+}
+
+/* Chain rule through z[n,k,p,q] = b[k] + sum_{c,r,s} w[k,c,r,s] x[n,c,p*sh+r-ph,q*sw+s-pw] (Eq. (7)):
+ *   dw[k,c,r,s] = sum_{n,p,q} dz[n,k,p,q] x[n,c,p*sh+r-ph,q*sw+s-pw]   (terms in the zero padding drop out),
+ *   db[k]       = sum_{n,p,q} dz[n,k,p,q]. */
+void orc_conv2d_bwd_params(const double *x, int N, int C, int H, int W, const double *dz, int K, int R, int S,
+                           int sh, int sw, int ph, int pw, double *dw, double *db)
+{
+    const int P = orc_conv_out_size(H, R, sh, ph), Q = orc_conv_out_size(W, S, sw, pw);
+#pragma omp parallel for schedule(static)
+    for (int k = 0; k < K; ++k) {
+        double sb = 0.0;
+        for (int n = 0; n < N; ++n)
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q) sb += dz[(((size_t)n * K + k) * P + p) * Q + q];
+        db[k] = sb;
+        for (int c = 0; c < C; ++c)
+            for (int r = 0; r < R; ++r)
+                for (int s = 0; s < S; ++s) {
+                    double acc = 0.0;
+                    for (int n = 0; n < N; ++n)
+                        for (int p = 0; p < P; ++p) {
+                            const int ih = p * sh + r - ph;
+                            if (ih < 0 || ih >= H) continue;
+                            for (int q = 0; q < Q; ++q) {
+                                const int iw = q * sw + s - pw;
+                                if (iw < 0 || iw >= W) continue;
+                                acc += dz[(((size_t)n * K + k) * P + p) * Q + q] * x[(((size_t)n * C + c) * H + ih) * W + iw];
+                            }
+                        }
+                    dw[(((size_t)k * C + c) * R + r) * S + s] = acc;
+                }
+    }
+}

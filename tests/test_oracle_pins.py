@@ -380,3 +380,87 @@ def test_table4_fixture_is_consistent():
     assert 0 <= tot[0] - sum(v[0] for v in rows.values()) < 2.0
     assert 0 <= tot[1] - sum(v[1] for v in rows.values()) < 2.0
     assert abs(tot[0] / tot[1] - 3.09) < 0.01
+
+
+# ---- layer-wise regression of a slim layer (Sec. 3.1: the optimisation goal below Eq. (4), Lemma 1) ------------
+def _loss(x, w, b, y, stride, pad):
+    f = oracle.conv2d(x, w, b, stride, pad, relu=True)
+    return oracle.regression_loss_grad(f, y)[0]
+
+
+def test_regression_gradients_match_finite_differences():
+    """The gradient is what the loss does under a small change of one parameter: central differences of L
+    itself (which only needs the forward pass, pinned above) against dw, db for every bias and a spread of
+    weights; strides, padding and a non-square filter so that a transposed index or a dropped padding
+    term shows."""
+    rng = np.random.default_rng(42)
+    for (N, C, H, W, K, R, S, stride, pad) in [(2, 3, 7, 6, 4, 3, 2, 2, 1), (1, 2, 5, 5, 3, 3, 3, 1, 1), (2, 2, 6, 8, 2, 1, 1, 1, 0),
+                                                (1, 1, 9, 7, 2, 5, 3, (2, 1), (2, 0))]:
+        x = rng.standard_normal((N, C, H, W))
+        w = rng.standard_normal((K, C, R, S)) * 0.4
+        b = rng.standard_normal(K) * 0.2
+        f = oracle.conv2d(x, w, b, stride, pad, relu=True)
+        y = np.abs(rng.standard_normal(f.shape))
+        loss, dz = oracle.regression_loss_grad(f, y)
+        assert loss == pytest.approx(((f - y) ** 2).sum(), rel=1e-14)
+        dw, db = oracle.conv2d_bwd_params(x, dz, R, S, stride, pad)
+        h = 1e-6
+        for k in range(K):
+            bp, bm = b.copy(), b.copy()
+            bp[k] += h
+            bm[k] -= h
+            fd = (_loss(x, w, bp, y, stride, pad) - _loss(x, w, bm, y, stride, pad)) / (2 * h)
+            assert fd == pytest.approx(db[k], rel=1e-5, abs=1e-7)
+        for _ in range(12):
+            idx = tuple(int(rng.integers(0, n)) for n in w.shape)
+            wp, wm = w.copy(), w.copy()
+            wp[idx] += h
+            wm[idx] -= h
+            fd = (_loss(x, wp, b, y, stride, pad) - _loss(x, wm, b, y, stride, pad)) / (2 * h)
+            assert fd == pytest.approx(dw[idx], rel=1e-5, abs=1e-7)
+
+
+def test_conv_param_gradient_of_1x1_is_a_matrix_product():
+    """For a 1x1 convolution z = W X per image, so dW = sum_n dZ_n X_n^T and db = row sums of dZ: numpy's matmul."""
+    rng = np.random.default_rng(43)
+    x = rng.standard_normal((3, 5, 4, 6))
+    dz = rng.standard_normal((3, 7, 4, 6))
+    dw, db = oracle.conv2d_bwd_params(x, dz, 1, 1, 1, 0)
+    ref = sum(dz[n].reshape(7, -1) @ x[n].reshape(5, -1).T for n in range(3))
+    np.testing.assert_allclose(dw[:, :, 0, 0], ref, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(db, dz.sum(axis=(0, 2, 3)), rtol=1e-12)
+    # linear in dz, and a strided / padded case against brute force over the definition
+    dz2 = rng.standard_normal(dz.shape)
+    dw2, db2 = oracle.conv2d_bwd_params(x, dz + 2 * dz2, 1, 1, 1, 0)
+    dwb, dbb = oracle.conv2d_bwd_params(x, dz2, 1, 1, 1, 0)
+    np.testing.assert_allclose(dw2, dw + 2 * dwb, rtol=1e-12, atol=1e-12)
+    x = rng.standard_normal((2, 2, 5, 4))
+    P, Q = oracle.conv_out_size(5, 3, 2, 1), oracle.conv_out_size(4, 2, 1, 0)
+    dz = rng.standard_normal((2, 3, P, Q))
+    dw, _ = oracle.conv2d_bwd_params(x, dz, 3, 2, (2, 1), (1, 0))
+    xp = np.pad(x, ((0, 0), (0, 0), (1, 1), (0, 0)))
+    for k in range(3):
+        for c in range(2):
+            for r in range(3):
+                for s in range(2):
+                    want = sum(dz[n, k, p, q] * xp[n, c, p * 2 + r, q + s] for n in range(2) for p in range(P) for q in range(Q))
+                    assert dw[k, c, r, s] == pytest.approx(want, rel=1e-12, abs=1e-12)
+
+
+def test_regression_has_zero_gradient_at_the_generating_layer_and_descends():
+    """If the target is the output of a layer of the same shape, that layer's parameters have zero loss and zero
+    gradient; from a perturbed start, gradient steps with a small rate lower the loss every time."""
+    rng = np.random.default_rng(44)
+    x = rng.standard_normal((4, 3, 8, 8))
+    w_star = rng.standard_normal((5, 3, 3, 3)) * 0.3
+    b_star = rng.standard_normal(5) * 0.1
+    y = oracle.conv2d(x, w_star, b_star, 2, 1, relu=True)
+    loss, dz = oracle.regression_loss_grad(y, y)
+    assert loss == 0.0 and not dz.any()
+    w, b = w_star + rng.standard_normal(w_star.shape) * 0.1, b_star + 0.05
+    losses = []
+    for _ in range(25):
+        loss, w, b = oracle.regression_step(x, w, b, y, 2, 1, lr=2e-3)
+        losses.append(loss)
+    assert all(b_ < a_ for a_, b_ in zip(losses, losses[1:]))
+    assert losses[-1] < 0.2 * losses[0]
