@@ -157,6 +157,31 @@ int dr_fc_fwd(const dr_tensor* xd, const void* x, const void* w, const float* bi
 /* Softmax over the channel axis of an {n, c, 1, 1} tensor; the output y is always fp32. */
 int dr_softmax_fwd(const dr_tensor* xd, const void* x, float* y, void* stream);
 
+/* ---- learning a slim layer (Sec. 3.1: the optimisation goal below Eq. (4), Lemma 1) ------------------------------
+ * The slim layer f~(W, b; X) = max(conv(X; W, b), 0) (dr_slim_conv_fwd) is fitted to the feature map Y of the block
+ * it replaces by gradient descent on L(W, b) = sum || Y - f~(W, b; X) ||_F^2.  One step: the forward pass, then
+ * dr_regression_loss_grad, dr_conv2d_bwd_params, and dr_sgd_step on the filters and on the biases.
+ * fp32, NCHW tensors, KCRS filters; anything else is DR_ERR_UNSUPPORTED. */
+
+/* L = sum (f - target)^2 and dL/dz for the layer's pre-activation z: dz = 2 (f - target) where f > 0, else 0.
+ * f: the layer's output (after its ReLU), target, dz: tensors of descriptor d (dz may alias f).  loss: one
+ * device float.  ws: device scratch of at least dr_regression_loss_workspace_bytes(). */
+size_t dr_regression_loss_workspace_bytes(void);
+int dr_regression_loss_grad(const dr_tensor* d, const void* f, const void* target, void* dz, float* loss, void* ws, size_t ws_bytes,
+                            void* stream);
+
+/* Gradient of the convolution's parameters from the gradient dz of its output (chain rule through Eq. (7)):
+ *   dw[k,c,r,s] = sum_{n,p,q} dz[n,k,p,q] x[n,c,p*sh+r-ph,q*sw+s-pw],   db[k] = sum_{n,p,q} dz[n,k,p,q].
+ * dzd must be the convolution's output descriptor for input xd; dw has the filters' shape (KCRS), db (may be
+ * NULL) k floats.  ws: device scratch of at least dr_conv2d_bwd_params_workspace_bytes (partial sums over ranges
+ * of images, added in a fixed order: the result does not depend on scheduling). */
+int dr_conv2d_bwd_params_workspace_bytes(const dr_tensor* xd, const dr_conv* cd, size_t* bytes);
+int dr_conv2d_bwd_params(const dr_tensor* xd, const void* x, const dr_conv* cd, const dr_tensor* dzd, const void* dz, void* dw,
+                         float* db, void* ws, size_t ws_bytes, void* stream);
+
+/* One step of gradient descent on count fp32 parameters: w[i] = w[i] - lr * dw[i]. */
+int dr_sgd_step(size_t count, float* w, const float* dw, float lr, void* stream);
+
 /* ---- inception module (Sec. 3.2, Fig. 4) ---------------------------------------------------- */
 
 #define DR_MAX_STEPS 4

@@ -99,6 +99,11 @@ _SIGNATURES = {
     "dr_fold_bn": ([_i, _z, _vp, _vp, _vp, _vp, _vp, _vp, _f, _vp, _vp], _i),
     "dr_fc_fwd": ([_P(dr_tensor), _vp, _vp, _vp, _P(dr_tensor), _vp, _vp], _i),
     "dr_softmax_fwd": ([_P(dr_tensor), _vp, _vp, _vp], _i),
+    "dr_regression_loss_workspace_bytes": ([], _z),
+    "dr_regression_loss_grad": ([_P(dr_tensor), _vp, _vp, _vp, _vp, _vp, _z, _vp], _i),
+    "dr_conv2d_bwd_params_workspace_bytes": ([_P(dr_tensor), _P(dr_conv), _P(_z)], _i),
+    "dr_conv2d_bwd_params": ([_P(dr_tensor), _vp, _P(dr_conv), _P(dr_tensor), _vp, _vp, _vp, _vp, _z, _vp], _i),
+    "dr_sgd_step": ([_z, _vp, _vp, _f, _vp], _i),
     "dr_inception_workspace_bytes": ([_P(dr_tensor), _P(dr_inception), _P(_z)], _i),
     "dr_inception_fwd": ([_P(dr_tensor), _vp, _P(dr_inception), _P(_vp), _P(_vp), _P(dr_tensor), _vp, _vp, _z, _vp], _i),
     "dr_net_create": ([_P(dr_layer_desc), _i, _P(_vp)], _i),
@@ -320,6 +325,34 @@ def inception_fwd(x, idesc, weights, biases, y, ws, stream=None):
     _check(lib().dr_inception_fwd(desc(x), _ptr(x), idesc, wp, bp, desc(y), _ptr(y), _ptr(ws),
                                   0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
     return y
+
+
+def regression_loss_grad(f, target, dz, loss, ws, stream=None):
+    """dz = dL/dz and loss[0] = L = sum (f - target)^2 for a slim layer's output f (after its ReLU); all device tensors."""
+    _check(lib().dr_regression_loss_grad(desc(f), _ptr(f), _ptr(target), _ptr(dz), _ptr(loss), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream(stream)))
+    return dz
+
+
+def regression_loss_workspace_bytes():
+    return int(lib().dr_regression_loss_workspace_bytes())
+
+
+def conv2d_bwd_params_workspace_bytes(x, cd):
+    n = C.c_size_t(0)
+    _check(lib().dr_conv2d_bwd_params_workspace_bytes(desc(x), cd, C.byref(n)))
+    return n.value
+
+
+def conv2d_bwd_params(x, cd, dz, dw, db, ws, stream=None):
+    _check(lib().dr_conv2d_bwd_params(desc(x), _ptr(x), cd, desc(dz), _ptr(dz), _ptr(dw), _ptr(db), _ptr(ws),
+                                      0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
+    return dw, db
+
+
+def sgd_step(w, dw, lr, stream=None):
+    _check(lib().dr_sgd_step(w.numel(), _ptr(w), _ptr(dw), lr, _stream(stream)))
+    return w
 
 
 def trace_begin(label_filter="", conv_k=0, conv_c=0, conv_r=0, capacity=4096):

@@ -879,6 +879,76 @@ int dr_softmax_fwd(const dr_tensor* xd, const void* x, float* y, void* stream)
     return launch_softmax(xd->dtype, x, y, xd->n, xd->c, (hipStream_t)stream);
 }
 
+size_t dr_regression_loss_workspace_bytes(void) { return regression_loss_workspace_bytes(); }
+
+int dr_regression_loss_grad(const dr_tensor* d, const void* f, const void* target, void* dz, float* loss, void* ws, size_t ws_bytes,
+                            void* stream)
+{
+    const char* who = "dr_regression_loss_grad";
+    DR_TRY(check_tensor(who, "d", d));
+    if (d->dtype != DR_F32) return fail(DR_ERR_UNSUPPORTED, "%s: fp32 tensors only", who);
+    if (!loss) return fail(DR_ERR_NULL, "%s: loss is NULL", who);
+    if (!ws || ws_bytes < regression_loss_workspace_bytes()) return fail(DR_ERR_WORKSPACE, "%s: needs %zu bytes of workspace", who, regression_loss_workspace_bytes());
+    const size_t count = tensor_elems(*d);
+    if (count && (!f || !target || !dz)) return fail(DR_ERR_NULL, "%s: f, target or dz is NULL", who);
+    return launch_regression_loss_grad((const float*)f, (const float*)target, (float*)dz, count, loss, ws, (hipStream_t)stream);
+}
+
+static int bwd_params_geom(const char* who, const dr_tensor* xd, const dr_conv* cd, ConvGeom* g, dr_tensor* o)
+{
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_conv_desc(who, cd));
+    if (xd->dtype != DR_F32 || xd->layout != DR_NCHW || cd->filter_layout != DR_KCRS)
+        return fail(DR_ERR_UNSUPPORTED, "%s: fp32 NCHW tensors and KCRS filters only", who);
+    if (xd->c != cd->c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd->c, cd->c);
+    *o = conv_out(*xd, *cd);
+    if ((double)xd->n * xd->c * xd->h * xd->w * 4 >= 2147483648.0 || (double)o->n * o->c * o->h * o->w * 4 >= 2147483648.0)
+        return fail(DR_ERR_UNSUPPORTED, "%s: tensors of 2 GiB or more", who);
+    g->N = xd->n; g->C = xd->c; g->H = xd->h; g->W = xd->w;
+    g->K = cd->k; g->R = cd->r; g->S = cd->s;
+    g->sh = cd->stride_h; g->sw = cd->stride_w; g->ph = cd->pad_h; g->pw = cd->pad_w;
+    g->P = o->h; g->Q = o->w;
+    g->Kg = cd->c * cd->r * cd->s;
+    g->Ng = o->n * o->h * o->w;
+    g->y_ctot = cd->k; g->y_coff = 0; g->relu = 0; g->res_ctot = 0; g->w_krsc = 0; g->nhwc = 0; g->c_logical = 0;
+    return DR_OK;
+}
+
+int dr_conv2d_bwd_params_workspace_bytes(const dr_tensor* xd, const dr_conv* cd, size_t* bytes)
+{
+    const char* who = "dr_conv2d_bwd_params_workspace_bytes";
+    if (!bytes) return fail(DR_ERR_NULL, "%s: bytes is NULL", who);
+    ConvGeom g;
+    dr_tensor o;
+    DR_TRY(bwd_params_geom(who, xd, cd, &g, &o));
+    *bytes = conv_wgrad_workspace_bytes(g);
+    return DR_OK;
+}
+
+int dr_conv2d_bwd_params(const dr_tensor* xd, const void* x, const dr_conv* cd, const dr_tensor* dzd, const void* dz, void* dw,
+                         float* db, void* ws, size_t ws_bytes, void* stream)
+{
+    const char* who = "dr_conv2d_bwd_params";
+    ConvGeom g;
+    dr_tensor o;
+    DR_TRY(bwd_params_geom(who, xd, cd, &g, &o));
+    DR_TRY(check_tensor(who, "dzd", dzd));
+    if (!same_shape(o, *dzd) || dzd->dtype != DR_F32 || dzd->layout != DR_NCHW)
+        return fail(DR_ERR_SHAPE, "%s: dz must be the layer's fp32 NCHW output, %dx%dx%dx%d", who, o.n, o.c, o.h, o.w);
+    const size_t need = conv_wgrad_workspace_bytes(g);
+    if (need > 0 && (!ws || ws_bytes < need)) return fail(DR_ERR_WORKSPACE, "%s: needs %zu bytes of workspace", who, need);
+    if ((size_t)g.K * g.Kg == 0) return DR_OK;
+    if (!dw) return fail(DR_ERR_NULL, "%s: dw is NULL", who);
+    if (g.Ng > 0 && (!x || !dz)) return fail(DR_ERR_NULL, "%s: x or dz is NULL", who);     // (no terms: the kernels write zeros)
+    return launch_conv_wgrad_f32(g, (const float*)x, (const float*)dz, (float*)dw, db, ws, (hipStream_t)stream);
+}
+
+int dr_sgd_step(size_t count, float* w, const float* dw, float lr, void* stream)
+{
+    if (count && (!w || !dw)) return fail(DR_ERR_NULL, "dr_sgd_step: w or dw is NULL");
+    return launch_sgd_step(w, dw, lr, count, (hipStream_t)stream);
+}
+
 int dr_inception_workspace_bytes(const dr_tensor* xd, const dr_inception* desc, size_t* bytes)
 {
     const char* who = "dr_inception_workspace_bytes";

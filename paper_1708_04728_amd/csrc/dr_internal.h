@@ -67,6 +67,13 @@ bool conv_bf16_stem_eligible(const ConvGeom& g);
 int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias,
                           uint16_t* y, hipStream_t st);
 
+// train.hip: regression of a slim layer (fp32, NCHW, KCRS)
+size_t regression_loss_workspace_bytes();
+int launch_regression_loss_grad(const float* f, const float* y, float* dz, size_t count, float* loss, void* ws, hipStream_t st);
+size_t conv_wgrad_workspace_bytes(const ConvGeom& g);
+int launch_conv_wgrad_f32(const ConvGeom& g, const float* x, const float* dz, float* dw, float* db, void* ws, hipStream_t st);
+int launch_sgd_step(float* w, const float* dw, float lr, size_t count, hipStream_t st);
+
 // pointwise.hip
 int launch_pack_filters(int dtype, const void* w_kcrs, void* w_krsc, int K, int C, int RS, hipStream_t st);
 int launch_relu(int dtype, const void* x, void* y, size_t count, hipStream_t st);
