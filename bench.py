@@ -108,6 +108,65 @@ def paper_variant_ms(wl, reps=20):
     return best
 
 
+def slim_layer_regression(batch=32, iters=40, lr=2e-7):
+    """Sec. 3.1, Lemma 1 on config 1's block: the slim layer (3x3, 64 -> 192, stride 2, ReLU) is learned by gradient
+    descent on sum || Y - f~(W, b; X) ||^2, Y being the output of the original block (conv - ReLU - LRN - pool) on
+    `batch` seeded images, from fresh He-normal weights.  A toy: it shows the loss falling and what one step
+    costs, not accuracy.  Everything runs in the library's kernels; times from HIP events."""
+    import numpy as np
+    import torch
+
+    import workloads
+    from paper_1708_04728_amd import binding as B, graph as G
+    x = workloads.make_input(1, batch)
+    c_in = x.shape[1]
+    xg = G.to_device(x, "f32")
+    stream = torch.cuda.current_stream()
+    net = B.Net(G.net_descs(workloads.CONFIGS[1]["original"], c_in))
+    xd = B.desc(xg)
+    y = G.empty_like_desc(net.output_desc(xd))
+    ws = torch.empty(max(net.workspace_bytes(xd), 256), dtype=torch.uint8, device="cuda")
+    net.fwd(xg, G.flat_params(workloads.make_params(1, "original"), "f32"), y, ws, stream)      # the target feature map
+    q = workloads.make_params(1, "slim")[0]
+    w, b = G.to_device(q["w"], "f32"), G.to_device(q["b"], "f32")
+    k, c, r, s = w.shape
+    cd1 = B.conv_desc(k, c, r, s, 1, 1, False, B.DR_KCRS)        # dr_slim_conv_fwd multiplies the stride by the pool's
+    cd2 = B.conv_desc(k, c, r, s, 2, 1, True, B.DR_KCRS)
+    f = torch.empty_like(y)
+    dw, db, loss = torch.empty_like(w), torch.empty_like(b), torch.zeros(1, device="cuda")
+    ws2 = torch.empty(max(B.conv2d_bwd_params_workspace_bytes(xg, cd2), B.regression_loss_workspace_bytes(), 256), dtype=torch.uint8, device="cuda")
+    losses = []
+
+    def step(record):
+        B.slim_conv_fwd(xg, cd1, 2, w, b, f, stream=stream)
+        B.regression_loss_grad(f, y, f, loss, ws2, stream)
+        if record:
+            losses.append(float(loss.item()))
+        B.conv2d_bwd_params(xg, cd2, f, dw, db, ws2, stream)
+        B.sgd_step(w, dw, lr, stream)
+        B.sgd_step(b, db, lr, stream)
+
+    for _ in range(iters):
+        step(True)
+    # one traced step for the per-kernel times, then the cost of a step without host round trips
+    B.trace_begin("", capacity=64)
+    step(False)
+    recs = B.trace_end(64)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(10):
+        step(False)
+    e1.record(stream)
+    e1.synchronize()
+    wg = [r_ for r_ in recs if r_[0].startswith("conv_wgrad")][0]
+    wg_tf = conv_flops(wg) / (wg[6] * 1e-3) / 1e12
+    return {"layer": "3x3 %d->%d stride 2 on %dx%d, batch %d, fp32" % (c, k, x.shape[2], x.shape[3], batch), "iterations": iters, "lr": lr,
+            "loss_first": round(losses[0], 1), "loss_last": round(losses[-1], 1), "loss_ratio": round(losses[-1] / losses[0], 4),
+            "monotone": all(b_ < a_ for a_, b_ in zip(losses, losses[1:])),
+            "ms_per_step": round(e0.elapsed_time(e1) / 10, 4), "kernels_ms": {r_[0]: round(r_[6], 4) for r_ in recs},
+            "wgrad_tflops": round(wg_tf, 2), "wgrad_frac_of_fp32_mfma_peak": round(wg_tf / MI355X_MFMA_TFLOPS["f32"], 4)}
+
+
 def conv_flops(rec):
     label, k, c, r, s, items = rec[:6]
     return 2.0 * k * c * r * s * items
@@ -411,6 +470,8 @@ def main():
             allc[str(cid)] = w2.summary(reps=10, warmup=3)
             if cid == 2:
                 allc["2"]["paper_variant_ms"] = round(paper_variant_ms(w2), 4)
+            if cid == 1:
+                allc["1"]["slim_layer_regression"] = slim_layer_regression()
             del w2
             torch.cuda.empty_cache()
         out["all_configs"] = allc
