@@ -4,6 +4,7 @@
 //
 //   regression_loss_grad   dz = 2 (f - y) where f > 0 else 0,  L = sum (f - y)^2
 //   conv_wgrad             dw[k][c,r,s] = sum_{n,p,q} dz[n,k,p,q] x[n,c,p*sh+r-ph,q*sw+s-pw],  db[k] = sum dz[n,k,p,q]
+//                          (db is column C*R*S of the same GEMM: the gathered operand is 1 there)
 //   sgd_step               w -= lr * dw
 //
 // The weight gradient is a GEMM  D[m][n] = sum_l A[m][l] B[l][n]  with m = filter, n = (c, r, s) and the
@@ -23,11 +24,11 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int OOB = (int)0x80000000;
 
-// grid of a grid-stride kernel: at most 1024 workgroups (the loss kernel leaves one partial sum per workgroup)
+// grid of a grid-stride kernel: at most 4096 workgroups (the loss kernel leaves one partial sum per workgroup)
 inline unsigned blocks_for_train(size_t count)
 {
     const size_t b = (count + 255) / 256;
-    return (unsigned)(b < 1 ? 1 : (b > 1024 ? 1024 : b));
+    return (unsigned)(b < 1 ? 1 : (b > 4096 ? 4096 : b));
 }
 
 __device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, int voff, int soff)
@@ -49,11 +50,23 @@ __device__ __forceinline__ float block_sum(float v, float* red)
 }
 
 __global__ __launch_bounds__(256) void regression_loss_grad_kernel(const float* __restrict__ f, const float* __restrict__ y,
-                                                                   float* __restrict__ dz, size_t count, float* __restrict__ partial)
+                                                                   float* __restrict__ dz, size_t nvec, size_t count, float* __restrict__ partial)
 {
     __shared__ float red[4];
     float acc = 0.f;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) {
+    // 16-byte vectors where the three pointers allow it (nvec = 0 otherwise), then the scalar tail
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (size_t)gridDim.x * 256) {
+        const f32x4 fv = reinterpret_cast<const f32x4*>(f)[i], yv = reinterpret_cast<const f32x4*>(y)[i];
+        f32x4 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float d = fv[j] - yv[j];
+            acc += d * d;
+            o[j] = fv[j] > 0.f ? 2.f * d : 0.f;
+        }
+        reinterpret_cast<f32x4*>(dz)[i] = o;
+    }
+    for (size_t i = nvec * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) {
         const float fi = f[i], d = fi - y[i];
         acc += d * d;
         dz[i] = fi > 0.f ? 2.f * d : 0.f;
@@ -75,9 +88,11 @@ __global__ void sum_partials_kernel(const float* __restrict__ partial, int n, fl
 struct WArgs {
     const float* x;
     const float* dz;
-    float* out;            // dw itself (splits == 1) or the partial sums [splits][K][CRS]
+    float* out;            // the partial sums [splits][K][CRS + 1] (splits > 1), else unused
+    float* dw;             // splits == 1: the results themselves
+    float* db;             // (may be NULL)
     int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
-    int CRS, grid_m, grid_n, splits, imgs_per_split;
+    int CRS, grid_m, grid_n, splits, imgs_per_split;    // the GEMM has CRS + 1 columns: column CRS is db
     int x_bytes, dz_bytes;
 };
 
@@ -112,7 +127,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_f32_kernel(const WArgs a)
             b_off[i] = c * HW + (r - a.ph) * a.W + (s - a.pw);
             b_r[i] = r - a.ph; b_s[i] = s - a.pw;
         } else {
-            b_off[i] = OOB; b_r[i] = 0; b_s[i] = 0;
+            b_off[i] = OOB; b_r[i] = n == a.CRS ? 1 : 0; b_s[i] = 0;      // b_r = 1: the column of ones (bias gradient)
         }
     }
     const int slices_per_img = (PQ + BL - 1) / BL;
@@ -131,6 +146,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_f32_kernel(const WArgs a)
             ra[i] = buf_load(rz, ao, img * a.K * PQ * 4);
             const bool in = l_on && b_off[i] != OOB && (unsigned)(ih0 + b_r[i]) < (unsigned)a.H && (unsigned)(iw0 + b_s[i]) < (unsigned)a.W;
             rb[i] = buf_load(rx, in ? (b_off[i] + xo) * 4 : OOB, img * a.C * HW * 4);
+            if (b_off[i] == OOB && b_r[i] == 1 && l_on) rb[i] = 1.f;
         }
     };
 
@@ -159,37 +175,32 @@ __global__ __launch_bounds__(256) void conv_wgrad_f32_kernel(const WArgs a)
         for (int j = 0; j < 16; ++j) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[j >> 2][j & 3], bv[j >> 2][j & 3], acc, 0, 0, 0);
     }
     // register v holds row 8 (v / 4) + 4 half + v % 4 of column lane % 32
-    float* out = a.out + (size_t)sp * a.K * a.CRS;
+    const int CRS1 = a.CRS + 1;
+    float* out = a.out + (size_t)sp * a.K * CRS1;
     const int n = n0 + wn * 32 + l32;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int m = m0 + wm * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        if (m < a.K && n < a.CRS) out[(size_t)m * a.CRS + n] = acc[v];
+        if (m >= a.K || n > a.CRS) continue;
+        if (a.splits > 1) out[(size_t)m * CRS1 + n] = acc[v];
+        else if (n < a.CRS) a.dw[(size_t)m * a.CRS + n] = acc[v];
+        else if (a.db) a.db[m] = acc[v];
     }
 }
 
-// dw[i] = sum over the splits, in split order
-__global__ __launch_bounds__(256) void sum_splits_kernel(const float* __restrict__ part, int splits, size_t count, float* __restrict__ dw)
+// element i of the [K][CRS + 1] result = sum over the splits, in split order; column CRS goes to db
+__global__ __launch_bounds__(256) void sum_splits_kernel(const float* __restrict__ part, int splits, int K, int CRS, float* __restrict__ dw,
+                                                         float* __restrict__ db)
 {
+    const size_t count = (size_t)K * (CRS + 1);
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) {
         float s = 0.f;
         for (int sp = 0; sp < splits; ++sp) s += part[(size_t)sp * count + i];
-        dw[i] = s;
+        const size_t m = i / (CRS + 1);
+        const int n = (int)(i - m * (CRS + 1));
+        if (n < CRS) dw[m * CRS + n] = s;
+        else if (db) db[m] = s;
     }
-}
-
-// db[k] = sum_{n,p,q} dz[n][k][p][q]: one workgroup per filter, fixed partition of the terms
-__global__ __launch_bounds__(256) void bias_grad_kernel(const float* __restrict__ dz, int N, int K, int PQ, float* __restrict__ db)
-{
-    __shared__ float red[4];
-    const int k = blockIdx.x;
-    float acc = 0.f;
-    for (int n = 0; n < N; ++n) {
-        const float* src = dz + ((size_t)n * K + k) * PQ;
-        for (int i = threadIdx.x; i < PQ; i += 256) acc += src[i];
-    }
-    const float s = block_sum(acc, red);
-    if (threadIdx.x == 0) db[k] = s;
 }
 
 __global__ __launch_bounds__(256) void sgd_step_kernel(float* __restrict__ w, const float* __restrict__ dw, float lr, size_t count)
@@ -200,7 +211,7 @@ __global__ __launch_bounds__(256) void sgd_step_kernel(float* __restrict__ w, co
 int wgrad_splits(int N, int K, int CRS, int* imgs_per_split)
 {
     if (N < 1) { *imgs_per_split = 1; return 1; }
-    const int tiles = ((K + BM - 1) / BM) * ((CRS + BN - 1) / BN);
+    const int tiles = ((K + BM - 1) / BM) * ((CRS + 1 + BN - 1) / BN);
     int want = (1024 + tiles - 1) / tiles;                  // about four workgroups per compute unit
     if (want > N) want = N;
     if (want < 1) want = 1;
@@ -210,13 +221,15 @@ int wgrad_splits(int N, int K, int CRS, int* imgs_per_split)
 
 }  // namespace
 
-size_t regression_loss_workspace_bytes() { return 1024 * sizeof(float); }
+size_t regression_loss_workspace_bytes() { return 4096 * sizeof(float); }
 
 int launch_regression_loss_grad(const float* f, const float* y, float* dz, size_t count, float* loss, void* ws, hipStream_t st)
 {
     TraceScope trace("loss_grad", nullptr, (long long)count, st, 3ll * count * 4);
-    const unsigned grid = blocks_for_train(count);
-    hipLaunchKernelGGL(regression_loss_grad_kernel, dim3(grid), dim3(256), 0, st, f, y, dz, count, (float*)ws);
+    const bool vec = (((uintptr_t)f | (uintptr_t)y | (uintptr_t)dz) & 15) == 0;
+    const size_t nvec = vec ? count / 4 : 0;
+    const unsigned grid = blocks_for_train(nvec ? nvec : count);
+    hipLaunchKernelGGL(regression_loss_grad_kernel, dim3(grid), dim3(256), 0, st, f, y, dz, nvec, count, (float*)ws);
     hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(64), 0, st, (const float*)ws, (int)grid, loss);
     return check_launch("regression_loss_grad");
 }
@@ -225,7 +238,7 @@ size_t conv_wgrad_workspace_bytes(const ConvGeom& g)
 {
     int ips = 0;
     const int splits = wgrad_splits(g.N, g.K, g.Kg, &ips);
-    return splits > 1 ? (size_t)splits * g.K * g.Kg * sizeof(float) : 0;
+    return splits > 1 ? (size_t)splits * g.K * (g.Kg + 1) * sizeof(float) : 0;
 }
 
 int launch_conv_wgrad_f32(const ConvGeom& g, const float* x, const float* dz, float* dw, float* db, void* ws, hipStream_t st)
@@ -236,25 +249,21 @@ int launch_conv_wgrad_f32(const ConvGeom& g, const float* x, const float* dz, fl
     a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw; a.P = g.P; a.Q = g.Q;
     a.CRS = g.Kg;
     a.grid_m = (g.K + BM - 1) / BM;
-    a.grid_n = (g.Kg + BN - 1) / BN;
+    a.grid_n = (g.Kg + 1 + BN - 1) / BN;
     a.splits = wgrad_splits(g.N, g.K, g.Kg, &a.imgs_per_split);
     a.x_bytes = (int)((size_t)g.N * g.C * g.H * g.W * 4);
     a.dz_bytes = (int)((size_t)g.N * g.K * g.P * g.Q * 4);
-    a.out = a.splits > 1 ? (float*)ws : dw;
+    a.out = (float*)ws; a.dw = dw; a.db = db;
     {
         ConvGeom t = g;
         TraceScope trace("conv_wgrad_f32", &t, g.Ng, st);
         hipLaunchKernelGGL(conv_wgrad_f32_kernel, dim3((unsigned)(a.grid_m * a.grid_n * a.splits)), dim3(256), 0, st, a);
     }
     if (const int rc = check_launch("conv_wgrad")) return rc;
-    const size_t count = (size_t)g.K * g.Kg;
     if (a.splits > 1) {
+        const size_t count = (size_t)g.K * (g.Kg + 1);
         TraceScope trace("wgrad_sum", nullptr, (long long)count, st, (long long)((a.splits + 1) * count * 4));
-        hipLaunchKernelGGL(sum_splits_kernel, dim3(blocks_for_train(count)), dim3(256), 0, st, (const float*)ws, a.splits, count, dw);
-    }
-    if (db) {
-        TraceScope trace("bias_grad", nullptr, (long long)g.K, st, (long long)((size_t)g.Ng * g.K * 4));
-        hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)g.K), dim3(256), 0, st, dz, g.N, g.K, g.P * g.Q, db);
+        hipLaunchKernelGGL(sum_splits_kernel, dim3(blocks_for_train(count)), dim3(256), 0, st, (const float*)ws, a.splits, g.K, g.Kg, dw, db);
     }
     return check_launch("conv_wgrad");
 }
