@@ -75,14 +75,20 @@ __global__ __launch_bounds__(256) void regression_loss_grad_kernel(const float* 
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
 }
 
-// out[0] = sum of partial[0..n) in index order, accumulated in double
-__global__ void sum_partials_kernel(const float* __restrict__ partial, int n, float* __restrict__ out)
+// out[0] = sum of partial[0..n): thread t adds the entries t, t + 256, ... in double, the 256 sums are then added
+// in a fixed tree, so the value does not depend on scheduling
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ partial, int n, float* __restrict__ out)
 {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        double s = 0.0;
-        for (int i = 0; i < n; ++i) s += (double)partial[i];
-        out[0] = (float)s;
+    __shared__ double red[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += 256) s += (double)partial[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int d = 128; d >= 1; d >>= 1) {
+        if ((int)threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+        __syncthreads();
     }
+    if (threadIdx.x == 0) out[0] = (float)red[0];
 }
 
 struct WArgs {
@@ -230,7 +236,7 @@ int launch_regression_loss_grad(const float* f, const float* y, float* dz, size_
     const size_t nvec = vec ? count / 4 : 0;
     const unsigned grid = blocks_for_train(nvec ? nvec : count);
     hipLaunchKernelGGL(regression_loss_grad_kernel, dim3(grid), dim3(256), 0, st, f, y, dz, nvec, count, (float*)ws);
-    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(64), 0, st, (const float*)ws, (int)grid, loss);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, st, (const float*)ws, (int)grid, loss);
     return check_launch("regression_loss_grad");
 }
 
