@@ -118,3 +118,30 @@ def test_slim_layer_regression_follows_the_oracle():
     np.testing.assert_allclose(got, ref_losses, rtol=2e-4)
     assert all(b_ < a_ for a_, b_ in zip(got, got[1:]))
     assert rel_err(host(wg), w_ref) < 10 * TOL_F32
+
+
+def test_degenerate_inputs():
+    """No images / no pixels: the gradients are zero (and the kernels dereference nothing); an empty tensor has zero
+    loss; unsupported layouts are refused before anything is launched."""
+    cd = B.conv_desc(5, 3, 3, 3, 1, 1, True, B.DR_KCRS)
+    x = torch.empty((0, 3, 8, 8), device="cuda")
+    dz = torch.empty((0, 5, 8, 8), device="cuda")
+    dw = torch.full((5, 3, 3, 3), float("nan"), device="cuda")
+    db = torch.full((5,), float("nan"), device="cuda")
+    B.conv2d_bwd_params(x, cd, dz, dw, db, _ws(B.conv2d_bwd_params_workspace_bytes(x, cd)))
+    torch.cuda.synchronize()
+    assert not host(dw).any() and not host(db).any()
+    f = torch.empty((0, 4, 2, 2), device="cuda")
+    loss = torch.full((1,), 7.0, device="cuda")
+    B.regression_loss_grad(f, f, f, loss, _ws(B.regression_loss_workspace_bytes()))
+    torch.cuda.synchronize()
+    assert float(loss.item()) == 0.0
+    xb = torch.zeros((1, 8, 4, 4), device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(B.DeepRebirthError):
+        B.conv2d_bwd_params_workspace_bytes(xb, B.conv_desc(4, 8, 1, 1, 1, 0, True, B.DR_KCRS))
+    x1 = torch.zeros((1, 16, 4, 4), device="cuda")
+    with pytest.raises(B.DeepRebirthError):                      # KRSC filters
+        B.conv2d_bwd_params_workspace_bytes(x1, B.conv_desc(4, 16, 1, 1, 1, 0, True, B.DR_KRSC))
+    with pytest.raises(B.DeepRebirthError):                      # dz of the wrong shape
+        B.conv2d_bwd_params(x1, B.conv_desc(4, 16, 1, 1, 1, 0, True, B.DR_KCRS), torch.zeros((1, 4, 3, 3), device="cuda"),
+                            torch.zeros((4, 16, 1, 1), device="cuda"), None, _ws(256))
