@@ -305,7 +305,7 @@ def main():
     ap.add_argument("--only", action="store_true", help="skip the summary of the other configurations")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; the path shards by batch with no communication, "
+        print("bench.py: the library runs on ONE GPU; the path shards by batch with no communication, "
               "so --gpus %d is not measured here" % args.gpus, file=sys.stderr)
         sys.exit(2)
 

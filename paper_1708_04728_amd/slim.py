@@ -43,7 +43,7 @@ def _last_conv(branch):
 
 
 def branch_slim(inception):
-    """Branch slimming (Sec. 3.2) as BASELINE's variant: the non-tensor (pool) branch and the
+    """Branch slimming (Sec. 3.2) in the form the benchmark configurations use: the non-tensor (pool) branch and the
     single-1x1 tensor branch are removed, and the branch with the largest filter (which must be at
     least as large as the pooling window) emits their feature maps as well, so the concatenated
     width is unchanged."""
