@@ -397,6 +397,7 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
         fork = bs->event();
         if (hipEventRecord(fork, main_st) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipEventRecord failed", who);
     }
+    SharedDeviceScope shared(bs != nullptr);
     for (int b = 0; b < d.n_branches; ++b) {
         const dr_branch& br = d.branches[b];
         dr_tensor t = xd;

@@ -531,6 +531,8 @@ int launch_cfg(DArgs a, hipStream_t st)
 // them, the cost of a tile grows with its filter count (measured: about 0.44 + filters / 32) and the
 // number of rounds is tiles / resident workgroups, rounded up while it is small (a persistent workgroup
 // walks a whole number of tiles).
+thread_local int t_shared_device = 0;
+
 inline float tile_rounds(int K, int Ng, int bm, int bn)
 {
     const float r = (float)((K + bm - 1) / bm) * (float)((Ng + bn - 1) / bn) / (float)(device_cus() * 2);
@@ -539,6 +541,12 @@ inline float tile_rounds(int K, int Ng, int bm, int bn)
 int launch_auto(DArgs a, hipStream_t st)
 {
     const int K = a.g.K, Ng = a.g.Ng;
+    // a layer whose 64 x 64 tiles all fit the device at two workgroups per compute unit: twice the
+    // workgroups of the 128-pixel tiles and a ring of four stages, for layers that would leave compute
+    // units idle (the 7 x 7 maps, the narrow reducers of the 14 x 14 maps); also taken for K <= 32,
+    // where padding the filter block to 64 costs less than one more kernel variant between the others
+    // (not while other streams of the same caller keep the device busy: measured slower there)
+    if (!t_shared_device && ((K + 63) / 64) * ((Ng + 63) / 64) <= 2 * device_cus()) return launch_cfg<1, 1, 2, 2, 4, 2>(a, st);   // 64 x 64 tiles
     if (K <= 32) {
         // fewer 256-pixel tiles than compute units: halve the tiles
         if ((Ng + 255) / 256 < device_cus()) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);   // 32 x 128 tiles
@@ -554,6 +562,9 @@ int launch_auto(DArgs a, hipStream_t st)
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace
+
+SharedDeviceScope::SharedDeviceScope(bool on) : on_(on) { if (on_) ++t_shared_device; }
+SharedDeviceScope::~SharedDeviceScope() { if (on_) --t_shared_device; }
 
 bool conv_bf16_dma_eligible(const ConvGeom& g, const void* x, const void* w)
 {

@@ -66,6 +66,15 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
 bool conv_bf16_stem_eligible(const ConvGeom& g);
 int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias,
                           uint16_t* y, hipStream_t st);
+// While one of these lives on a host thread, convolutions launched by that thread share the device with
+// kernels on other streams (branches of a module side by side): the launcher then keeps its larger
+// tiles instead of cutting a small layer into enough workgroups to fill the device by itself.
+struct SharedDeviceScope {
+    explicit SharedDeviceScope(bool on);
+    ~SharedDeviceScope();
+    bool on_;
+};
+
 
 // train.hip: regression of a slim layer (fp32, NCHW, KCRS)
 size_t regression_loss_workspace_bytes();

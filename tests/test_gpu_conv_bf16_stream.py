@@ -40,7 +40,7 @@ def _run(case, relu=False, bias=True, seed=0):
 # N, C, H, W, K, R, S, stride, pad
 CASES = [
     # --- slices inside one tap (C % 64 == 0)
-    (1, 64, 12, 12, 24, 1, 1, 1, 0),        # K <= 32 and few pixels: 32 x 128 tiles, one slice per tile
+    (1, 64, 12, 12, 24, 1, 1, 1, 0),        # few tiles: 64 x 64 tiles (as for most small cases below), one slice per tile
     (2, 64, 30, 30, 64, 3, 3, 1, 1),        # one round of 64 x 128 tiles, 9 slices
     (1, 128, 40, 40, 72, 3, 3, 1, 1),       # ragged filter block
     (1, 64, 190, 190, 136, 1, 1, 1, 0),     # many pixels: several channel blocks, ragged last pixel tile, grid not a multiple of 8
@@ -71,6 +71,8 @@ CASES = [
     (2, 16, 160, 160, 96, 3, 3, 1, 1),      # 96 filters, 51 200 pixels: one round of 96 x 128 tiles instead of two of 64 x 128
     (2, 64, 160, 160, 96, 1, 1, 1, 0),      # the same with slices inside one tap
     (1, 32, 96, 96, 288, 5, 5, 1, 2),       # 288 filters, slices running over filter rows
+    (1, 64, 200, 200, 24, 1, 1, 1, 0),      # K <= 32 and 40 000 pixels: 32 x 128 tiles
+    (1, 16, 200, 200, 24, 3, 3, 1, 1),      # the same with slices running over filter rows
 ]
 
 
