@@ -89,6 +89,19 @@ int dr_pool_out_size(int in, int win, int stride, int pad);
 int dr_conv2d_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
                   const dr_tensor* yd, void* y, int y_c_offset, void* stream);
 
+/* The same convolution with scratch memory from the caller.  A layer with fewer output tiles than the
+ * device has compute units (one image, or a few: the setting of the paper's own measurements, Sec. 4)
+ * would leave most of them idle; with scratch the contraction over (c, r, s) is cut into ranges that
+ * run side by side, and a second kernel adds the ranges in a fixed order and applies bias and ReLU
+ * (no atomics: results are the same from run to run).  dr_conv2d_workspace_bytes gives the size for
+ * (xd, cd): 0 when the layer would not be cut (then ws may be NULL); cd with the stride of a slim
+ * layer gives the slim layer's size.  ws: device memory, 256-byte aligned, of at least that size
+ * (else DR_ERR_WORKSPACE), used only until the call's work on `stream` has finished.  fp32 NCHW layers
+ * are cut; every other layer runs exactly as in dr_conv2d_fwd. */
+int dr_conv2d_workspace_bytes(const dr_tensor* xd, const dr_conv* cd, size_t* bytes);
+int dr_conv2d_fwd_ws(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
+                     const dr_tensor* yd, void* y, int y_c_offset, void* ws, size_t ws_bytes, void* stream);
+
 /* Reorders a filter tensor from KCRS to KRSC on the device: w_krsc[j][r][s][c] = w_kcrs[j][c][r][s]
  * (cd->k, c, r, s give the shape; dtype DR_F32 or DR_BF16; the two buffers must not overlap).
  * Returns DR_ERR_UNSUPPORTED when cd->c is not a multiple of 16 (fp32) or 8 (bf16): such filters

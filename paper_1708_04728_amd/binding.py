@@ -85,6 +85,8 @@ _SIGNATURES = {
     "dr_conv_out_size": ([_i, _i, _i, _i], _i),
     "dr_pool_out_size": ([_i, _i, _i, _i], _i),
     "dr_conv2d_fwd": ([_P(dr_tensor), _vp, _P(dr_conv), _vp, _vp, _P(dr_tensor), _vp, _i, _vp], _i),
+    "dr_conv2d_workspace_bytes": ([_P(dr_tensor), _P(dr_conv), _P(_z)], _i),
+    "dr_conv2d_fwd_ws": ([_P(dr_tensor), _vp, _P(dr_conv), _vp, _vp, _P(dr_tensor), _vp, _i, _vp, _z, _vp], _i),
     "dr_pack_filters": ([_P(dr_conv), _i, _vp, _vp, _vp], _i),
     "dr_slim_conv_fwd": ([_P(dr_tensor), _vp, _P(dr_conv), _i, _i, _vp, _vp, _P(dr_tensor), _vp, _i, _vp], _i),
     "dr_relu": ([_P(dr_tensor), _vp, _vp, _vp], _i),
@@ -216,6 +218,20 @@ def pool_out_size(n, win, stride, pad):
 def conv2d_fwd(x, cd, w, bias, y, y_c_offset=0, stream=None):
     xd, yd = desc(x), desc(y)
     _check(lib().dr_conv2d_fwd(xd, _ptr(x), cd, _ptr(w), _ptr(bias), yd, _ptr(y), y_c_offset, _stream(stream)))
+    return y
+
+
+def conv2d_workspace_bytes(x, cd):
+    n = C.c_size_t(0)
+    _check(lib().dr_conv2d_workspace_bytes(desc(x), cd, C.byref(n)))
+    return n.value
+
+
+def conv2d_fwd_ws(x, cd, w, bias, y, ws, y_c_offset=0, stream=None):
+    """ws: a device tensor of at least conv2d_workspace_bytes(x, cd) bytes, or None when that is 0."""
+    xd, yd = desc(x), desc(y)
+    nbytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().dr_conv2d_fwd_ws(xd, _ptr(x), cd, _ptr(w), _ptr(bias), yd, _ptr(y), y_c_offset, _ptr(ws), nbytes, _stream(stream)))
     return y
 
 

@@ -24,6 +24,17 @@ int fail(int code, const char* fmt, ...)
     return code;
 }
 
+int device_cus()
+{
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+        else cus = 256;
+    }
+    return cus;
+}
+
 int check_launch(const char* what)
 {
     const hipError_t e = hipGetLastError();
@@ -126,8 +137,38 @@ bool same_shape(const dr_tensor& a, const dr_tensor& b)
 }
 
 // Validated convolution launch (shared by the single-layer entry points and the composite ones).
+// Geometry of layer cd on input xd with output descriptor o (the output tensor's fields are set by the caller).
+ConvGeom conv_geom(const dr_tensor& xd, const dr_conv& cd, const dr_tensor& o)
+{
+    ConvGeom g;
+    g.N = xd.n; g.C = xd.c; g.H = xd.h; g.W = xd.w;
+    g.K = cd.k; g.R = cd.r; g.S = cd.s;
+    g.sh = cd.stride_h; g.sw = cd.stride_w; g.ph = cd.pad_h; g.pw = cd.pad_w;
+    g.P = o.h; g.Q = o.w;
+    g.Kg = cd.c * cd.r * cd.s;
+    g.Ng = o.n * o.h * o.w;
+    g.y_ctot = o.c; g.y_coff = 0;
+    g.relu = cd.relu != 0;
+    g.res_ctot = 0;
+    g.w_krsc = cd.filter_layout == DR_KRSC;
+    g.nhwc = xd.layout == DR_NHWC;
+    g.c_logical = 0;
+    return g;
+}
+
+// Scratch a convolution uses when its caller has some to give (fp32: the partial sums of a contraction
+// cut over several workgroups, for layers with too few output tiles to occupy the device); 0 = none.
+size_t conv_scratch_bytes(const dr_tensor& xd, const dr_conv& cd)
+{
+    if (xd.dtype != DR_F32 || xd.layout != DR_NCHW) return 0;
+    const dr_tensor o = conv_out(xd, cd);
+    if ((double)cd.c * cd.r * cd.s >= 2147483648.0 || (double)o.n * o.h * o.w >= 2147483648.0 || tensor_elems(o) == 0) return 0;
+    return conv_f32_scratch_bytes(conv_geom(xd, cd, o));
+}
+
 int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias,
-             const void* residual, int res_ctot, const dr_tensor& yd, void* y, int y_c_offset, hipStream_t st, int c_logical = 0)
+             const void* residual, int res_ctot, const dr_tensor& yd, void* y, int y_c_offset, hipStream_t st, int c_logical = 0,
+             void* scratch = nullptr, size_t scratch_bytes = 0)
 {
     if (xd.c != cd.c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd.c, cd.c);
     const dr_tensor o = conv_out(xd, cd);
@@ -143,21 +184,12 @@ int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv&
         return fail(DR_ERR_UNSUPPORTED, "%s: problem too large", who);
     if ((size_t)o.n * cd.k * o.h * o.w == 0) return DR_OK;   // nothing to compute: pointers may be NULL
     if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
-    ConvGeom g;
-    g.N = xd.n; g.C = xd.c; g.H = xd.h; g.W = xd.w;
-    g.K = cd.k; g.R = cd.r; g.S = cd.s;
-    g.sh = cd.stride_h; g.sw = cd.stride_w; g.ph = cd.pad_h; g.pw = cd.pad_w;
-    g.P = o.h; g.Q = o.w;
-    g.Kg = cd.c * cd.r * cd.s;
-    g.Ng = o.n * o.h * o.w;
+    ConvGeom g = conv_geom(xd, cd, o);
     g.y_ctot = yd.c; g.y_coff = y_c_offset;
-    g.relu = cd.relu != 0;
     g.res_ctot = residual ? res_ctot : 0;
-    g.w_krsc = cd.filter_layout == DR_KRSC;
-    g.nhwc = xd.layout == DR_NHWC;
     g.c_logical = c_logical;
     if (xd.dtype == DR_F32)
-        return launch_conv_f32(g, (const float*)x, (const float*)w, bias, (const float*)residual, (float*)y, st);
+        return launch_conv_f32(g, (const float*)x, (const float*)w, bias, (const float*)residual, (float*)y, st, scratch, scratch_bytes);
     return launch_conv_bf16(g, (const uint16_t*)x, (const uint16_t*)w, bias, (const uint16_t*)residual, (uint16_t*)y, st);
 }
 
@@ -419,9 +451,11 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
                 if (direct) cd.relu = relu_after;
                 void* dst = direct ? y : (s == 0 && stacked[b]) ? stacked_dst[b] : ar.take(tensor_bytes(o));
                 if (!dst && !ar.measure) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
+                const size_t sbytes = conv_scratch_bytes(t, cd);
+                void* sc = sbytes ? ar.take(sbytes) : nullptr;
                 if (!ar.measure && !(s == 0 && stacked[b])) {
                     if (!w) return fail(DR_ERR_NULL, "%s: missing weights of branch %d step %d", who, b, s);
-                    DR_TRY(conv_run(who, t, cur, cd, w, bias, nullptr, 0, direct ? yd : o, dst, direct ? c_off : 0, st));
+                    DR_TRY(conv_run(who, t, cur, cd, w, bias, nullptr, 0, direct ? yd : o, dst, direct ? c_off : 0, st, 0, sc, sc ? sbytes : 0));
                     if (relu_after && !cd.relu) DR_TRY(launch_relu(o.dtype, dst, dst, tensor_elems(o), st));
                 }
                 if (last && !direct) segs[nseg++] = ConcatSeg{dst, o.c, c_off};
@@ -597,6 +631,8 @@ int net_plan(const dr_net& net, const dr_tensor& xd, NetPlan* plan)
         Arena ar(nullptr, 0, true);
         if (L.kind == DR_LAYER_CONV && conv_wants_padding(t, L.conv)) {
             DR_TRY(padded_conv_run("dr_net", t, nullptr, L.conv, nullptr, nullptr, o, nullptr, ar, nullptr));
+        } else if (L.kind == DR_LAYER_CONV) {
+            ar.take(conv_scratch_bytes(t, L.conv));
         } else if (L.kind == DR_LAYER_INCEPTION) {
             ParamCursor w{nullptr, 0}, b{nullptr, 0};
             DR_TRY(inception_run(t, nullptr, L.inception, w, b, o, nullptr, ar, nullptr));
@@ -695,6 +731,31 @@ int dr_conv2d_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const v
     DR_TRY(check_tensor(who, "yd", yd));
     DR_TRY(check_conv_desc(who, cd));
     return conv_run(who, *xd, x, *cd, w, bias, nullptr, 0, *yd, y, y_c_offset, (hipStream_t)stream);
+}
+
+int dr_conv2d_workspace_bytes(const dr_tensor* xd, const dr_conv* cd, size_t* bytes)
+{
+    const char* who = "dr_conv2d_workspace_bytes";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_conv_desc(who, cd));
+    if (!bytes) return fail(DR_ERR_NULL, "%s: bytes is NULL", who);
+    if (xd->c != cd->c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd->c, cd->c);
+    *bytes = conv_scratch_bytes(*xd, *cd);
+    return DR_OK;
+}
+
+int dr_conv2d_fwd_ws(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
+                     const dr_tensor* yd, void* y, int y_c_offset, void* ws, size_t ws_bytes, void* stream)
+{
+    const char* who = "dr_conv2d_fwd_ws";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    DR_TRY(check_conv_desc(who, cd));
+    if (xd->c != cd->c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd->c, cd->c);
+    const size_t need = conv_scratch_bytes(*xd, *cd);
+    if (need && (!ws || ws_bytes < need)) return fail(DR_ERR_WORKSPACE, "%s: needs %zu bytes of workspace, got %zu", who, need, ws ? ws_bytes : (size_t)0);
+    if (need && ((uintptr_t)ws & 255) != 0) return fail(DR_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned", who);
+    return conv_run(who, *xd, x, *cd, w, bias, nullptr, 0, *yd, y, y_c_offset, (hipStream_t)stream, 0, need ? ws : nullptr, need);
 }
 
 int dr_pack_filters(const dr_conv* cd, int dtype, const void* w_kcrs, void* w_krsc, void* stream)
@@ -1114,8 +1175,11 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
         case DR_LAYER_CONV:
             if (conv_wants_padding(t, L.conv))
                 DR_TRY(padded_conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], od, dst, ar, st));
-            else
-                DR_TRY(conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], nullptr, 0, od, dst, 0, st));
+            else {
+                const size_t sbytes = conv_scratch_bytes(t, L.conv);
+                void* sc = sbytes ? ar.take(sbytes) : nullptr;
+                DR_TRY(conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], nullptr, 0, od, dst, 0, st, 0, sc, sc ? sbytes : 0));
+            }
             break;
         case DR_LAYER_RELU: DR_TRY(launch_relu(t.dtype, cur, dst, tensor_elems(t), st)); break;
         case DR_LAYER_LRN: DR_TRY(launch_lrn(t, cur, dst, L.lrn, st)); break;

@@ -489,17 +489,6 @@ void conv_bf16_dma_kernel(const DArgs a)
     wait_lgkm<0>();
 }
 
-int device_cus()
-{
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-        else cus = 256;
-    }
-    return cus;
-}
-
 template <int TM, int TN, int WGM, int WGN, int NS, int OCC>
 int launch_cfg(DArgs a, hipStream_t st)
 {

@@ -26,6 +26,14 @@
 //        per slice, and the filter rows are read with 16-byte loads.
 //   CF = false (filters in KCRS order, any shape): k runs in KCRS order and every gathered element
 //        decodes (c, r, s).
+//
+// A layer with fewer tiles than the device has compute units (one image, or a few) leaves most of the
+// matrix cores idle while each workgroup walks the whole contraction alone.  Given scratch memory, the
+// launcher then cuts the contraction into `splits` ranges of slices: blockIdx.y picks the range, the
+// workgroup stores its raw partial sums to part[split][m][n], and conv_f32_reduce_kernel adds the
+// ranges in a fixed order and applies bias, residual and ReLU.  No atomics: the result does not
+// depend on the order in which workgroups finish.
+#include <algorithm>
 #include <type_traits>
 
 #include "dr_internal.h"
@@ -48,6 +56,8 @@ struct KArgs {
     int grid_m, grid_n;
     int x_bytes, w_bytes;   // sizes of the x and w tensors (both < 2 GiB, checked by the launcher)
     int w_krsc;             // filters are in KRSC order (else KCRS)
+    float* part;            // partial sums [splits][K][Ng] of a split contraction, or NULL
+    int splits, slices_per_split;
 };
 
 template <int V> using IC = std::integral_constant<int, V>;
@@ -69,8 +79,9 @@ __device__ __forceinline__ float buf_load(__amdgpu_buffer_rsrc_t r, int voff, in
 
 // BM x BN: workgroup tile; WGM x WGN: wave grid (4 waves); BK: k per LDS slice; PF: prefetch distance
 // in slices; CF: slice order (see above); FR, FS: compile-time filter size for CF = false (0 = taken
-// from the geometry at run time).
-template <int BM, int BN, int WGM, int WGN, int BK, int PF, bool CF, int FR, int FS>
+// from the geometry at run time); SPLIT: the workgroup takes range blockIdx.y of the contraction and
+// stores raw partial sums.
+template <int BM, int BN, int WGM, int WGN, int BK, int PF, bool CF, int FR, int FS, bool SPLIT>
 __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
 {
     constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
@@ -161,6 +172,20 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
             for (int j = 0; j < 4; ++j) vb[CF ? i : 0][j] = base + ((bkq0 + i * BKQ_STEP) * 4 + j) * HW * 4;
     };
 
+    // this workgroup's range of slices: [s_begin, s_begin + nslices)
+    const int nslices_all = CF ? RS * (g.C / BK) : (g.Kg + BK - 1) / BK;
+    const int s_begin = SPLIT ? (int)blockIdx.y * a.slices_per_split : 0;
+    const int nslices = SPLIT ? min(a.slices_per_split, nslices_all - s_begin) : nslices_all;
+    if constexpr (CF && SPLIT) {
+        if (s_begin) {
+            const int per_tap = g.C / BK, tap = s_begin / per_tap;
+            ld_c0 = (s_begin - tap * per_tap) * BK;
+            ld_r = tap / S;
+            ld_s = tap - ld_r * S;
+            if (ld_c0) tap_offsets();   // load_slice computes them itself at the first slice of a tap
+        }
+    }
+
     auto load_slice = [&](int it, auto set_c) {
         constexpr int SET = decltype(set_c)::value;
         if constexpr (CF) {
@@ -180,7 +205,7 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
             ld_c0 += BK;
             if (ld_c0 == g.C) { ld_c0 = 0; if (++ld_s == S) { ld_s = 0; ++ld_r; } }
         } else {
-            const int k0 = it * BK;
+            const int k0 = (s_begin + it) * BK;
 #pragma unroll
             for (int i = 0; i < A_PER; ++i) {
                 const int gk = k0 + ((tid + i * NT) % KQ) * 4;
@@ -234,8 +259,6 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nslices = CF ? RS * (g.C / BK) : (g.Kg + BK - 1) / BK;
-
     // One slice: MFMAs on LDS buffer it&1; then register set SET (slice it+1, loaded PF slices ago)
     // moves to the other LDS buffer and is refilled with slice it+1+PF.
     auto slice_step = [&](int it, auto set_c) {
@@ -287,6 +310,17 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
         const int img = n / PQ, pix = n - img * PQ;
         float* yb = a.y + ((size_t)img * g.y_ctot + g.y_coff) * PQ + pix;
         const float* rbase = a.res ? a.res + (size_t)img * g.res_ctot * PQ + pix : nullptr;
+        if constexpr (SPLIT) {
+            float* pb = a.part + (size_t)blockIdx.y * g.K * g.Ng + n;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * WM + i * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                    if (m < g.K) pb[(size_t)m * g.Ng] = acc[i][j][v];
+                }
+            continue;
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -302,15 +336,78 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
     }
 }
 
+// y = bias + residual + sum over the ranges of a split contraction, ReLU: one thread per output element,
+// consecutive threads along n (these layers are small: what counts is the number of loads in flight).
+__global__ __launch_bounds__(256) void conv_f32_reduce_kernel(const float* __restrict__ part, int splits, ConvGeom g,
+                                                              const float* __restrict__ bias, const float* __restrict__ res,
+                                                              float* __restrict__ y)
+{
+    const size_t total = (size_t)g.K * g.Ng;
+    const int PQ = g.P * g.Q;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int m = (int)(i / g.Ng), n = (int)(i - (size_t)m * g.Ng);
+        float sum = 0.f;
+#pragma unroll 4
+        for (int s = 0; s < splits; ++s) sum += part[s * total + i];   // unrolled: four loads in flight, the order of the sum unchanged
+        const int img = n / PQ, pix = n - img * PQ;
+        float o = sum + (bias ? bias[m] : 0.f);
+        if (res) o += res[((size_t)img * g.res_ctot + m) * PQ + pix];
+        if (g.relu) o = fmaxf(o, 0.f);
+        y[((size_t)img * g.y_ctot + g.y_coff + m) * PQ + pix] = o;
+    }
+}
+
+// How a layer's contraction is cut when scratch memory is there: enough ranges to give the device about two
+// workgroups per compute unit, each at least two slices long; 1 = not cut (the layer's tiles reach half
+// of the compute units, or it is too shallow).
+inline int split_plan(int tiles, int nslices, int* slices_per_split)
+{
+    const int cus = device_cus();
+    *slices_per_split = nslices;
+    if (2 * tiles > cus || nslices < 4) return 1;   // measured: no gain once half the compute units have a tile
+    const int want = (2 * cus + tiles - 1) / tiles;
+    int per = (nslices + want - 1) / want;
+    if (per < 2) per = 2;
+    *slices_per_split = per;
+    return (nslices + per - 1) / per;
+}
+
+template <int BM, int BN, int BK>
+size_t split_bytes(const ConvGeom& g)
+{
+    const bool cf = g.w_krsc;
+    const int nslices = cf ? g.R * g.S * (g.C / BK) : (g.Kg + BK - 1) / BK;
+    int per;
+    const int splits = split_plan(((g.K + BM - 1) / BM) * ((g.Ng + BN - 1) / BN), nslices, &per);
+    return splits > 1 ? (size_t)splits * g.K * g.Ng * sizeof(float) : 0;
+}
+
 template <int BM, int BN, int WGM, int WGN, int BK, int PF>
-int launch_tile(const KArgs& base, hipStream_t st)
+int launch_tile(const KArgs& base, void* ws, size_t ws_bytes, hipStream_t st)
 {
     KArgs a = base;
     a.grid_m = (a.g.K + BM - 1) / BM;
     a.grid_n = (a.g.Ng + BN - 1) / BN;
-    const dim3 grid((unsigned)(a.grid_m * a.grid_n)), block(NT);
+    a.part = nullptr;
+    a.splits = 1;
+    const int nslices = a.w_krsc ? a.g.R * a.g.S * (a.g.C / BK) : (a.g.Kg + BK - 1) / BK;
+    a.slices_per_split = nslices;
+    if (ws) {
+        int per;
+        const int splits = split_plan(a.grid_m * a.grid_n, nslices, &per);
+        if (splits > 1 && (size_t)splits * a.g.K * a.g.Ng * sizeof(float) <= ws_bytes && ((uintptr_t)ws & 15) == 0) {
+            a.part = (float*)ws;
+            a.splits = splits;
+            a.slices_per_split = per;
+        }
+    }
+    const dim3 grid((unsigned)(a.grid_m * a.grid_n), (unsigned)a.splits), block(NT);
     const int R = a.g.R, S = a.g.S;
-#define DR_LAUNCH(CF, FR, FS) hipLaunchKernelGGL((conv_f32_kernel<BM, BN, WGM, WGN, BK, PF, CF, FR, FS>), grid, block, 0, st, a)
+#define DR_LAUNCH(CF, FR, FS)                                                                                              \
+    do {                                                                                                                   \
+        if (a.part) hipLaunchKernelGGL((conv_f32_kernel<BM, BN, WGM, WGN, BK, PF, CF, FR, FS, true>), grid, block, 0, st, a);   \
+        else hipLaunchKernelGGL((conv_f32_kernel<BM, BN, WGM, WGN, BK, PF, CF, FR, FS, false>), grid, block, 0, st, a);         \
+    } while (0)
     if (a.w_krsc) DR_LAUNCH(true, 0, 0);
     else if (R == 1 && S == 1) DR_LAUNCH(false, 1, 1);
     else if (R == 3 && S == 3) DR_LAUNCH(false, 3, 3);
@@ -319,13 +416,29 @@ int launch_tile(const KArgs& base, hipStream_t st)
     else if (R == 11 && S == 11) DR_LAUNCH(false, 11, 11);
     else DR_LAUNCH(false, 0, 0);
 #undef DR_LAUNCH
-    return check_launch("conv_f32");
+    const int rc = check_launch("conv_f32");
+    if (rc != DR_OK) return rc;
+    if (a.part) {
+        const ConvGeom& g = a.g;
+        const size_t threads = (size_t)g.K * g.Ng;
+        const unsigned blocks = (unsigned)std::min<size_t>((threads + 255) / 256, (size_t)device_cus() * 8);
+        hipLaunchKernelGGL(conv_f32_reduce_kernel, dim3(blocks), dim3(256), 0, st, a.part, a.splits, g, a.bias, a.res, a.y);
+        return check_launch("conv_f32 (sum of the split contraction)");
+    }
+    return DR_OK;
 }
 
 }  // namespace
 
+size_t conv_f32_scratch_bytes(const ConvGeom& g)
+{
+    const bool rows32 = (g.K + 31) / 32 * 32 < (g.K + 63) / 64 * 64;
+    if (g.w_krsc && g.C % 32 == 0) return rows32 ? split_bytes<32, 128, 32>(g) : split_bytes<64, 64, 32>(g);
+    return rows32 ? split_bytes<32, 128, 16>(g) : split_bytes<64, 64, 16>(g);
+}
+
 int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const float* bias, const float* residual,
-                    float* y, hipStream_t st)
+                    float* y, hipStream_t st, void* ws, size_t ws_bytes)
 {
     TraceScope trace("conv_f32", &g, g.Ng, st);
     KArgs a;
@@ -342,8 +455,8 @@ int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const flo
     // deepest slice the channel count allows, two slices of prefetch.
     const bool rows32 = (g.K + 31) / 32 * 32 < (g.K + 63) / 64 * 64;
     if (g.w_krsc && g.C % 32 == 0)
-        return rows32 ? launch_tile<32, 128, 1, 4, 32, 2>(a, st) : launch_tile<64, 64, 2, 2, 32, 2>(a, st);
-    return rows32 ? launch_tile<32, 128, 1, 4, 16, 2>(a, st) : launch_tile<64, 64, 2, 2, 16, 2>(a, st);
+        return rows32 ? launch_tile<32, 128, 1, 4, 32, 2>(a, ws, ws_bytes, st) : launch_tile<64, 64, 2, 2, 32, 2>(a, ws, ws_bytes, st);
+    return rows32 ? launch_tile<32, 128, 1, 4, 16, 2>(a, ws, ws_bytes, st) : launch_tile<64, 64, 2, 2, 16, 2>(a, ws, ws_bytes, st);
 }
 
 }  // namespace dr

@@ -12,6 +12,8 @@ namespace dr {
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 // Checks the launch status of the kernels just enqueued.
 int check_launch(const char* what);
+// compute units of the current device (256 when the query fails)
+int device_cus();
 
 inline size_t elem_size(int dtype) { return dtype == DR_BF16 ? 2 : 4; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -46,8 +48,11 @@ struct ConvGeom {
 
 // conv_f32.hip / conv_bf16.hip: y = conv(x, w) + bias [+ residual] [ReLU].
 // `residual` (may be NULL) has the output's n, P, Q and res_ctot channels, read at channel j.
+// ws (may be NULL): scratch of conv_f32_scratch_bytes(g) bytes, 16-byte aligned, which lets a layer with few
+// output tiles cut its contraction over several workgroups (see conv_f32.hip); too small = not used.
+size_t conv_f32_scratch_bytes(const ConvGeom& g);
 int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const float* bias, const float* residual,
-                    float* y, hipStream_t st);
+                    float* y, hipStream_t st, void* ws = nullptr, size_t ws_bytes = 0);
 int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
                      const uint16_t* residual, uint16_t* y, hipStream_t st);
 

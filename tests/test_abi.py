@@ -80,11 +80,27 @@ def test_inception_and_net_planning_on_host():
     n = C.c_size_t(0)
     xd = _t(32, 192, 28, 28)
     assert B.lib().dr_inception_workspace_bytes(xd, d, C.byref(n)) == B.DR_OK
-    # layer-by-layer form keeps every branch tensor: 64+96+128+16+32+192+32 channels of 32x28x28 fp32
-    assert n.value == (64 + 96 + 128 + 16 + 32 + 192 + 32) * 32 * 784 * 4
+    # layer-by-layer form keeps every branch tensor: 64+96+128+16+32+192+32 channels of 32x28x28 fp32; on top of
+    # that, the scratch of those convolutions that would leave compute units idle (each rounded up to 256 bytes)
+    def scratch(c_in, k, r):
+        m = C.c_size_t(0)
+        assert B.lib().dr_conv2d_workspace_bytes(_t(32, c_in, 28, 28), B.conv_desc(k, c_in, r, pad=r // 2), C.byref(m)) == B.DR_OK
+        return (m.value + 255) // 256 * 256
+    convs = [(192, 64, 1), (192, 96, 1), (96, 128, 3), (192, 16, 1), (16, 32, 5), (192, 32, 1)]
+    assert scratch(96, 128, 3) == 0
+    assert n.value == (64 + 96 + 128 + 16 + 32 + 192 + 32) * 32 * 784 * 4 + sum(scratch(*c) for c in convs)
     d2 = G.inception_desc(layers[0][1], 192, B.DR_FUSE_RELU | B.DR_FUSE_CONCAT)
     assert B.lib().dr_inception_workspace_bytes(xd, d2, C.byref(n)) == B.DR_OK
-    assert n.value == (96 + 16 + 192) * 32 * 784 * 4
+    assert n.value == (96 + 16 + 192) * 32 * 784 * 4 + sum(scratch(*c) for c in convs)
+    # the query itself: whole [K][pixels] planes of partial sums for a one-image layer, nothing for bf16 or big layers
+    m = C.c_size_t(0)
+    assert B.lib().dr_conv2d_workspace_bytes(_t(1, 64, 56, 56), B.conv_desc(192, 64, 3, stride=2, pad=1), C.byref(m)) == B.DR_OK
+    assert m.value > 0 and m.value % (192 * 784 * 4) == 0
+    assert B.lib().dr_conv2d_workspace_bytes(_t(128, 64, 56, 56), B.conv_desc(192, 64, 3, pad=1), C.byref(m)) == B.DR_OK and m.value == 0
+    assert B.lib().dr_conv2d_workspace_bytes(_t(1, 64, 56, 56, B.DR_BF16), B.conv_desc(192, 64, 3, pad=1), C.byref(m)) == B.DR_OK and m.value == 0
+    assert B.lib().dr_conv2d_workspace_bytes(_t(1, 32, 56, 56), B.conv_desc(192, 64, 3, pad=1), C.byref(m)) == B.DR_ERR_SHAPE
+    assert B.lib().dr_conv2d_fwd_ws(_t(1, 64, 56, 56), C.c_void_p(4096), B.conv_desc(192, 64, 3, stride=2, pad=1), C.c_void_p(4096), None,
+                                    _t(1, 192, 28, 28), C.c_void_p(4096), 0, None, 0, None) == B.DR_ERR_WORKSPACE
     bad = G.inception_desc(layers[0][1], 100, 0)
     assert B.lib().dr_inception_workspace_bytes(xd, bad, C.byref(n)) == B.DR_ERR_SHAPE
 

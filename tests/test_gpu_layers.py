@@ -76,6 +76,72 @@ def test_conv2d_f32(case, relu, layout):
     assert rel_err(host(y), ref) < TOL_F32
 
 
+# layers with few output tiles: the contraction is cut over several workgroups when scratch is given
+SPLIT_CASES = [
+    (1, 64, 56, 56, 192, 3, 3, 2, 1),      # config 1 slim: 39 tiles
+    (1, 64, 64, 64, 128, 3, 3, 1, 1),      # 128 tiles, ranges of 5 slices: with KRSC they start inside a filter tap
+    (1, 48, 14, 14, 40, 3, 3, 1, 1),       # ragged filter block, 16-deep slices with KRSC
+    (1, 7, 13, 17, 33, 2, 4, 3, 1),        # tiny and ragged, four slices in two ranges
+    (2, 32, 9, 11, 70, 5, 5, 2, 2),        # two images
+    (1, 96, 27, 27, 256, 5, 5, 2, 2),      # 150 slices of 16 (KCRS) or 75 of 32 (KRSC), 16 tiles
+    (3, 16, 6, 6, 20, 3, 3, 1, 0),         # 32-filter tiles
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_CASES)
+@pytest.mark.parametrize("layout", ["kcrs", "krsc"])
+def test_conv2d_f32_with_workspace(case, layout):
+    N, C, H, W, K, R, S, stride, pad = case
+    if layout == "krsc" and not B.can_pack(C):
+        pytest.skip("KRSC filters need a channel count that is a multiple of 16")
+    rng = _rng(hash(case) % 2 ** 31 + 1)
+    x, w = _vals(rng, (N, C, H, W), "f32"), _vals(rng, (K, C, R, S), "f32") * np.float32(np.sqrt(2.0 / (C * R * S)))
+    b = (_vals(rng, (K,), "f32") * np.float32(0.1))
+    ref = oracle.conv2d(x, w, b, stride, pad, True)
+    cd = B.conv_desc(K, C, R, S, stride, pad, True, B.DR_KRSC if layout == "krsc" else B.DR_KCRS)
+    xg, wg = gpu(x), gpu(w)
+    if layout == "krsc":
+        wg = B.pack_filters(wg)
+    need = B.conv2d_workspace_bytes(xg, cd)
+    assert need > 0 and need % (K * ref.shape[0] * ref.shape[2] * ref.shape[3] * 4) == 0      # whole [K][n] planes
+    ws = torch.full((need // 4 + 7,), float("nan"), dtype=torch.float32, device="cuda")
+    # written at a channel offset of a wider tensor; the other channels stay as they are
+    y = torch.full((ref.shape[0], K + 5, ref.shape[2], ref.shape[3]), -3.0, dtype=torch.float32, device="cuda")
+    B.conv2d_fwd_ws(xg, cd, wg, gpu(b), y, ws, y_c_offset=2)
+    torch.cuda.synchronize()
+    got = host(y)
+    assert rel_err(got[:, 2:2 + K], ref) < TOL_F32
+    assert (got[:, :2] == -3.0).all() and (got[:, 2 + K:] == -3.0).all()
+    # the same call again gives the same bits (fixed order of the sum over the ranges)
+    y2 = torch.full_like(y, -3.0)
+    B.conv2d_fwd_ws(xg, cd, wg, gpu(b), y2, ws, y_c_offset=2)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+
+
+def test_conv2d_with_workspace_refusals_and_layers_that_are_not_cut():
+    x = torch.zeros((1, 64, 56, 56), dtype=torch.float32, device="cuda")
+    w = torch.zeros((192, 64, 3, 3), dtype=torch.float32, device="cuda")
+    y = torch.zeros((1, 192, 28, 28), dtype=torch.float32, device="cuda")
+    cd = B.conv_desc(192, 64, 3, stride=2, pad=1)
+    need = B.conv2d_workspace_bytes(x, cd)
+    assert need > 0
+    small = torch.zeros((need // 4 - 1,), dtype=torch.float32, device="cuda")
+    with pytest.raises(RuntimeError, match="workspace"):
+        B.conv2d_fwd_ws(x, cd, w, None, y, small)
+    with pytest.raises(RuntimeError, match="workspace"):
+        B.conv2d_fwd_ws(x, cd, w, None, y, None)
+    # a layer whose tiles reach half of the compute units needs no scratch and runs without any
+    rng = _rng(11)
+    xb, wb = _vals(rng, (16, 32, 40, 40), "f32"), _vals(rng, (64, 32, 3, 3), "f32") * np.float32(0.1)
+    cdb = B.conv_desc(64, 32, 3, pad=1)
+    assert B.conv2d_workspace_bytes(gpu(xb), cdb) == 0
+    yb = torch.empty((16, 64, 40, 40), dtype=torch.float32, device="cuda")
+    B.conv2d_fwd_ws(gpu(xb), cdb, gpu(wb), None, yb, None)
+    torch.cuda.synchronize()
+    assert rel_err(host(yb), oracle.conv2d(xb, wb, None, 1, 1)) < TOL_F32
+
+
 def test_conv2d_channel_offset_and_no_bias():
     rng = _rng(7)
     x, w = _vals(rng, (2, 8, 10, 10), "f32"), _vals(rng, (5, 8, 3, 3), "f32")
