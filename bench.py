@@ -252,6 +252,42 @@ class Workload:
             out[form] = (float(self.np.min(ts)), float(self.np.median(ts)))
         return out
 
+    def block_times(self, reps=5):
+        """Time per block of the network (the rows of Table 4: conv1, conv2, the inception modules, loss3; the
+        pooling layers between modules as rows of their own), per form, in ms: the library's per-layer
+        HIP-event times (dr_net_layer_times), best of a few runs, summed over the layers of a block."""
+        B = self.B
+        names = ["inception_3a", "inception_3b", "inception_4a", "inception_4b", "inception_4c", "inception_4d",
+                 "inception_4e", "inception_5a", "inception_5b"]
+        out = {}
+        for form, f in self.forms.items():
+            net = f["net"]
+            net.set_timing(True)
+            best = None
+            for _ in range(reps):
+                self.run(form)
+                self.torch.cuda.synchronize()
+                t = net.layer_times()
+                best = t if best is None else [min(a, b) for a, b in zip(best, t)]
+            net.set_timing(False)
+            rows, convs, modules, pools = {}, 0, 0, 0
+            for kind, ms in zip(net.kinds, best):
+                if kind == B.DR_LAYER_INCEPTION:
+                    name = names[modules] if modules < len(names) else "inception_%d" % modules
+                    modules += 1
+                elif kind in (B.DR_LAYER_AVGPOOL, B.DR_LAYER_FC, B.DR_LAYER_SOFTMAX):
+                    name = "loss3"
+                elif modules:               # between modules: pool3, pool4
+                    pools += 1
+                    name = "pool%d" % (pools + 2)
+                else:                       # the stem: conv1 = first convolution and what follows it, conv2 = the rest
+                    if kind == B.DR_LAYER_CONV:
+                        convs += 1
+                    name = "conv1" if convs <= 1 else "conv2"
+                rows[name] = rows.get(name, 0.0) + ms
+            out[form] = {k: round(v, 4) for k, v in rows.items()}
+        return out
+
     def memory(self):
         """Run-time memory of the forward pass per form (the analogue of the memory columns of Table 6): the
         workspace the library plans for this batch (two ping-pong activation buffers + per-layer scratch), the
@@ -430,6 +466,13 @@ def main():
         "non_tensor_hbm_gbs_launches_over_32MB": round(sum(nt_bytes(r) for r in big) / max(sum(r[6] for r in big), 1e-9) / 1e6, 1) if big else None,
         "non_tensor_by_kind": {k: {"launches": v[2], "ms": round(v[1], 4), "gbs": round(v[0] / max(v[1], 1e-9) / 1e6, 1)} for k, v in sorted(by_kind.items())},
         "roofline": roofline,
+        "per_block_ms": wl.block_times() if args.config == 5 else None,
+        "per_block_ms_paper_S5": {"conv1": [94.92, 8.424], "conv2": [153.8, 16.62], "inception_3a": [55.23, 21.17],
+                                  "inception_3b": [98.41, 25.94], "inception_4a": [30.53, 16.80], "inception_4b": [32.60, 20.29],
+                                  "inception_4c": [46.96, 18.71], "inception_4d": [36.88, 24.67], "inception_4e": [48.24, 28.08],
+                                  "inception_5a": [24.64, 10.69], "inception_5b": [24.92, 14.58], "loss3": [3.014, 2.97],
+                                  "note": "Table 4, GoogLeNet vs GoogLeNet-Slim, one image on a Galaxy S5 CPU (context only)"}
+        if args.config == 5 else None,
         "activation_memory": wl.memory(),
         "paper_context": "GoogLeNet 651.4 ms -> GoogLeNet-Slim 210.6 ms on Samsung Galaxy S5 CPU; 10.17 -> 6.57 ms on "
                          "Titan X (batch 1, Table 4/5); inception_3a 55.23 -> 21.17 ms on S5; run-time memory 33.2 -> 13.2 MB per "

@@ -392,6 +392,7 @@ class Net:
         _check(lib().dr_net_create(arr, len(layer_descs), C.byref(h)))
         self._h = h
         self.n_layers = len(layer_descs)
+        self.kinds = [int(d.kind) for d in layer_descs]
 
     def __del__(self):
         if getattr(self, "_h", None) is not None and _lib is not None:
