@@ -13,7 +13,12 @@
 //   TAP = true  (C % 64 == 0): a slice lies inside one tap, the padding test is wave-uniform per
 //        tap and is hoisted out of the slice loop; only a scalar offset moves from slice to slice.
 //   TAP = false: the tap of a lane's chunk differs from lane to lane; it is looked up per slice in
-//        per-row validity bit masks (a few vector-ALU instructions per load).
+//        per-row validity bit masks (a few vector-ALU instructions per load).  When a row's run is not a
+//        multiple of 64 elements, the last slice of every row would be partly empty (S * C = 80: 2
+//        slices for 1.25); with `flat` set the slices instead run on into the next filter row - the
+//        filters of row r + 1 follow those of row r in KRSC memory, and a lane whose chunk has
+//        wrapped takes the next row's address and verdict - so that only the tile's last slice is
+//        ragged (5x5 filters on 16 channels: 7 slices instead of 10, on 32 channels 13 instead of 15).
 //
 // Data movement.  Every operand chunk is fetched by a 16-byte buffer load that writes LDS directly
 // (no register staging): lane l of a wave fills slot l of a 1 KiB block, i.e. 8 rows x 8 chunks of a
@@ -61,6 +66,8 @@ struct DArgs {
     int c8;                   // C / 8: chunks per tap
     int run_chunks;           // S * C / 8: chunks per filter row
     int slices_per_run;       // ceil(run_chunks / 8)
+    int slices_per_tile;      // slices of one tile's contraction: R * slices_per_run, fewer when `flat`
+    int flat;                 // TAP = false only: slices run on from one filter row into the next (see the header)
     unsigned magic_c8;        // ceil(2^32 / c8)
     unsigned long long m_pq, m_q;   // ceil(2^40 / (P*Q)), ceil(2^40 / Q)
     int vec_ok;               // 16-byte stores / bias / residual accesses are aligned
@@ -196,7 +203,7 @@ void conv_bf16_dma_kernel(const DArgs a)
     const int bid = xcd * (G >> 3) + min(xcd, G & 7) + (blockIdx.x >> 3);
     const int mt = bid % a.grid_m, nt0 = bid / a.grid_m, gn = G / a.grid_m;
     const int my_tiles = (a.grid_n - nt0 + gn - 1) / gn;
-    const int nslices = g.R * a.slices_per_run;
+    const int nslices = a.slices_per_tile;
     const int total = my_tiles * nslices;
 
     // ---- per-lane constants of the channel block: filter offsets for the loader, bias for the store
@@ -222,6 +229,7 @@ void conv_bf16_dma_kernel(const DArgs a)
     unsigned b_mask[B_PER];       // bits 0..15: tap s is OUTSIDE the image row; bits 16..31: filter row r is inside
     unsigned b_cur[B_PER];        // TAP: offset of the current tap or OOB;  else: b_mask with the current row's verdict
     int ld_nt = nt0, ld_r = 0, ld_j0 = 0, ld_s = 0, ld_c = 0;   // wave-uniform cursor of the next slice to load
+    int ld_fresh = 1;             // TAP = false: the cursor has entered a new filter row (its verdicts are due)
 
     // Per-lane state of pixel tile nt.  A 1x1 filter at stride 1 without padding reads input pixel n for
     // output pixel n: no decoding.  Otherwise the first fetched pixel is decoded into (image, p, q) by
@@ -296,25 +304,48 @@ void conv_bf16_dma_kernel(const DArgs a)
                 }
             }
         } else {
-            if (ld_j0 == 0) row_setup();
-            const int jl = ld_j0 + lc;                                             // this lane's chunk within the run
-            const int s = a.c8 == 1 ? jl : (int)__umulhi((unsigned)jl, a.magic_c8); // its tap: jl / (C / 8), at most 15
-            const int sh = 31 - s;
-            const bool a_ok = jl < a.run_chunks;
-            const int soff_a = (ld_r * a.run_chunks + ld_j0) * 16;
+            if (ld_fresh) { row_setup(); ld_fresh = 0; }
+            const int jl0 = ld_j0 + lc;                                            // this lane's chunk within the run of row ld_r
+            const bool straddle = a.flat && ld_j0 + 8 > a.run_chunks;             // (wave-uniform) the slice runs on into row ld_r + 1
+            const int soff_a = (ld_r * a.run_chunks + ld_j0) * 16;                // filter rows follow one another in memory
             const int run_off = ld_r * g.W * g.C * 2 + ld_j0 * 16;
+            if (!straddle) {
+                const int s = a.c8 == 1 ? jl0 : (int)__umulhi((unsigned)jl0, a.magic_c8);   // its tap: jl0 / (C / 8), at most 15
+                const int sh = 31 - s;
+                const bool a_ok = jl0 < a.run_chunks;
 #pragma unroll
-            for (int i = 0; i < A_PER; ++i)
-                load_to_lds16(rw, sa + i * PASS, a_ok ? a_voff[i] : OOB, soff_a);
+                for (int i = 0; i < A_PER; ++i)
+                    load_to_lds16(rw, sa + i * PASS, a_ok ? a_voff[i] : OOB, soff_a);
 #pragma unroll
-            for (int i = 0; i < B_PER; ++i) {
-                const unsigned off = ((b_cur[i] << sh) & 0x80000000u) | (unsigned)(b_base[i] + run_off);
-                load_to_lds16(rx, sb + i * PASS, (int)off, 0);
+                for (int i = 0; i < B_PER; ++i) {
+                    const unsigned off = ((b_cur[i] << sh) & 0x80000000u) | (unsigned)(b_base[i] + run_off);
+                    load_to_lds16(rx, sb + i * PASS, (int)off, 0);
+                }
+            } else {
+                const bool wrap = jl0 >= a.run_chunks;                            // this lane's chunk belongs to row ld_r + 1
+                const int jl = wrap ? jl0 - a.run_chunks : jl0;
+                const int s = a.c8 == 1 ? jl : (int)__umulhi((unsigned)jl, a.magic_c8);
+                const int sh = 31 - s;
+                const bool more = ld_r + 1 < g.R;                                 // (wave-uniform) there is a next row
+                const bool a_ok = !wrap || more;
+                const int off_l = run_off + (wrap ? (g.W * g.C - a.run_chunks * 8) * 2 : 0);
+                const int next_bit = (17 + ld_r) & 31;
+#pragma unroll
+                for (int i = 0; i < A_PER; ++i)
+                    load_to_lds16(rw, sa + i * PASS, a_ok ? a_voff[i] : OOB, soff_a);
+#pragma unroll
+                for (int i = 0; i < B_PER; ++i) {
+                    const unsigned nxt = (more && ((b_mask[i] >> next_bit) & 1u)) ? (b_mask[i] | 0xFFFF0000u) : 0xFFFFFFFFu;
+                    const unsigned vm = wrap ? nxt : b_cur[i];
+                    const unsigned off = ((vm << sh) & 0x80000000u) | (unsigned)(b_base[i] + off_l);
+                    load_to_lds16(rx, sb + i * PASS, (int)off, 0);
+                }
             }
             ld_j0 += 8;
             if (ld_j0 >= a.run_chunks) {
-                ld_j0 = 0;
-                if (++ld_r == g.R) { ld_r = 0; ld_nt += gn; tile_setup(ld_nt); }
+                ld_j0 = a.flat ? ld_j0 - a.run_chunks : 0;
+                ld_fresh = 1;
+                if (++ld_r == g.R) { ld_r = 0; ld_j0 = 0; ld_nt += gn; tile_setup(ld_nt); }
             }
         }
     };
@@ -578,6 +609,12 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
     a.m_q = ((1ull << 40) + (unsigned)g.Q - 1) / (unsigned)g.Q;
     a.pointwise = g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
     a.stem_hp = a.stem_wp = 0;
+    a.slices_per_tile = g.R * a.slices_per_run;
+    a.flat = 0;
+    if (g.C % 64 != 0 && a.run_chunks >= 8 && (g.R * a.run_chunks + 7) / 8 < a.slices_per_tile) {
+        a.flat = 1;                                   // slices that run on across filter rows save at least one slice per tile
+        a.slices_per_tile = (g.R * a.run_chunks + 7) / 8;
+    }
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y) && (!residual || (g.res_ctot % 8 == 0 && aligned16(residual)));
     a.nsplit = 0;
     if (split && split->n > 1) {
@@ -666,6 +703,7 @@ int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int 
     a.m_pq = ((1ull << 40) + (unsigned)(g.P * g.Q) - 1) / (unsigned)(g.P * g.Q);
     a.m_q = ((1ull << 40) + (unsigned)g.Q - 1) / (unsigned)g.Q;
     a.pointwise = 0;
+    a.slices_per_tile = 4; a.flat = 0;
     a.stem_hp = hp; a.stem_wp = wp;
     a.nsplit = 0;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y);
