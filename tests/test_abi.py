@@ -73,6 +73,17 @@ def test_argument_validation_runs_before_any_launch():
     assert L.dr_softmax_fwd(_t(2, 10, 2, 1), fake, fake, None) == B.DR_ERR_SHAPE
 
 
+def test_sizes_beyond_the_kernels_index_range_are_refused_on_the_host():
+    L = B.lib()
+    fake = C.c_void_p(4096)   # never dereferenced
+    huge = _t(1 << 11, 1 << 10, 1 << 5, 1 << 5)          # 2^31 elements
+    assert L.dr_relu(huge, fake, fake, None) == B.DR_ERR_UNSUPPORTED and "2^31" in B.last_error()
+    # fp32 convolution: the kernel addresses its operands with 32-bit byte offsets
+    xd, yd = _t(1, 16, 8192, 8192), _t(1, 1, 8192, 8192)  # input of 4 GiB
+    assert L.dr_conv2d_fwd(xd, fake, B.conv_desc(1, 16, 1), fake, None, yd, fake, 0, None) == B.DR_ERR_UNSUPPORTED
+    assert "GiB" in B.last_error()
+
+
 def test_inception_and_net_planning_on_host():
     layers = workloads.CONFIGS[2]["original"]
     d = G.inception_desc(layers[0][1], 192, 0)
