@@ -24,8 +24,17 @@
 //        the slice only moves a wave-uniform scalar offset, which rides in the buffer instructions'
 //        scalar operand, and the padding test is redone once per tap.  Almost no vector-ALU work
 //        per slice, and the filter rows are read with 16-byte loads.
-//   CF = false (filters in KCRS order, any shape): k runs in KCRS order and every gathered element
-//        decodes (c, r, s).
+//   CF = false (filters in KCRS order, any shape): k runs in KCRS order.  The workgroup first writes a
+//        table k -> (offset of x[0][c][r][s], r, s) to LDS (contractions of up to KTAB elements, which
+//        covers the small-channel first layers this path is for); an element's k is the same for a
+//        whole wave, so its table entry arrives by one broadcast LDS read and the lane adds its
+//        pixel's base offset; with padding it also tests the (r, s) bits of two per-lane masks of
+//        valid window rows and columns.  Longer contractions decode (c, r, s) per element.
+//        Without padding and with a filter width S that rounds up to a multiple of 4 cheaply (11 -> 12,
+//        7 -> 8), k instead runs over (c, r, groups of 4 taps): the four activations of a group are
+//        neighbours in memory and arrive by one 16-byte load per lane (consecutive pixels at stride 4
+//        read consecutive 16-byte pieces), the taps added by the rounding count as zeros on both sides.
+//        That quarter of the load instructions is what the first layer of AlexNet was limited by.
 //
 // A layer with fewer tiles than the device has compute units (one image, or a few) leaves most of the
 // matrix cores idle while each workgroup walks the whole contraction alone.  Given scratch memory, the
@@ -45,6 +54,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int NT = 256;       // threads per workgroup
+constexpr int KTAB = 512;     // CF = false: contraction elements (or groups of 4 taps) whose table entries fit the 4 KB LDS table
 
 struct KArgs {
     const float* x;
@@ -56,6 +66,7 @@ struct KArgs {
     int grid_m, grid_n;
     int x_bytes, w_bytes;   // sizes of the x and w tensors (both < 2 GiB, checked by the launcher)
     int w_krsc;             // filters are in KRSC order (else KCRS)
+    int row_groups;         // CF = false: k runs over (c, r, groups of 4 taps), see the header
     float* part;            // partial sums [splits][K][Ng] of a split contraction, or NULL
     int splits, slices_per_split;
 };
@@ -101,6 +112,7 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
 
     __shared__ __attribute__((aligned(16))) float As[2][BM * LDT];
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * LDT];
+    __shared__ __attribute__((aligned(16))) int ktab[CF ? 4 : 2 * KTAB];   // CF = false: {byte offset, r | s << 8} per k
 
     const ConvGeom& g = a.g;
     const int R = FR ? FR : g.R, S = FS ? FS : g.S;
@@ -143,6 +155,50 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
         iw0 = q * g.sw - g.pw;
         xoff0 = img * g.C * HW + ih0 * g.W + iw0;
     }
+    // ---- CF = false: the k table and this lane's masks of window rows / columns inside the image
+    const bool rg = !CF && a.row_groups;
+    const int S4 = (S + 3) & ~3;
+    const int kg_eff = rg ? g.C * R * S4 : g.Kg;     // contraction length including the taps added by rounding S up
+    const int ktab_n = (kg_eff + BK - 1) / BK * BK;
+    const bool use_tab = !CF && !rg && ktab_n <= KTAB && R <= 31 && S <= 31;
+    const bool nopad = g.ph == 0 && g.pw == 0;      // then every window lies inside the image
+    unsigned rowmask = 0, colmask = 0;
+    if constexpr (!CF) {
+        if (use_tab) {
+            for (int k = tid; k < ktab_n; k += NT) {
+                int off = OOB, rs_bits = 31;          // beyond the contraction: the load returns 0 (mask bit 31 is never set)
+                if (k < g.Kg) {
+                    const int c = k / RS, rs = k - c * RS, r = rs / S, s_ = rs - r * S;
+                    off = (c * HW + r * g.W + s_) * 4;
+                    rs_bits = r | (s_ << 8);
+                }
+                ktab[2 * k] = off;
+                ktab[2 * k + 1] = rs_bits;
+            }
+            if (n_ok) {
+                for (int r = 0; r < R; ++r) rowmask |= ((unsigned)(ih0 + r) < (unsigned)g.H ? 1u : 0u) << r;
+                for (int s_ = 0; s_ < S; ++s_) colmask |= ((unsigned)(iw0 + s_) < (unsigned)g.W ? 1u : 0u) << s_;
+            }
+            lds_barrier();                            // the table is complete before the first slice is gathered
+        }
+        if (rg) {
+            // per group of 4 taps: {byte offset of x[0][c][r][s0], element offset of w[0][c][r][s0] | taps that exist << 24}
+            for (int gq = tid; gq < ktab_n / 4; gq += NT) {
+                int xo = OOB, meta = 0;
+                const int kk = gq * 4;
+                if (kk < kg_eff) {
+                    const int c = kk / (R * S4), rem = kk - c * R * S4, r = rem / S4, s0 = rem - r * S4;
+                    xo = (c * HW + r * g.W + s0) * 4;
+                    meta = ((c * R + r) * S + s0) | (min(4, S - s0) << 24);
+                }
+                ktab[2 * gq] = xo;
+                ktab[2 * gq + 1] = meta;
+            }
+            lds_barrier();
+        }
+    }
+    const int bbase = n_ok ? xoff0 * 4 : OOB;        // (table path) byte offset of this lane's window origin
+
     // ---- per-thread state for A: rows f / KQ of the slice, byte offset of the row start
     const bool vecA = (g.Kg & 3) == 0;
     int arow[A_PER];
@@ -173,7 +229,7 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
     };
 
     // this workgroup's range of slices: [s_begin, s_begin + nslices)
-    const int nslices_all = CF ? RS * (g.C / BK) : (g.Kg + BK - 1) / BK;
+    const int nslices_all = CF ? RS * (g.C / BK) : (kg_eff + BK - 1) / BK;
     const int s_begin = SPLIT ? (int)blockIdx.y * a.slices_per_split : 0;
     const int nslices = SPLIT ? min(a.slices_per_split, nslices_all - s_begin) : nslices_all;
     if constexpr (CF && SPLIT) {
@@ -206,6 +262,35 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
             if (ld_c0 == g.C) { ld_c0 = 0; if (++ld_s == S) { ld_s = 0; ++ld_r; } }
         } else {
             const int k0 = (s_begin + it) * BK;
+            if (rg) {
+#pragma unroll
+                for (int i = 0; i < A_PER; ++i) {
+                    const int meta = ktab[2 * (k0 / 4 + (tid + i * NT) % KQ) + 1];
+                    const int ao = meta & 0xFFFFFF, nt = meta >> 24;
+                    f32x4 v;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = buf_load(rw, j < nt ? arow[i] + (ao + j) * 4 : OOB, 0);
+                    ra[SET][i] = v;
+                }
+#pragma unroll
+                for (int i = 0; i < B_PER; ++i) {
+                    const int gq = k0 / 4 + bkq0 + i * BKQ_STEP;              // the same for the whole wave
+                    const int xo = ktab[2 * gq], nt = ktab[2 * gq + 1] >> 24;
+                    const int vo = bbase + xo;
+                    f32x4 v;
+                    if ((unsigned)vo < (unsigned)a.x_bytes && (unsigned)vo + 16u > (unsigned)a.x_bytes) {
+                        // the tensor's last few elements: one by one, each checked against the end
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[j] = buf_load(rx, vo + 4 * j, 0);
+                    } else {
+                        v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rx, vo, 0, 0));
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = j < nt ? v[j] : 0.f;
+                    rb[SET][i] = v;
+                }
+                return;
+            }
 #pragma unroll
             for (int i = 0; i < A_PER; ++i) {
                 const int gk = k0 + ((tid + i * NT) % KQ) * 4;
@@ -219,6 +304,27 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
                     ra[SET][i] = v;
                 }
             }
+            if (use_tab) {
+#pragma unroll
+                for (int i = 0; i < B_PER; ++i) {
+                    const int gk = k0 + (bkq0 + i * BKQ_STEP) * 4;            // the same for the whole wave
+                    typedef int i32x4 __attribute__((ext_vector_type(4)));
+                    const i32x4 e01 = *reinterpret_cast<const i32x4*>(&ktab[2 * gk]);
+                    const i32x4 e23 = *reinterpret_cast<const i32x4*>(&ktab[2 * gk + 4]);
+                    const int off[4] = {e01[0], e01[2], e23[0], e23[2]}, rsb[4] = {e01[1], e01[3], e23[1], e23[3]};
+                    f32x4 v;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        int vo = bbase + off[j];
+                        if (!nopad) {
+                            const bool ok = ((rowmask >> (rsb[j] & 255)) & (colmask >> (rsb[j] >> 8)) & 1u) != 0;
+                            vo = ok ? vo : OOB;
+                        }
+                        v[j] = buf_load(rx, vo, 0);
+                    }
+                    rb[SET][i] = v;
+                }
+            } else {
 #pragma unroll
             for (int i = 0; i < B_PER; ++i) {
                 const int gk = k0 + (bkq0 + i * BKQ_STEP) * 4;
@@ -234,6 +340,7 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
                     if (++s == S) { s = 0; if (++r == R) { r = 0; ++c; } }
                 }
                 rb[SET][i] = v;
+            }
             }
         }
     };
@@ -372,11 +479,27 @@ inline int split_plan(int tiles, int nslices, int* slices_per_split)
     return (nslices + per - 1) / per;
 }
 
+// Slices of the contraction, and whether a KCRS layer takes the groups-of-4-taps order (no padding, a filter width
+// that rounding up to a multiple of 4 lengthens by at most a quarter, a table that fits LDS).
+template <int BK>
+int contraction_slices(const ConvGeom& g, int* row_groups)
+{
+    *row_groups = 0;
+    if (g.w_krsc) return g.R * g.S * (g.C / BK);
+    const int S4 = (g.S + 3) & ~3;
+    const long kg4 = (long)g.C * g.R * S4;
+    if (g.ph == 0 && g.pw == 0 && S4 * 4 <= g.S * 5 && (kg4 + BK - 1) / BK * BK <= 4 * KTAB) {
+        *row_groups = 1;
+        return (int)((kg4 + BK - 1) / BK);
+    }
+    return (g.Kg + BK - 1) / BK;
+}
+
 template <int BM, int BN, int BK>
 size_t split_bytes(const ConvGeom& g)
 {
-    const bool cf = g.w_krsc;
-    const int nslices = cf ? g.R * g.S * (g.C / BK) : (g.Kg + BK - 1) / BK;
+    int rgm;
+    const int nslices = contraction_slices<BK>(g, &rgm);
     int per;
     const int splits = split_plan(((g.K + BM - 1) / BM) * ((g.Ng + BN - 1) / BN), nslices, &per);
     return splits > 1 ? (size_t)splits * g.K * g.Ng * sizeof(float) : 0;
@@ -390,7 +513,7 @@ int launch_tile(const KArgs& base, void* ws, size_t ws_bytes, hipStream_t st)
     a.grid_n = (a.g.Ng + BN - 1) / BN;
     a.part = nullptr;
     a.splits = 1;
-    const int nslices = a.w_krsc ? a.g.R * a.g.S * (a.g.C / BK) : (a.g.Kg + BK - 1) / BK;
+    const int nslices = contraction_slices<BK>(a.g, &a.row_groups);
     a.slices_per_split = nslices;
     if (ws) {
         int per;
@@ -454,7 +577,7 @@ int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const flo
     // grid several workgroups per compute unit, which matters more here than operand reuse.  The
     // deepest slice the channel count allows, two slices of prefetch.
     const bool rows32 = (g.K + 31) / 32 * 32 < (g.K + 63) / 64 * 64;
-    if (g.w_krsc && g.C % 32 == 0)
+    if (g.w_krsc && g.C % 32 == 0)      // (32-deep slices with the groups-of-4-taps order: measured 10 % slower)
         return rows32 ? launch_tile<32, 128, 1, 4, 32, 2>(a, ws, ws_bytes, st) : launch_tile<64, 64, 2, 2, 32, 2>(a, ws, ws_bytes, st);
     return rows32 ? launch_tile<32, 128, 1, 4, 16, 2>(a, ws, ws_bytes, st) : launch_tile<64, 64, 2, 2, 16, 2>(a, ws, ws_bytes, st);
 }

@@ -49,6 +49,10 @@ CONV_CASES = [
     (1, 4, 6, 6, 150, 1, 1, 1, 0),         # M = 150: two tiles with a ragged second one
     (2, 48, 14, 14, 40, 3, 3, 1, 1),       # C = 48: KRSC with 16-deep slices only
     (1, 32, 9, 11, 70, 5, 5, 2, 2),        # KRSC, strided, ragged everything
+    (1, 3, 40, 37, 24, 7, 7, 2, 0),        # KCRS without padding: groups of 4 taps, 7 -> 8 wide
+    (2, 5, 12, 12, 10, 4, 4, 1, 0),        # the same with a width that is a multiple of 4 (no added taps)
+    (1, 2, 9, 30, 6, 3, 10, 1, 0),         # 10 -> 12 wide, windows that end on the tensor's last element
+    (3, 1, 14, 14, 20, 12, 12, 1, 0),      # one channel, 12 x 12
 ]
 
 
