@@ -81,6 +81,34 @@ def test_conv_stream(case):
     _run(case, relu=(hash(case) % 2 == 0))
 
 
+def _random_cases(count, seed):
+    """Seeded random layer shapes inside what the streaming kernel takes (C a multiple of 8, S <= 9, R <= 16):
+    small ones of every kind, and every fourth one with enough pixels to leave the 64 x 64 tiles."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        big = len(out) % 4 == 3
+        C = 8 * int(rng.integers(1, 18))
+        R, S = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+        stride = int(rng.integers(1, 4))
+        pad = int(rng.integers(0, min(R, S) // 2 + 2))
+        N = int(rng.integers(1, 4))
+        H, W = (int(rng.integers(60, 130)), int(rng.integers(60, 130))) if big else (int(rng.integers(3, 40)), int(rng.integers(3, 40)))
+        K = int(rng.integers(1, 40)) if big else int(rng.integers(1, 200))
+        if H + 2 * pad < R or W + 2 * pad < S or pad >= R or pad >= S:
+            continue
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        if N * P * Q * K * C * R * S > 3e8:
+            continue
+        out.append((N, C, H, W, K, R, S, stride, pad))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_cases(48, 20260101))
+def test_conv_stream_random_shapes(case):
+    _run(case, relu=(hash(case) % 2 == 0), bias=(hash(case) % 3 != 0))
+
+
 def test_conv_stream_many_tiles_per_workgroup():
     """More pixel tiles than the device holds workgroups: every workgroup walks several tiles, and the
     loads of one tile are in flight while the previous one is stored."""
