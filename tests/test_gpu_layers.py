@@ -80,6 +80,51 @@ def test_conv2d_f32(case, relu, layout):
     assert rel_err(host(y), ref) < TOL_F32
 
 
+def _random_f32_cases(count, seed):
+    """Seeded random fp32 layer shapes: any channel count (KCRS; KRSC as well when it is a multiple of 16), filters
+    up to 12 wide, half of them without padding (the groups-of-4-taps order takes those whose width allows it)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        C = int(rng.integers(1, 9)) if len(out) % 2 else 16 * int(rng.integers(1, 5))
+        R, S = int(rng.integers(1, 13)), int(rng.integers(1, 13))
+        stride = int(rng.integers(1, 5))
+        pad = 0 if len(out) % 4 < 2 else int(rng.integers(0, min(R, S) // 2 + 1))
+        N = int(rng.integers(1, 4))
+        H, W = int(rng.integers(R, 48)), int(rng.integers(S, 48))
+        K = int(rng.integers(1, 150))
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        if N * P * Q * K * C * R * S > 2e8:
+            continue
+        out.append((N, C, H, W, K, R, S, stride, pad))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_f32_cases(40, 20260102))
+def test_conv2d_f32_random_shapes(case):
+    N, C, H, W, K, R, S, stride, pad = case
+    rng = _rng(hash(case) % 2 ** 31 + 2)
+    x, w = _vals(rng, (N, C, H, W), "f32"), _vals(rng, (K, C, R, S), "f32") * np.float32(np.sqrt(2.0 / (C * R * S)))
+    b = (_vals(rng, (K,), "f32") * np.float32(0.1))
+    relu = hash(case) % 2 == 0
+    ref = oracle.conv2d(x, w, b, stride, pad, relu)
+    xg, bg = gpu(x), gpu(b)
+    for layout in ("kcrs", "krsc") if B.can_pack(C) else ("kcrs",):
+        cd = B.conv_desc(K, C, R, S, stride, pad, relu, B.DR_KRSC if layout == "krsc" else B.DR_KCRS)
+        wg = B.pack_filters(gpu(w)) if layout == "krsc" else gpu(w)
+        y = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+        B.conv2d_fwd(xg, cd, wg, bg, y)
+        torch.cuda.synchronize()
+        assert rel_err(host(y), ref) < TOL_F32, layout
+        need = B.conv2d_workspace_bytes(xg, cd)
+        if need:
+            ws = torch.empty((need // 4,), dtype=torch.float32, device="cuda")
+            y2 = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+            B.conv2d_fwd_ws(xg, cd, wg, bg, y2, ws)
+            torch.cuda.synchronize()
+            assert rel_err(host(y2), ref) < TOL_F32, (layout, "with workspace")
+
+
 # layers with few output tiles: the contraction is cut over several workgroups when scratch is given
 SPLIT_CASES = [
     (1, 64, 56, 56, 192, 3, 3, 2, 1),      # config 1 slim: 39 tiles
