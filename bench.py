@@ -220,7 +220,7 @@ class Workload:
             y = G.empty_like_desc(net.output_desc(xd))
             ws = torch.empty(max(net.workspace_bytes(xd), 256), dtype=torch.uint8, device="cuda")
             flat = G.flat_params(params_host, self.dtype, pack=True)
-            if (slim or fused) and bf16 and not folded and any(kind == "inception" for kind, _ in layers):
+            if (slim or fused) and not folded and any(kind == "inception" for kind, _ in layers):
                 flat = G.stack_first_steps(layers, flat)      # the layout DR_FUSE_STACK takes (Eq. (12))
             self.forms[form] = dict(net=net, y=y, ws=ws, params=flat,
                                     layers=layers, params_host=params_host, folded=folded)

@@ -211,12 +211,13 @@ typedef struct { int n_steps; dr_step steps[DR_MAX_STEPS]; } dr_branch;
                               (that convolution then also applies its ReLU in the store) */
 #define DR_FUSE_STACK  4   /* Eq. (12): first-step 1x1 convolutions (stride 1, no padding, followed by ReLU)
                               that read the module input run as one convolution with stacked filters, each
-                              writing its own destination (needs DR_FUSE_RELU).  Taken for bf16 NHWC
-                              tensors when the caller has laid the filters of those convolutions back to
-                              back in device memory in branch order (weights[j] of the next one starts
-                              where the previous one's k*c elements end; the same for the fp32 biases, or
-                              all biases NULL) and every bank but the last has a multiple of 8 filters;
-                              otherwise the convolutions run one by one, with the same result */
+                              writing its own destination (needs DR_FUSE_RELU).  Taken for bf16 NHWC and
+                              fp32 NCHW tensors when the caller has laid the filters of those convolutions
+                              back to back in device memory in branch order (weights[j] of the next one
+                              starts where the previous one's k*c elements end; the same for the fp32
+                              biases, or all biases NULL), all in one filter_layout, and (bf16) every bank
+                              but the last has a multiple of 8 filters; otherwise the convolutions run one
+                              by one, with the same result */
 #define DR_CONCURRENT_BRANCHES 8 /* branches 1.. run on streams the library owns (per host thread and
                               device, created on first use, default priority), forked from the caller's
                               stream by an event before the module and joined to it by events before the

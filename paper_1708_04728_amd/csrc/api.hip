@@ -357,7 +357,9 @@ int run_stacked_first_steps(const dr_tensor& xd, const void* x, const dr_incepti
         c_off += c;
     }
     if (nb < 2) return DR_OK;
-    // back to back in memory, in branch order; every bank but the last a multiple of 8 filters
+    // back to back in memory, in branch order; bf16: every bank but the last a multiple of 8 filters (16-byte stores)
+    const bool f32 = xd.dtype == DR_F32;
+    const size_t esz = f32 ? 4 : 2;
     const char* w0 = (const char*)wts.p[pidxs[0]];
     const char* b0 = bss.p ? (const char*)bss.p[pidxs[0]] : nullptr;
     if (!w0) return DR_OK;
@@ -368,8 +370,9 @@ int run_stacked_first_steps(const dr_tensor& xd, const void* x, const dr_incepti
         const char* bi = bss.p ? (const char*)bss.p[pidxs[i]] : nullptr;
         if ((const char*)wts.p[pidxs[i]] != w0 + woff) return DR_OK;
         if ((b0 == nullptr) != (bi == nullptr) || (b0 && bi != b0 + boff)) return DR_OK;
-        if (i + 1 < nb && c0.k % 8 != 0) return DR_OK;
-        woff += (size_t)c0.k * xd.c * 2;
+        if (!f32 && i + 1 < nb && c0.k % 8 != 0) return DR_OK;
+        if (c0.filter_layout != d.branches[members[0]].steps[0].conv.filter_layout) return DR_OK;
+        woff += (size_t)c0.k * xd.c * esz;
         boff += (size_t)c0.k * 4;
         ktot += c0.k;
     }
@@ -382,23 +385,29 @@ int run_stacked_first_steps(const dr_tensor& xd, const void* x, const dr_incepti
     g.Ng = xd.n * xd.h * xd.w;
     g.relu = 1;
     g.res_ctot = 0;
-    g.w_krsc = 1;           // a 1x1 filter bank is the same array in both orders
-    g.nhwc = 1;
+    // a 1x1 filter bank is the same array in both orders; fp32 keeps the order the branches name, so that the stacked
+    // convolution adds its products in the same order as one convolution per branch
+    g.w_krsc = f32 ? d.branches[members[0]].steps[0].conv.filter_layout == DR_KRSC : 1;
+    g.nhwc = f32 ? 0 : 1;
     g.c_logical = 0;
-    if (g.Ng == 0 || !x || !conv_bf16_dma_eligible(g, x, w0)) return DR_OK;
+    if (g.Ng == 0 || !x) return DR_OK;
+    if (f32 ? ((size_t)g.Ng * g.C * 4 >= (1ull << 31) || (size_t)ktot * g.C * 4 >= (1ull << 31)) : !conv_bf16_dma_eligible(g, x, w0))
+        return DR_OK;
     ConvSplit sp;
     sp.n = nb;
     for (int i = 0; i < nb; ++i) {
         const dr_branch& br = d.branches[members[i]];
         const bool direct = br.n_steps == 1 && fuse_cat;
         const int k = br.steps[0].conv.k;
-        void* buf = direct ? y : ar.take((size_t)g.Ng * k * 2);
+        void* buf = direct ? y : ar.take((size_t)g.Ng * k * esz);
         if (!buf) return fail(DR_ERR_WORKSPACE, "%s: workspace too small", who);
         sp.dst[i] = ConvDest{buf, direct ? yd.c : k, direct ? coffs[i] : 0, k};
         dst[members[i]] = direct ? nullptr : buf;
         stacked[members[i]] = true;
     }
     g.y_ctot = sp.dst[0].ctot; g.y_coff = sp.dst[0].c_offset;
+    if (f32)
+        return launch_conv_f32(g, (const float*)x, (const float*)w0, (const float*)b0, nullptr, (float*)sp.dst[0].y, st, nullptr, 0, &sp);
     TraceScope trace("conv_bf16", &g, g.Ng, st);
     return launch_conv_bf16_dma(g, (const uint16_t*)x, (const uint16_t*)w0, (const float*)b0, nullptr, (uint16_t*)sp.dst[0].y, st, &sp);
 }
@@ -413,10 +422,11 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
     int nseg = 0, c_off = 0;
     // DR_FUSE_STACK (Eq. (12)): first-step 1x1 convolutions on the module input run as one convolution
     // when their filters (and biases) lie back to back in memory in branch order, so that they form the
-    // stacked filter bank as they are; each keeps its own destination.  bf16 channels-last only.
+    // stacked filter bank as they are; each keeps its own destination.  bf16 channels-last and fp32 NCHW.
     void* stacked_dst[DR_MAX_BRANCHES] = {};
     bool stacked[DR_MAX_BRANCHES] = {};
-    if ((d.mode & DR_FUSE_STACK) && !ar.measure && xd.dtype == DR_BF16 && xd.layout == DR_NHWC && wts.p)
+    if ((d.mode & DR_FUSE_STACK) && !ar.measure && wts.p &&
+        ((xd.dtype == DR_BF16 && xd.layout == DR_NHWC) || (xd.dtype == DR_F32 && xd.layout == DR_NCHW)))
         DR_TRY(run_stacked_first_steps(xd, x, d, wts, bss, yd, y, ar, main_st, stacked, stacked_dst));
     // A trace of every kernel (no label filter) is there to time each kernel on its own: it runs the
     // branches in turn.

@@ -67,6 +67,14 @@ struct KArgs {
     int x_bytes, w_bytes;   // sizes of the x and w tensors (both < 2 GiB, checked by the launcher)
     int w_krsc;             // filters are in KRSC order (else KCRS)
     int row_groups;         // CF = false: k runs over (c, r, groups of 4 taps), see the header
+    // Stacked convolution (Eq. (12): several filter banks on one input) whose filter ranges go to different tensors:
+    // filter m < split_end[0] goes to destination 0, m < split_end[1] to destination 1, ... (unused ends hold INT_MAX).
+    // Element (img, m, pix) of destination d lies at y_seg[d][(img * ctot_seg[d] + m) * P * Q + pix] (the host has
+    // folded the destination's channel offset and the range's first filter into y_seg).  nsplit <= 1: everything to y.
+    int nsplit;
+    int split_end[3];
+    float* y_seg[4];
+    int ctot_seg[4];
     float* part;            // partial sums [splits][K][Ng] of a split contraction, or NULL
     int splits, slices_per_split;
 };
@@ -437,6 +445,13 @@ __global__ __launch_bounds__(NT) void conv_f32_kernel(const KArgs a)
                     float o = acc[i][j][v] + (a.bias ? a.bias[m] : 0.f);
                     if (rbase) o += rbase[(size_t)m * PQ];
                     if (g.relu) o = fmaxf(o, 0.f);
+                    if (a.nsplit > 1) {
+                        const bool s1 = m >= a.split_end[0], s2 = m >= a.split_end[1], s3 = m >= a.split_end[2];
+                        float* base = s3 ? a.y_seg[3] : s2 ? a.y_seg[2] : s1 ? a.y_seg[1] : a.y_seg[0];
+                        const int ct = s3 ? a.ctot_seg[3] : s2 ? a.ctot_seg[2] : s1 ? a.ctot_seg[1] : a.ctot_seg[0];
+                        base[((size_t)img * ct + m) * PQ + pix] = o;
+                        continue;
+                    }
                     yb[(size_t)m * PQ] = o;
                 }
             }
@@ -515,7 +530,7 @@ int launch_tile(const KArgs& base, void* ws, size_t ws_bytes, hipStream_t st)
     a.splits = 1;
     const int nslices = contraction_slices<BK>(a.g, &a.row_groups);
     a.slices_per_split = nslices;
-    if (ws) {
+    if (ws && a.nsplit <= 1) {
         int per;
         const int splits = split_plan(a.grid_m * a.grid_n, nslices, &per);
         if (splits > 1 && (size_t)splits * a.g.K * a.g.Ng * sizeof(float) <= ws_bytes && ((uintptr_t)ws & 15) == 0) {
@@ -561,12 +576,26 @@ size_t conv_f32_scratch_bytes(const ConvGeom& g)
 }
 
 int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const float* bias, const float* residual,
-                    float* y, hipStream_t st, void* ws, size_t ws_bytes)
+                    float* y, hipStream_t st, void* ws, size_t ws_bytes, const ConvSplit* split)
 {
     TraceScope trace("conv_f32", &g, g.Ng, st);
     KArgs a;
     a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g;
     a.grid_m = a.grid_n = 0;
+    a.nsplit = 0;
+    for (int d = 0; d < 4; ++d) { a.y_seg[d] = nullptr; a.ctot_seg[d] = 0; if (d < 3) a.split_end[d] = 0x7FFFFFFF; }
+    if (split && split->n > 1) {
+        a.nsplit = split->n;
+        const long PQ = (long)g.P * g.Q;
+        int start = 0;
+        for (int d = 0; d < split->n && d < 4; ++d) {
+            const ConvDest& s = split->dst[d];
+            a.y_seg[d] = (float*)s.y + ((long)s.c_offset - start) * PQ;
+            a.ctot_seg[d] = s.ctot;
+            start += s.k;
+            if (d < 3 && d + 1 < split->n) a.split_end[d] = start;
+        }
+    }
     const size_t xb = (size_t)g.N * g.C * g.H * g.W * 4, wb = (size_t)g.K * g.Kg * 4;
     if (xb >= (1ull << 31) || wb >= (1ull << 31))
         return fail(DR_ERR_UNSUPPORTED, "conv_f32: input (%zu bytes) or filter tensor (%zu bytes) is 2 GiB or larger", xb, wb);

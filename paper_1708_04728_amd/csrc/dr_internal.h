@@ -51,8 +51,10 @@ struct ConvGeom {
 // ws (may be NULL): scratch of conv_f32_scratch_bytes(g) bytes, 16-byte aligned, which lets a layer with few
 // output tiles cut its contraction over several workgroups (see conv_f32.hip); too small = not used.
 size_t conv_f32_scratch_bytes(const ConvGeom& g);
+struct ConvSplit;
+// split (may be NULL): destinations of a stacked convolution, as for launch_conv_bf16_dma (no residual, no scratch then)
 int launch_conv_f32(const ConvGeom& g, const float* x, const float* w, const float* bias, const float* residual,
-                    float* y, hipStream_t st, void* ws = nullptr, size_t ws_bytes = 0);
+                    float* y, hipStream_t st, void* ws = nullptr, size_t ws_bytes = 0, const ConvSplit* split = nullptr);
 int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
                      const uint16_t* residual, uint16_t* y, hipStream_t st);
 

@@ -39,6 +39,38 @@ def test_inception_3a(form, mode, pack):
     assert rel_err(got, ref) < TOL_F32
 
 
+def _run_stacked(layer, params, x, mode, pack):
+    xg = G.to_device(x, "f32")
+    c_out = G._out_channels([layer], x.shape[1])
+    flat = G.stack_first_steps([layer], G.flat_params(params, "f32", pack=pack))
+    d = G.inception_desc(layer[1], x.shape[1], mode, pack)
+    ws = torch.empty(max(B.inception_workspace_bytes(xg, d), 256), dtype=torch.uint8, device="cuda")
+    y = torch.full((x.shape[0], c_out, x.shape[2], x.shape[3]), float("nan"), dtype=torch.float32, device="cuda")
+    B.inception_fwd(xg, d, flat[0::2], flat[1::2], y, ws)
+    torch.cuda.synchronize()
+    return host(y)
+
+
+@pytest.mark.parametrize("form", ["original", "slim"])
+@pytest.mark.parametrize("pack", [False, True])
+def test_inception_3a_stacked_first_steps_fp32(form, pack):
+    """DR_FUSE_STACK (Eq. (12)) on fp32 NCHW tensors: with the first-step 1x1 filters laid back to back they run as
+    one convolution whose filter ranges go to their own tensors.  Against the oracle on three images; and at
+    the full batch, where no contraction is cut over workgroups, bit for bit the result of one convolution per
+    branch (same products, same order), with and without the fused concat."""
+    layer = workloads.CONFIGS[2][form][0]
+    params = workloads.make_params(2, form)
+    base = B.DR_FUSE_RELU | B.DR_FUSE_CONCAT
+    x3 = workloads.make_input(2, 3)
+    ref = oracle.forward([layer], params, x3)
+    for mode in (base | B.DR_FUSE_STACK, B.DR_FUSE_RELU | B.DR_FUSE_STACK):
+        assert rel_err(_run_stacked(layer, params, x3, mode, pack), ref) < TOL_F32, (form, pack, mode)
+    x = workloads.make_input(2)
+    plain = run_inception(layer, params, x, base, pack=pack)
+    for mode in (base | B.DR_FUSE_STACK, B.DR_FUSE_RELU | B.DR_FUSE_STACK):
+        assert np.array_equal(_run_stacked(layer, params, x, mode, pack), plain), (form, pack, mode)
+
+
 @pytest.mark.parametrize("form", ["original", "slim"])
 def test_inception_branches_side_by_side_equal_branches_in_turn(form):
     """The branches of a module run on the library's own streams between a fork and a join on the caller's
