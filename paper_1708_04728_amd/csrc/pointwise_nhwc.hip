@@ -224,48 +224,51 @@ template <> __device__ __forceinline__ void unpack16<uint16_t>(const uint4& r, f
 
 template <typename T, int PR, int STRIDE>
 __global__ __launch_bounds__(256) void maxpool3_front_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int H, int W, int P,
-                                                             int Q, int pstrips, int qgroups, int bx_log2, int pad)
+                                                             int Q, int pstrips, int pgroups, unsigned cv_magic, unsigned qcv_magic, int pad)
 {
     constexpr int V = Store<T>::VN, NR = (PR - 1) * STRIDE + 3;
-    const int CV = C / V;
-    const int bx = 1 << bx_log2, by = 256 >> bx_log2;
-    const int tx = threadIdx.x & (bx - 1), ty = threadIdx.x >> bx_log2;
-    const unsigned qg = blockIdx.x % (unsigned)qgroups, t = blockIdx.x / (unsigned)qgroups;
-    const unsigned strip = t % (unsigned)pstrips, n = t / (unsigned)pstrips;
-    const int q = (int)qg * by + ty;
-    if (q >= Q) return;
+    const int CV = C / V, QCV = Q * CV;
+    // a thread owns one (strip of output rows, output column, channel vector) item of one image; the items are numbered
+    // strip by strip, column by column, which within a row is also their order in memory (channels-last): consecutive
+    // lanes touch consecutive 16-byte pieces whatever the channel count, and no lane idles except in an image's last
+    // workgroup.  (The magic numbers are ceil(2^32 / divisor); the launcher checks that the divisions are exact.)
+    const unsigned pg = blockIdx.x % (unsigned)pgroups, n = blockIdx.x / (unsigned)pgroups;
+    const int item = (int)pg * 256 + (int)threadIdx.x;
+    if (item >= pstrips * QCV) return;
+    const int strip = (int)__umulhi((unsigned)item, qcv_magic);
+    const int pair = item - strip * QCV;
+    const int q = (int)__umulhi((unsigned)pair, cv_magic);
+    const int cv = pair - q * CV;
     const int p0 = (int)strip * PR;
     const int w0 = q * STRIDE - pad, h0 = p0 * STRIDE - pad;
     const T* xb = x + (size_t)n * H * W * C;
     constexpr uint32_t NEG = NegInfWord<T>::v;
-    for (int cv = tx; cv < CV; cv += bx) {
-        uint4 raw[NR][3];
+    uint4 raw[NR][3];
 #pragma unroll
-        for (int r = 0; r < NR; ++r)
+    for (int r = 0; r < NR; ++r)
 #pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                raw[r][c] = make_uint4(NEG, NEG, NEG, NEG);
-                if ((unsigned)(h0 + r) < (unsigned)H && (unsigned)(w0 + c) < (unsigned)W)
-                    raw[r][c] = *reinterpret_cast<const uint4*>(xb + ((size_t)(h0 + r) * W + (w0 + c)) * C + cv * V);
-            }
-        float rm[NR][V];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            float a[V], b[V], c[V];
-            unpack16<T>(raw[r][0], a);
-            unpack16<T>(raw[r][1], b);
-            unpack16<T>(raw[r][2], c);
-#pragma unroll
-            for (int j = 0; j < V; ++j) rm[r][j] = fmaxf(fmaxf(a[j], b[j]), c[j]);
+        for (int c = 0; c < 3; ++c) {
+            raw[r][c] = make_uint4(NEG, NEG, NEG, NEG);
+            if ((unsigned)(h0 + r) < (unsigned)H && (unsigned)(w0 + c) < (unsigned)W)
+                raw[r][c] = *reinterpret_cast<const uint4*>(xb + ((size_t)(h0 + r) * W + (w0 + c)) * C + cv * V);
         }
+    float rm[NR][V];
 #pragma unroll
-        for (int i = 0; i < PR; ++i) {
-            if (p0 + i >= P) break;
-            float o[V];
+    for (int r = 0; r < NR; ++r) {
+        float a[V], b[V], c[V];
+        unpack16<T>(raw[r][0], a);
+        unpack16<T>(raw[r][1], b);
+        unpack16<T>(raw[r][2], c);
 #pragma unroll
-            for (int j = 0; j < V; ++j) o[j] = fmaxf(fmaxf(rm[i * STRIDE][j], rm[i * STRIDE + 1][j]), rm[i * STRIDE + 2][j]);
-            Store<T>::stv(y + (((size_t)n * P + p0 + i) * Q + q) * C + cv * V, o);
-        }
+        for (int j = 0; j < V; ++j) rm[r][j] = fmaxf(fmaxf(a[j], b[j]), c[j]);
+    }
+#pragma unroll
+    for (int i = 0; i < PR; ++i) {
+        if (p0 + i >= P) break;
+        float o[V];
+#pragma unroll
+        for (int j = 0; j < V; ++j) o[j] = fmaxf(fmaxf(rm[i * STRIDE][j], rm[i * STRIDE + 1][j]), rm[i * STRIDE + 2][j]);
+        Store<T>::stv(y + (((size_t)n * P + p0 + i) * Q + q) * C + cv * V, o);
     }
 }
 
@@ -285,12 +288,17 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
         // strips of 4 output rows (best in sweeps over the pooling layers of the networks here), 2 while the
         // launch would otherwise have fewer than ~2048 workgroups
         const long per_strip = (long)yd.n * qgroups;
-        if (vec && (p.stride_h == 1 || p.stride_h == 2)) {
+        const double qcv_d = (double)yd.w * cv;
+        if (vec && (p.stride_h == 1 || p.stride_h == 2) && qcv_d * qcv_d * yd.h < 4294967296.0) {   // (the kernel's divisions are exact then)
+            const int qcv = yd.w * cv;
+            const unsigned cv_magic = (unsigned)((0x100000000ull + cv - 1) / cv), qcv_magic = (unsigned)((0x100000000ull + qcv - 1) / qcv);
+            // workgroups per image for `strips_` strips
+            auto groups_for = [&](int strips_) { return (int)(((long)strips_ * qcv + 255) / 256); };
 #ifdef DR_TUNE
             if (const char* e = getenv("DR_POOL_PR")) {
                 const int pr = atoi(e), st_ = (yd.h + pr - 1) / pr;
-                const dim3 gt((unsigned)(per_strip * st_));
-#define DR_PT(PR, S) hipLaunchKernelGGL((maxpool3_front_kernel<T, PR, S>), gt, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, st_, qgroups, bx_log2, p.pad_h)
+                const dim3 gt((unsigned)((long)yd.n * groups_for(st_)));
+#define DR_PT(PR, S) hipLaunchKernelGGL((maxpool3_front_kernel<T, PR, S>), gt, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, st_, groups_for(st_), cv_magic, qcv_magic, p.pad_h)
                 if (p.stride_h == 1) { if (pr == 1) DR_PT(1, 1); else if (pr == 2) DR_PT(2, 1); else if (pr == 4) DR_PT(4, 1); else if (pr == 7) DR_PT(7, 1); else return fail(DR_ERR_UNSUPPORTED, "pr"); }
                 else { if (pr == 1) DR_PT(1, 2); else if (pr == 2) DR_PT(2, 2); else if (pr == 4) DR_PT(4, 2); else return fail(DR_ERR_UNSUPPORTED, "pr"); }
 #undef DR_PT
@@ -300,16 +308,17 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
             // strips of 7 rows for the 14 x 14 and 7 x 7 stride-1 layers (measured 10 % faster there than strips of 4)
             const bool seven = p.stride_h == 1 && yd.h % 7 == 0 && yd.h <= 14;
             const int PRF = p.stride_h == 1 ? (seven ? 7 : 4) : 2, strips = (yd.h + PRF - 1) / PRF;
-            const dim3 gf((unsigned)(per_strip * strips));
+            const int pgroups = groups_for(strips);
+            const dim3 gf((unsigned)((long)yd.n * pgroups));
             if (seven)
                 hipLaunchKernelGGL((maxpool3_front_kernel<T, 7, 1>), gf, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w,
-                                   strips, qgroups, bx_log2, p.pad_h);
+                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h);
             else if (p.stride_h == 1)
                 hipLaunchKernelGGL((maxpool3_front_kernel<T, 4, 1>), gf, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w,
-                                   strips, qgroups, bx_log2, p.pad_h);
+                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h);
             else
                 hipLaunchKernelGGL((maxpool3_front_kernel<T, 2, 2>), gf, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w,
-                                   strips, qgroups, bx_log2, p.pad_h);
+                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h);
             return check_launch("maxpool");
         }
         int PR = 4;
