@@ -293,6 +293,22 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
 int dr_net_set_timing(dr_net* net, int enabled);
 int dr_net_layer_times(dr_net* net, float* ms_per_layer, int n);
 
+/* The forward pass as a HIP graph.  dr_net_capture records what dr_net_fwd would enqueue for these arguments
+ * into a graph (nothing runs) and instantiates it; dr_graph_launch enqueues the whole forward on `stream` with one
+ * call.  For callers that run the same forward many times: the launches of a layer-by-layer network are short, and
+ * with DR_CONCURRENT_BRANCHES the graph also carries the branches' dependencies without the events between queues
+ * that the same mode costs when every kernel is launched by itself.  The graph holds the pointers it was captured
+ * with: x, the parameters, y and ws must stay allocated, their contents may change between launches (every launch
+ * reads them anew); two launches of one graph must not overlap in time (they share ws).  `stream` of dr_net_capture
+ * must be a stream the caller created (not the default stream); per-layer timing and a running kernel trace must
+ * be off (DR_ERR_UNSUPPORTED).  Capture and instantiation allocate host and device memory; a launch allocates
+ * nothing.  Errors of the layer list are reported as by dr_net_fwd. */
+typedef struct dr_graph dr_graph;
+int dr_net_capture(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params,
+                   const dr_tensor* yd, void* y, void* ws, size_t ws_bytes, void* stream, dr_graph** out);
+int dr_graph_launch(dr_graph* graph, void* stream);
+void dr_graph_destroy(dr_graph* graph);
+
 /* ---- measurement ---------------------------------------------------------------------------------- */
 
 /* One traced kernel launch.  label: kernel family ("conv_f32", "conv_bf16", "relu", "lrn", "maxpool",

@@ -114,6 +114,9 @@ _SIGNATURES = {
     "dr_net_output_desc": ([_vp, _P(dr_tensor), _P(dr_tensor)], _i),
     "dr_net_workspace_bytes": ([_vp, _P(dr_tensor), _P(_z)], _i),
     "dr_net_fwd": ([_vp, _P(dr_tensor), _vp, _P(_vp), _P(dr_tensor), _vp, _vp, _z, _vp], _i),
+    "dr_net_capture": ([_vp, _P(dr_tensor), _vp, _P(_vp), _P(dr_tensor), _vp, _vp, _z, _vp, _P(_vp)], _i),
+    "dr_graph_launch": ([_vp, _vp], _i),
+    "dr_graph_destroy": ([_vp], None),
     "dr_net_set_timing": ([_vp, _i], _i),
     "dr_net_layer_times": ([_vp, _P(_f), _i], _i),
     "dr_trace_begin": ([C.c_char_p, _i, _i, _i, _i], _i),
@@ -383,6 +386,21 @@ def trace_end(capacity=4096):
     return [(a.label.decode(), a.k, a.c, a.r, a.s, a.items, a.ms, a.bytes) for a in arr[:n.value]]
 
 
+class Graph:
+    """Owner of a dr_graph handle (a captured forward pass); keeps the tensors it was captured with alive."""
+
+    def __init__(self, handle, keep):
+        self._h, self._keep = handle, keep
+
+    def launch(self, stream=None):
+        _check(lib().dr_graph_launch(self._h, _stream(stream)))
+
+    def __del__(self):
+        if getattr(self, "_h", None) is not None and _lib is not None:
+            _lib.dr_graph_destroy(self._h)
+            self._h = None
+
+
 class Net:
     """Owner of a dr_net handle."""
 
@@ -419,6 +437,15 @@ class Net:
         _check(lib().dr_net_fwd(self._h, desc(x), _ptr(x), pp, desc(y), _ptr(y), _ptr(ws),
                                 0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
         return y
+
+    def capture(self, x, params, y, ws, stream):
+        """The forward for these tensors as a HIP graph (see dr_net_capture).  `stream`: a torch stream other than
+        the default one, used for the capture only.  The tensors must outlive the returned Graph."""
+        pp = (C.c_void_p * max(len(params), 1))(*[p.data_ptr() for p in params])
+        h = C.c_void_p()
+        _check(lib().dr_net_capture(self._h, desc(x), _ptr(x), pp, desc(y), _ptr(y), _ptr(ws),
+                                    0 if ws is None else ws.numel() * ws.element_size(), _stream(stream), C.byref(h)))
+        return Graph(h, (x, params, y, ws))
 
     def set_timing(self, enabled):
         _check(lib().dr_net_set_timing(self._h, int(enabled)))

@@ -1228,4 +1228,57 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
     return DR_OK;
 }
 
+struct dr_graph {
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+
+int dr_net_capture(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params, const dr_tensor* yd, void* y,
+                   void* ws, size_t ws_bytes, void* stream, dr_graph** out)
+{
+    const char* who = "dr_net_capture";
+    if (!out) return fail(DR_ERR_NULL, "%s: out is NULL", who);
+    *out = nullptr;
+    if (!net) return fail(DR_ERR_NULL, "%s: net is NULL", who);
+    if (!stream) return fail(DR_ERR_UNSUPPORTED, "%s: capture needs a stream the caller created, not the default stream", who);
+    if (net->timing) return fail(DR_ERR_UNSUPPORTED, "%s: per-layer timing is on", who);
+    if (g_trace.active) return fail(DR_ERR_UNSUPPORTED, "%s: a kernel trace is running", who);
+    // the streams and events of side-by-side branches are created on first use: not inside a capture
+    for (const dr_layer_desc& L : net->layers)
+        if (L.kind == DR_LAYER_INCEPTION && (L.inception.mode & DR_CONCURRENT_BRANCHES) && !branch_streams())
+            return fail(DR_ERR_HIP, "%s: cannot create the branch streams", who);
+    hipStream_t st = (hipStream_t)stream;
+    if (hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipStreamBeginCapture failed", who);
+    const int rc = dr_net_fwd(net, xd, x, params, yd, y, ws, ws_bytes, stream);
+    hipGraph_t g = nullptr;
+    const hipError_t e = hipStreamEndCapture(st, &g);
+    if (rc != DR_OK) {                       // dr_net_fwd's message stands
+        if (g) (void)hipGraphDestroy(g);
+        return rc;
+    }
+    if (e != hipSuccess || !g) return fail(DR_ERR_HIP, "%s: hipStreamEndCapture failed (%s)", who, hipGetErrorString(e));
+    hipGraphExec_t ex = nullptr;
+    if (hipGraphInstantiate(&ex, g, nullptr, nullptr, 0) != hipSuccess || !ex) {
+        (void)hipGraphDestroy(g);
+        return fail(DR_ERR_HIP, "%s: hipGraphInstantiate failed", who);
+    }
+    *out = new dr_graph{g, ex};
+    return DR_OK;
+}
+
+int dr_graph_launch(dr_graph* graph, void* stream)
+{
+    if (!graph) return fail(DR_ERR_NULL, "dr_graph_launch: graph is NULL");
+    if (hipGraphLaunch(graph->exec, (hipStream_t)stream) != hipSuccess) return fail(DR_ERR_HIP, "dr_graph_launch: hipGraphLaunch failed");
+    return DR_OK;
+}
+
+void dr_graph_destroy(dr_graph* graph)
+{
+    if (!graph) return;
+    (void)hipGraphExecDestroy(graph->exec);
+    (void)hipGraphDestroy(graph->graph);
+    delete graph;
+}
+
 }  // extern "C"

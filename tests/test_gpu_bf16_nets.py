@@ -197,6 +197,63 @@ def test_config5_googlenet_original_structure_fused():
     assert rel_err(got, plain) < TOL_BF16 * math.sqrt(5 + 18 + 2)
 
 
+@pytest.mark.parametrize("form", ["original", "slim"])
+def test_config5_googlenet_as_a_hip_graph(form):
+    """dr_net_capture / dr_graph_launch: the forward recorded once and replayed.  The original form is captured with
+    its branches side by side (streams joined by events inside the capture).  Every replay must give the bits of
+    the eager run, also with other work and synchronisations of the program between the replays and with new
+    input contents (the graph reads the buffers anew)."""
+    slim = form == "slim"
+    layers = workloads.CONFIGS[5][form]
+    params = workloads.make_params(5, form)
+    x = workloads.make_input(5, 3)
+    mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if slim else B.DR_CONCURRENT_BRANCHES
+    xg = G.to_device(x, "bf16", nhwc=True)
+    net = B.Net(G.net_descs(layers, 3, inception_mode=mode, fuse_relu=slim, pack="bf16"))
+    y = G.empty_like_desc(net.output_desc(B.desc(xg)))
+    ws = torch.empty(max(net.workspace_bytes(B.desc(xg)), 256), dtype=torch.uint8, device="cuda")
+    flat = G.flat_params(params, "bf16", pack=True)
+    if slim:
+        flat = G.stack_first_steps(layers, flat)
+    net.fwd(xg, flat, y, ws)
+    torch.cuda.synchronize()
+    yt = y.t if isinstance(y, B.NHWC) else y
+    eager = yt.clone()
+    side = torch.cuda.Stream()
+    graph = net.capture(xg, flat, y, ws, side)
+    torch.cuda.synchronize()
+    other = torch.empty_like(ws)
+    for rep in range(4):
+        yt.zero_()
+        ws.random_(0, 255)                      # scratch contents do not matter
+        other.copy_(ws)                         # the program's own work between the replays
+        torch.cuda.synchronize()
+        graph.launch()
+        torch.cuda.synchronize()
+        assert torch.equal(yt, eager), (form, rep)
+    # new contents in the captured input buffer: the replay follows them
+    x2 = workloads.round_to_bf16(x[::-1].copy())
+    xg.t.copy_(G.to_device(x2, "bf16", nhwc=True).t)
+    graph.launch()
+    torch.cuda.synchronize()
+    swapped = yt.clone()
+    net.fwd(xg, flat, y, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(yt, swapped)
+    assert torch.equal(swapped.flip(0), eager)
+    # what capture refuses
+    net.set_timing(True)
+    with pytest.raises(B.DeepRebirthError):
+        net.capture(xg, flat, y, ws, side)
+    net.set_timing(False)
+    with pytest.raises(B.DeepRebirthError):
+        net.capture(xg, flat, y, ws[:16], side)          # workspace too small: reported as by dr_net_fwd, capture ended
+    graph2 = net.capture(xg, flat, y, ws, side)          # ... and the stream can capture again
+    graph2.launch()
+    torch.cuda.synchronize()
+    assert torch.equal(yt, swapped)
+
+
 # ---- full sizes, in the launch configuration the benchmark times -------------------------------------------
 # The whole batch runs on the GPU; the oracle recomputes a few of the images (images are independent), and
 # properties that hold for every image are checked on all of them.
