@@ -304,6 +304,12 @@ int dr_net_layer_times(dr_net* net, float* ms_per_layer, int n);
  * be off (DR_ERR_UNSUPPORTED).  Capture and instantiation allocate host and device memory; a launch allocates
  * nothing.  Errors of the layer list are reported as by dr_net_fwd. */
 typedef struct dr_graph dr_graph;
+/* The general form: between dr_capture_begin and dr_capture_end every dr_* call that is given `stream` is recorded
+ * instead of run (several forwards, single layers, ...); dr_capture_end instantiates the recording (out = NULL:
+ * discards it).  Nothing else may be enqueued on `stream` in between, and dr_net_set_timing must be off for the
+ * networks recorded.  dr_net_capture is dr_capture_begin, dr_net_fwd, dr_capture_end. */
+int dr_capture_begin(void* stream);
+int dr_capture_end(void* stream, dr_graph** out);
 int dr_net_capture(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params,
                    const dr_tensor* yd, void* y, void* ws, size_t ws_bytes, void* stream, dr_graph** out);
 int dr_graph_launch(dr_graph* graph, void* stream);

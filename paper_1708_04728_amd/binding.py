@@ -115,6 +115,8 @@ _SIGNATURES = {
     "dr_net_workspace_bytes": ([_vp, _P(dr_tensor), _P(_z)], _i),
     "dr_net_fwd": ([_vp, _P(dr_tensor), _vp, _P(_vp), _P(dr_tensor), _vp, _vp, _z, _vp], _i),
     "dr_net_capture": ([_vp, _P(dr_tensor), _vp, _P(_vp), _P(dr_tensor), _vp, _vp, _z, _vp, _P(_vp)], _i),
+    "dr_capture_begin": ([_vp], _i),
+    "dr_capture_end": ([_vp, _P(_vp)], _i),
     "dr_graph_launch": ([_vp, _vp], _i),
     "dr_graph_destroy": ([_vp], None),
     "dr_net_set_timing": ([_vp, _i], _i),
@@ -399,6 +401,27 @@ class Graph:
         if getattr(self, "_h", None) is not None and _lib is not None:
             _lib.dr_graph_destroy(self._h)
             self._h = None
+
+
+class capture:
+    """with capture(stream) as c: ... dr_* calls given `stream` ...; then c.graph is the recorded Graph.  `keep`:
+    tensors the recording uses, kept alive with the graph."""
+
+    def __init__(self, stream, keep=()):
+        self.stream, self.keep, self.graph = stream, tuple(keep), None
+
+    def __enter__(self):
+        _check(lib().dr_capture_begin(_stream(self.stream)))
+        return self
+
+    def __exit__(self, exc_type, exc, tb):
+        if exc_type is not None:
+            lib().dr_capture_end(_stream(self.stream), None)
+            return False
+        h = C.c_void_p()
+        _check(lib().dr_capture_end(_stream(self.stream), C.byref(h)))
+        self.graph = Graph(h, self.keep)
+        return False
 
 
 class Net:

@@ -1233,28 +1233,28 @@ struct dr_graph {
     hipGraphExec_t exec;
 };
 
-int dr_net_capture(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params, const dr_tensor* yd, void* y,
-                   void* ws, size_t ws_bytes, void* stream, dr_graph** out)
+int dr_capture_begin(void* stream)
 {
-    const char* who = "dr_net_capture";
-    if (!out) return fail(DR_ERR_NULL, "%s: out is NULL", who);
-    *out = nullptr;
-    if (!net) return fail(DR_ERR_NULL, "%s: net is NULL", who);
+    const char* who = "dr_capture_begin";
     if (!stream) return fail(DR_ERR_UNSUPPORTED, "%s: capture needs a stream the caller created, not the default stream", who);
-    if (net->timing) return fail(DR_ERR_UNSUPPORTED, "%s: per-layer timing is on", who);
     if (g_trace.active) return fail(DR_ERR_UNSUPPORTED, "%s: a kernel trace is running", who);
     // the streams and events of side-by-side branches are created on first use: not inside a capture
-    for (const dr_layer_desc& L : net->layers)
-        if (L.kind == DR_LAYER_INCEPTION && (L.inception.mode & DR_CONCURRENT_BRANCHES) && !branch_streams())
-            return fail(DR_ERR_HIP, "%s: cannot create the branch streams", who);
-    hipStream_t st = (hipStream_t)stream;
-    if (hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipStreamBeginCapture failed", who);
-    const int rc = dr_net_fwd(net, xd, x, params, yd, y, ws, ws_bytes, stream);
+    if (!branch_streams()) return fail(DR_ERR_HIP, "%s: cannot create the branch streams", who);
+    if (hipStreamBeginCapture((hipStream_t)stream, hipStreamCaptureModeThreadLocal) != hipSuccess)
+        return fail(DR_ERR_HIP, "%s: hipStreamBeginCapture failed", who);
+    return DR_OK;
+}
+
+int dr_capture_end(void* stream, dr_graph** out)
+{
+    const char* who = "dr_capture_end";
+    if (out) *out = nullptr;
+    if (!stream) return fail(DR_ERR_UNSUPPORTED, "%s: no capture on the default stream", who);
     hipGraph_t g = nullptr;
-    const hipError_t e = hipStreamEndCapture(st, &g);
-    if (rc != DR_OK) {                       // dr_net_fwd's message stands
+    const hipError_t e = hipStreamEndCapture((hipStream_t)stream, &g);
+    if (!out) {                              // the caller gives the recording up
         if (g) (void)hipGraphDestroy(g);
-        return rc;
+        return e == hipSuccess ? DR_OK : fail(DR_ERR_HIP, "%s: hipStreamEndCapture failed (%s)", who, hipGetErrorString(e));
     }
     if (e != hipSuccess || !g) return fail(DR_ERR_HIP, "%s: hipStreamEndCapture failed (%s)", who, hipGetErrorString(e));
     hipGraphExec_t ex = nullptr;
@@ -1264,6 +1264,26 @@ int dr_net_capture(dr_net* net, const dr_tensor* xd, const void* x, const void* 
     }
     *out = new dr_graph{g, ex};
     return DR_OK;
+}
+
+int dr_net_capture(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params, const dr_tensor* yd, void* y,
+                   void* ws, size_t ws_bytes, void* stream, dr_graph** out)
+{
+    const char* who = "dr_net_capture";
+    if (!out) return fail(DR_ERR_NULL, "%s: out is NULL", who);
+    *out = nullptr;
+    if (!net) return fail(DR_ERR_NULL, "%s: net is NULL", who);
+    if (net->timing) return fail(DR_ERR_UNSUPPORTED, "%s: per-layer timing is on", who);
+    DR_TRY(dr_capture_begin(stream));
+    const int rc = dr_net_fwd(net, xd, x, params, yd, y, ws, ws_bytes, stream);
+    if (rc != DR_OK) {                       // dr_net_fwd's message stands
+        char msg[sizeof g_err];
+        snprintf(msg, sizeof msg, "%s", g_err);
+        (void)dr_capture_end(stream, nullptr);
+        snprintf(g_err, sizeof g_err, "%s", msg);
+        return rc;
+    }
+    return dr_capture_end(stream, out);
 }
 
 int dr_graph_launch(dr_graph* graph, void* stream)

@@ -126,6 +126,52 @@ def run_net(layers, params, x, dtype="f32", fuse_relu=False, inception_mode=0, f
     return (out, net.layer_times()) if timing else out
 
 
+def test_two_forwards_recorded_as_one_graph():
+    """dr_capture_begin / dr_capture_end: the original and the slim form of config 1's block, and a single layer
+    call, recorded together; the replay gives the bits of the calls made one by one, three times over with
+    other work in between."""
+    x = workloads.make_input(1)
+    xg = G.to_device(x, "f32")
+    nets, outs, wss, flats = [], [], [], []
+    for form in ("original", "slim"):
+        layers = workloads.CONFIGS[1][form]
+        net = B.Net(G.net_descs(layers, x.shape[1], fuse_relu=(form == "slim"), pack="f32"))
+        y = G.empty_like_desc(net.output_desc(B.desc(xg)))
+        ws = torch.empty(max(net.workspace_bytes(B.desc(xg)), 256), dtype=torch.uint8, device="cuda")
+        flat = G.flat_params(workloads.make_params(1, form), "f32", pack=True)
+        nets.append(net); outs.append(y); wss.append(ws); flats.append(flat)
+    r = torch.empty_like(outs[0])
+    for net, y, ws, flat in zip(nets, outs, wss, flats):
+        net.fwd(xg, flat, y, ws)
+    B.relu(outs[0], r)
+    torch.cuda.synchronize()
+    want = [outs[0].clone(), outs[1].clone(), r.clone()]
+    assert rel_err(host(outs[0]), oracle.forward(workloads.CONFIGS[1]["original"], workloads.make_params(1, "original"), x)) < TOL_F32
+    side = torch.cuda.Stream()
+    with B.capture(side, [xg, r] + outs + wss + flats) as c:
+        for net, y, ws, flat in zip(nets, outs, wss, flats):
+            net.fwd(xg, flat, y, ws, side)
+        B.relu(outs[0], r, side)
+    for rep in range(3):
+        for t in outs + [r]:
+            t.zero_()
+        torch.cuda.synchronize()
+        c.graph.launch()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(outs + [r], want)), rep
+    # a recording the caller gives up: the stream is usable again
+    with pytest.raises(ValueError):
+        with B.capture(side):
+            nets[0].fwd(xg, flats[0], outs[0], wss[0], side)
+            raise ValueError("changed my mind")
+    with B.capture(side) as c2:
+        nets[1].fwd(xg, flats[1], outs[1], wss[1], side)
+    outs[1].zero_()
+    c2.graph.launch()
+    torch.cuda.synchronize()
+    assert torch.equal(outs[1], want[1])
+
+
 @pytest.mark.parametrize("form,fuse", [("original", False), ("original", True), ("slim", True)])
 def test_config1_streamline_block(form, fuse):
     layers = workloads.CONFIGS[1][form]
