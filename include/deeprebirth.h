@@ -12,7 +12,8 @@
  *     fp32 accumulation and round-to-nearest-even on store.  Biases and BatchNorm vectors are
  *     always fp32.
  *   - Pointers named x, y, w, bias, ws, params[i] are DEVICE pointers owned by the caller; the
- *     library never allocates, frees or retains them.  Descriptor structs are HOST memory, read
+ *     library never allocates, frees or retains them (a recorded graph, see dr_capture_begin, is the one
+ *     exception: it keeps the addresses it was recorded with).  Descriptor structs are HOST memory, read
  *     during the call only.  x and y must not overlap unless an entry point says otherwise.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every entry point
  *     validates its arguments on the host first, then enqueues its kernels on `stream` and
