@@ -834,6 +834,44 @@ __global__ __launch_bounds__(256) void stem_pack_kernel(const uint16_t* __restri
     }
 }
 
+// The same copy, a workgroup per PACK_ROWS rows of xp: the input rows are fetched whole with 16-byte loads into LDS
+// (an input row of W * C bf16 values must be a multiple of 16 bytes, x 16-byte aligned) and the pixels are picked
+// out of LDS; two pixels of xp per thread and 16-byte store.  A quarter of the load instructions of the kernel above.
+constexpr int PACK_ROWS = 4;
+__global__ __launch_bounds__(256) void stem_pack_rows_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ xp, int C, int H, int W,
+                                                             int pad_h, int pad_w, int hp, int wp)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char pack_lds[];
+    const int row_bytes = W * C * 2, chunks = row_bytes >> 4, pairs = wp >> 1;
+    const int groups = (hp + PACK_ROWS - 1) / PACK_ROWS;
+    const int n = blockIdx.x / groups, yy0 = (blockIdx.x - n * groups) * PACK_ROWS;
+    for (int i = threadIdx.x; i < PACK_ROWS * chunks; i += blockDim.x) {
+        const int r = i / chunks, ch = i - r * chunks, yi = yy0 + r - pad_h;
+        if (yy0 + r < hp && (unsigned)yi < (unsigned)H)
+            *reinterpret_cast<uint4*>(pack_lds + r * row_bytes + ch * 16) =
+                *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(x) + ((size_t)n * H + yi) * row_bytes + ch * 16);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < PACK_ROWS * pairs; i += blockDim.x) {
+        const int r = i / pairs, pr = i - r * pairs, yy = yy0 + r, yi = yy - pad_h;
+        if (yy >= hp) continue;
+        uint32_t e[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+        if ((unsigned)yi < (unsigned)H) {
+            const uint16_t* row = reinterpret_cast<const uint16_t*>(pack_lds + r * row_bytes);
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int xi = 2 * pr + k - pad_w;
+                if ((unsigned)xi < (unsigned)W) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) e[4 * k + c] = c < C ? row[xi * C + c] : 0u;
+                }
+            }
+        }
+        *reinterpret_cast<uint4*>(xp + (((size_t)n * hp + yy) * wp + 2 * pr) * 4) =
+            make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
+}
+
 // wp8[k][r][s][c] (8 x 8 x 4 per filter) = w[k][c][r][s] (KCRS) or w[k][r][s][c] (KRSC) inside R x S x C, else 0
 __global__ __launch_bounds__(256) void stem_filters_kernel(const uint16_t* __restrict__ w, uint16_t* __restrict__ y, int K, int C, int R,
                                                            int S, int krsc)
@@ -854,6 +892,13 @@ int launch_stem_pack_bf16(const void* x, void* xp, int N, int C, int H, int W, i
     TraceScope trace("conv_pad", nullptr, (long long)((size_t)N * hp * wp * 4), st);
     const size_t total = (size_t)N * hp * wp;
     if (total == 0) return DR_OK;
+    const size_t row_bytes = (size_t)W * C * 2;
+    const size_t groups = (size_t)N * ((hp + PACK_ROWS - 1) / PACK_ROWS);
+    if (row_bytes % 16 == 0 && PACK_ROWS * row_bytes <= 48 * 1024 && aligned16(x) && aligned16(xp) && wp % 2 == 0 && groups < (1u << 31)) {
+        hipLaunchKernelGGL(stem_pack_rows_kernel, dim3((unsigned)groups), dim3(256), PACK_ROWS * row_bytes, st, (const uint16_t*)x,
+                           (uint16_t*)xp, C, H, W, pad_h, pad_w, hp, wp);
+        return check_launch("stem_pack");
+    }
     hipLaunchKernelGGL(stem_pack_kernel, dim3(blocks_for(total, 256, 256 * 64)), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)xp, C, H, W,
                        pad_h, pad_w, hp, wp, total);
     return check_launch("stem_pack");

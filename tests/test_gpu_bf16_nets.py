@@ -300,6 +300,9 @@ def test_config4_resnet_stage_full_batch_sampled():
     (1, 4, 20, 20, 72, 5, 2, 2),     # four channels, 5x5
     (2, 3, 12, 14, 16, 3, 1, 1),     # odd column stride: channels padded to 8 instead
     (1, 6, 9, 9, 32, 3, 2, 1),       # six channels: padded to 8
+    (2, 3, 33, 32, 64, 7, 2, 3),     # input rows a multiple of 16 bytes: the 4-channel copy goes through LDS, row by row
+    (1, 3, 21, 24, 24, 7, 4, 3),     # the same at stride 4, number of rows not a multiple of the rows per workgroup
+    (3, 1, 13, 16, 40, 3, 2, 0),     # the same with one channel, no padding
 ])
 def test_small_channel_first_layer_through_net(case):
     """Convolutions on inputs with fewer than 8 channels take copies with padded channels inside dr_net_fwd
