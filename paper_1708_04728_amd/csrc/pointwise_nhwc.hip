@@ -224,15 +224,22 @@ template <> __device__ __forceinline__ void unpack16<uint16_t>(const uint4& r, f
 
 template <typename T, int PR, int STRIDE>
 __global__ __launch_bounds__(256) void maxpool3_front_kernel(const T* __restrict__ x, T* __restrict__ y, int C, int H, int W, int P,
-                                                             int Q, int pstrips, int pgroups, unsigned cv_magic, unsigned qcv_magic, int pad)
+                                                             int Q, int pstrips, int pgroups, unsigned cv_magic, unsigned qcv_magic, int pad,
+                                                             unsigned blocks)
 {
     constexpr int V = Store<T>::VN, NR = (PR - 1) * STRIDE + 3;
     const int CV = C / V, QCV = Q * CV;
+    // Workgroups go to the device's 8 dies in turn (workgroup b to die b % 8), each die with an L2 of its own.  The
+    // workgroups are renumbered so that a die works on one contiguous eighth of the tensor: the rows two neighbouring
+    // strips share and the columns two neighbouring workgroups share are then fetched into one L2 instead of two.
+    // (The launcher rounds the grid up to a multiple of 8; the surplus workgroups leave here.)
+    const unsigned block = (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (block >= blocks) return;
     // a thread owns one (strip of output rows, output column, channel vector) item of one image; the items are numbered
     // strip by strip, column by column, which within a row is also their order in memory (channels-last): consecutive
     // lanes touch consecutive 16-byte pieces whatever the channel count, and no lane idles except in an image's last
     // workgroup.  (The magic numbers are ceil(2^32 / divisor); the launcher checks that the divisions are exact.)
-    const unsigned pg = blockIdx.x % (unsigned)pgroups, n = blockIdx.x / (unsigned)pgroups;
+    const unsigned pg = block % (unsigned)pgroups, n = block / (unsigned)pgroups;
     const int item = (int)pg * 256 + (int)threadIdx.x;
     if (item >= pstrips * QCV) return;
     const int strip = (int)__umulhi((unsigned)item, qcv_magic);
@@ -296,29 +303,31 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
             auto groups_for = [&](int strips_) { return (int)(((long)strips_ * qcv + 255) / 256); };
 #ifdef DR_TUNE
             if (const char* e = getenv("DR_POOL_PR")) {
-                const int pr = atoi(e), st_ = (yd.h + pr - 1) / pr;
+                const int pr = atoi(e) > 0 ? atoi(e) : 1, st_ = (yd.h + pr - 1) / pr;
                 const dim3 gt((unsigned)((long)yd.n * groups_for(st_)));
-#define DR_PT(PR, S) hipLaunchKernelGGL((maxpool3_front_kernel<T, PR, S>), gt, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, st_, groups_for(st_), cv_magic, qcv_magic, p.pad_h)
-                if (p.stride_h == 1) { if (pr == 1) DR_PT(1, 1); else if (pr == 2) DR_PT(2, 1); else if (pr == 4) DR_PT(4, 1); else if (pr == 7) DR_PT(7, 1); else return fail(DR_ERR_UNSUPPORTED, "pr"); }
-                else { if (pr == 1) DR_PT(1, 2); else if (pr == 2) DR_PT(2, 2); else if (pr == 4) DR_PT(4, 2); else return fail(DR_ERR_UNSUPPORTED, "pr"); }
+#define DR_PT(PR, S) hipLaunchKernelGGL((maxpool3_front_kernel<T, PR, S>), dim3((gt.x + 7) / 8 * 8), dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, st_, groups_for(st_), cv_magic, qcv_magic, p.pad_h, gt.x)
+                bool done = true;
+                if (p.stride_h == 1) { if (pr == 1) DR_PT(1, 1); else if (pr == 2) DR_PT(2, 1); else if (pr == 4) DR_PT(4, 1); else if (pr == 7) DR_PT(7, 1); else done = false; }
+                else { if (pr == 1) DR_PT(1, 2); else if (pr == 2) DR_PT(2, 2); else if (pr == 4) DR_PT(4, 2); else done = false; }
 #undef DR_PT
-                return check_launch("maxpool");
+                if (done) return check_launch("maxpool");
             }
 #endif
             // strips of 7 rows for the 14 x 14 and 7 x 7 stride-1 layers (measured 10 % faster there than strips of 4)
             const bool seven = p.stride_h == 1 && yd.h % 7 == 0 && yd.h <= 14;
             const int PRF = p.stride_h == 1 ? (seven ? 7 : 4) : 2, strips = (yd.h + PRF - 1) / PRF;
             const int pgroups = groups_for(strips);
-            const dim3 gf((unsigned)((long)yd.n * pgroups));
+            const unsigned blocks = (unsigned)((long)yd.n * pgroups);
+            const dim3 gf((blocks + 7) / 8 * 8);        // a multiple of 8: see the kernel's renumbering
             if (seven)
                 hipLaunchKernelGGL((maxpool3_front_kernel<T, 7, 1>), gf, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w,
-                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h);
+                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h, blocks);
             else if (p.stride_h == 1)
                 hipLaunchKernelGGL((maxpool3_front_kernel<T, 4, 1>), gf, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w,
-                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h);
+                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h, blocks);
             else
                 hipLaunchKernelGGL((maxpool3_front_kernel<T, 2, 2>), gf, dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w,
-                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h);
+                                   strips, pgroups, cv_magic, qcv_magic, p.pad_h, blocks);
             return check_launch("maxpool");
         }
         int PR = 4;
