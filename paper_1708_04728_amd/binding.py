@@ -341,7 +341,7 @@ def inception_workspace_bytes(x, idesc):
 
 def inception_fwd(x, idesc, weights, biases, y, ws, stream=None):
     nw = len(weights)
-    wp = (C.c_void_p * nw)(*[w.data_ptr() for w in weights])
+    wp = (C.c_void_p * nw)(*[0 if w is None else w.data_ptr() for w in weights])
     bp = (C.c_void_p * nw)(*[0 if b is None else b.data_ptr() for b in biases])
     _check(lib().dr_inception_fwd(desc(x), _ptr(x), idesc, wp, bp, desc(y), _ptr(y), _ptr(ws),
                                   0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))

@@ -7,6 +7,7 @@
 
 #include <new>
 #include <algorithm>
+#include <atomic>
 #include <vector>
 
 #include "dr_internal.h"
@@ -24,15 +25,17 @@ int fail(int code, const char* fmt, ...)
     return code;
 }
 
+// compute units of the current device (asked once per device; 256 if the runtime will not say)
 int device_cus()
 {
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-        else cus = 256;
-    }
-    return cus;
+    constexpr int MAX_DEV = 64;
+    static std::atomic<int> cus[MAX_DEV];
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return 256;
+    if ((v = cus[dev].load(std::memory_order_relaxed)) > 0) return v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    cus[dev].store(v, std::memory_order_relaxed);
+    return v;
 }
 
 int check_launch(const char* what)
@@ -314,7 +317,7 @@ int inception_validate(const dr_tensor& xd, const dr_inception& d, dr_tensor* ou
 // priority, never destroyed.  Events are handed out round-robin: a wait refers to the record that
 // preceded it, so an event can be recorded again once its wait has been enqueued.
 struct BranchStreams {
-    int dev = -1;
+    bool ready = false;
     hipStream_t s[DR_MAX_BRANCHES - 1];
     hipEvent_t ev[64];
     unsigned next = 0;
@@ -322,15 +325,17 @@ struct BranchStreams {
 };
 BranchStreams* branch_streams()
 {
-    static thread_local BranchStreams pool;
+    constexpr int MAX_DEV = 16;                      // devices of one process that can run branches side by side
+    static thread_local BranchStreams pools[MAX_DEV];
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
-    if (pool.dev != dev) {
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
+    BranchStreams& pool = pools[dev];
+    if (!pool.ready) {
         for (auto& s : pool.s)
             if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) return nullptr;
         for (auto& e : pool.ev)
             if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
-        pool.dev = dev;
+        pool.ready = true;
     }
     return &pool;
 }
@@ -440,6 +445,21 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
         if (hipEventRecord(fork, main_st) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipEventRecord failed", who);
     }
     SharedDeviceScope shared(bs != nullptr);
+    // Every side stream that has been made to wait for the fork is joined to the caller's stream again, also when
+    // the module fails half-way: the caller's stream (or a capture in progress) is never left with loose ends.
+    struct Join {
+        BranchStreams* bs;
+        hipStream_t main;
+        bool pending[DR_MAX_BRANCHES] = {};
+        ~Join()
+        {
+            for (int b = 1; bs && b < DR_MAX_BRANCHES; ++b) {
+                if (!pending[b]) continue;
+                const hipEvent_t e = bs->event();
+                if (hipEventRecord(e, bs->s[b - 1]) == hipSuccess) (void)hipStreamWaitEvent(main, e, 0);
+            }
+        }
+    } join{bs, main_st};
     for (int b = 0; b < d.n_branches; ++b) {
         const dr_branch& br = d.branches[b];
         dr_tensor t = xd;
@@ -447,6 +467,7 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
         const bool side = bs && b > 0;
         const hipStream_t st = side ? bs->s[b - 1] : main_st;
         if (side && hipStreamWaitEvent(st, fork, 0) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipStreamWaitEvent failed", who);
+        join.pending[b] = side;
         for (int s = 0; s < br.n_steps; ++s) {
             const dr_step& stp = br.steps[s];
             const bool last = s == br.n_steps - 1;
@@ -486,6 +507,7 @@ int inception_run(const dr_tensor& xd, const void* x, const dr_inception& d, Par
             const hipEvent_t done = bs->event();
             if (hipEventRecord(done, st) != hipSuccess || hipStreamWaitEvent(main_st, done, 0) != hipSuccess)
                 return fail(DR_ERR_HIP, "%s: joining branch %d failed", who, b);
+            join.pending[b] = false;
         }
     }
     if (nseg && !ar.measure) DR_TRY(launch_concat(yd, nseg, segs, y, main_st));

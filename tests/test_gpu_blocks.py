@@ -221,3 +221,40 @@ def test_config3_alexnet_front_full_batch_sampled():
         got = run_net(layers, params, x, fuse_relu=fuse)
         assert got.shape[0] == 128 and np.isfinite(got).all() and (got >= 0).all()
         assert rel_err(got[pick], oracle.forward(layers, params, x[pick])) < TOL_F32
+
+
+def test_module_that_fails_half_way_leaves_no_loose_ends():
+    """Branches side by side (DR_CONCURRENT_BRANCHES): a module that fails after some branches have been started (a
+    missing filter pointer in the last branch) reports the error with every started branch joined to the caller's
+    stream again: the same stream then runs the module correctly, and a recording that met the error can be given
+    up and started anew."""
+    layer = workloads.CONFIGS[2]["original"][0]
+    params = workloads.make_params(2, "original")
+    x = workloads.make_input(2, 3)
+    ref = oracle.forward([layer], params, x)
+    mode = B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_CONCURRENT_BRANCHES
+    xg = G.to_device(x, "f32")
+    d = G.inception_desc(layer[1], x.shape[1], mode, False)
+    ws = torch.empty(max(B.inception_workspace_bytes(xg, d), 256), dtype=torch.uint8, device="cuda")
+    y = torch.full(ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    flat = G.flat_params(params, "f32", pack=False)
+    weights, biases = list(flat[0::2]), list(flat[1::2])
+    broken = weights[:-1] + [None]
+    side = torch.cuda.Stream()
+    with pytest.raises(B.DeepRebirthError) as e:
+        B.inception_fwd(xg, d, broken, biases, y, ws, side)
+    assert e.value.code == B.DR_ERR_NULL
+    B.inception_fwd(xg, d, weights, biases, y, ws, side)
+    side.synchronize()
+    assert rel_err(host(y), ref) < TOL_F32
+    with pytest.raises(B.DeepRebirthError):
+        with B.capture(side):
+            B.inception_fwd(xg, d, broken, biases, y, ws, side)
+    with B.capture(side, [xg, y, ws] + flat) as c:
+        B.inception_fwd(xg, d, weights, biases, y, ws, side)
+    for rep in range(2):
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        c.graph.launch()
+        torch.cuda.synchronize()
+        assert rel_err(host(y), ref) < TOL_F32
