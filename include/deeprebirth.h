@@ -222,7 +222,9 @@ typedef struct { int n_steps; dr_step steps[DR_MAX_STEPS]; } dr_branch;
 #define DR_CONCURRENT_BRANCHES 8 /* branches 1.. run on streams the library owns (per host thread and
                               device, created on first use, default priority), forked from the caller's
                               stream by an event before the module and joined to it by events before the
-                              concat: to the caller the module is still one piece of work on `stream`.
+                              concat: to the caller the module is still one piece of work on `stream`,
+                              also when the call returns an error after some branches have been started
+                              (they are joined before it returns).  Devices 0..15 of a process.
                               Without it the branches run one after another on the caller's stream.
                               Pays when a module's kernels are long next to the cost of the events
                               (several microseconds per fork / join) and leave compute units idle */
