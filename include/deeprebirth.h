@@ -164,7 +164,9 @@ int dr_fold_bn(int k, size_t crs, const float* w, const float* b, const float* g
 int dr_avgpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_tensor* yd, void* y, void* stream);
 
 /* Inner-product layer (a tensor layer, Sec. 1): y[n,o] = bias[o] + sum_i w[o,i] x[n,i], with
- * i running over c*h*w of xd.  yd = {n, out, 1, 1}.  w: out x (c*h*w), dtype of x. */
+ * i running over (c, h, w) of xd in that order.  yd = {n, out, 1, 1}.  w: out x (c*h*w), dtype of x.
+ * A DR_NHWC input whose map is larger than 1x1 is refused (DR_ERR_UNSUPPORTED): its memory order
+ * is (h, w, c), not the order of i. */
 int dr_fc_fwd(const dr_tensor* xd, const void* x, const void* w, const float* bias, const dr_tensor* yd, void* y,
               void* stream);
 

@@ -331,10 +331,24 @@ BranchStreams* branch_streams()
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return nullptr;
     BranchStreams& pool = pools[dev];
     if (!pool.ready) {
-        for (auto& s : pool.s)
-            if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        for (auto& e : pool.ev)
-            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        // all or nothing: what a failed attempt had created is released again, and the next call starts afresh
+        int ns = 0, ne = 0;
+        bool ok = true;
+        for (auto& s : pool.s) {
+            if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) { ok = false; break; }
+            ++ns;
+        }
+        for (auto& e : pool.ev) {
+            if (!ok) break;
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { ok = false; break; }
+            ++ne;
+        }
+        if (!ok) {
+            for (int i = 0; i < ne; ++i) (void)hipEventDestroy(pool.ev[i]);
+            for (int i = 0; i < ns; ++i) (void)hipStreamDestroy(pool.s[i]);
+            (void)hipGetLastError();
+            return nullptr;
+        }
         pool.ready = true;
     }
     return &pool;
@@ -634,6 +648,8 @@ int layer_out(const dr_layer_desc& L, const dr_tensor& t, dr_tensor* o)
         return DR_OK;
     case DR_LAYER_FC:
         if (L.fc_out < 1) return fail(DR_ERR_SHAPE, "%s: fc_out %d", who, L.fc_out);
+        // the inner product pairs w[o][i] with x[n][i], i running over (c, h, w): memory order only for NCHW or a 1x1 map
+        if (t.layout == DR_NHWC && t.h * t.w > 1) return fail(DR_ERR_UNSUPPORTED, "%s: inner product on a channels-last %dx%d map", who, t.h, t.w);
         *o = dr_tensor{t.n, L.fc_out, 1, 1, t.dtype, t.layout};
         return DR_OK;
     case DR_LAYER_SOFTMAX:
@@ -961,6 +977,8 @@ int dr_fc_fwd(const dr_tensor* xd, const void* x, const void* w, const float* bi
     if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
     if (yd->n != xd->n || yd->h != 1 || yd->w != 1) return fail(DR_ERR_SHAPE, "%s: output must be {n, out, 1, 1}", who);
     if (yd->dtype != xd->dtype) return fail(DR_ERR_UNSUPPORTED, "%s: input and output dtypes differ", who);
+    // i runs over (c, h, w): that is the tensor's memory order only for NCHW, or for any layout when the map is 1x1
+    if (xd->layout == DR_NHWC && xd->h * xd->w > 1) return fail(DR_ERR_UNSUPPORTED, "%s: channels-last input with a %dx%d map", who, xd->h, xd->w);
     return launch_fc(xd->dtype, x, w, bias, y, xd->n, xd->c * xd->h * xd->w, yd->c, (hipStream_t)stream);
 }
 

@@ -38,9 +38,6 @@
 #include <type_traits>
 
 #include "dr_internal.h"
-#ifdef DR_TUNE
-#include <stdlib.h>
-#endif
 
 namespace dr {
 namespace {
@@ -635,44 +632,6 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
             }
         }
     }
-#ifdef DR_TUNE
-    if (const char* e = getenv("DR_BF16_CFG")) {
-        switch (atoi(e)) {
-        case 1: return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);   // 32 x 256
-        case 2: return launch_cfg<1, 2, 1, 4, 3, 1>(a, st);
-        case 3: return launch_cfg<2, 2, 1, 4, 3, 1>(a, st);   // 64 x 256
-        case 4: return launch_cfg<2, 2, 1, 4, 2, 1>(a, st);
-        case 5: return launch_cfg<2, 4, 2, 2, 3, 1>(a, st);   // 128 x 256
-        case 6: return launch_cfg<2, 2, 2, 2, 4, 1>(a, st);   // 128 x 128
-        case 7: return launch_cfg<2, 2, 2, 2, 2, 2>(a, st);
-        case 8: return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);   // 64 x 128
-        case 9: return launch_cfg<2, 1, 1, 4, 2, 3>(a, st);
-        case 10: return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);  // 32 x 128
-        case 11: return launch_cfg<2, 1, 1, 4, 2, 2>(a, st);
-        case 12: return launch_cfg<4, 2, 1, 4, 2, 1>(a, st);  // 128 x 256, wave tile 128 x 64
-        case 13: return launch_cfg<6, 1, 1, 4, 2, 1>(a, st);  // 192 x 128
-        case 14: return launch_cfg<3, 2, 1, 4, 2, 1>(a, st);  // 96 x 256
-        case 15: return launch_cfg<4, 1, 1, 4, 2, 2>(a, st);  // 128 x 128, wave tile 128 x 32
-        case 16: return launch_cfg<3, 1, 1, 4, 2, 2>(a, st);  // 96 x 128
-        case 17: return launch_cfg<1, 1, 1, 4, 3, 2>(a, st);  // 32 x 128, deeper rings
-        case 18: return launch_cfg<1, 1, 1, 4, 6, 1>(a, st);
-        case 19: return launch_cfg<1, 1, 2, 2, 4, 2>(a, st);  // 64 x 64
-        case 20: return launch_cfg<1, 1, 2, 2, 3, 3>(a, st);
-        case 21: return launch_cfg<1, 1, 2, 2, 6, 1>(a, st);
-        case 22: return launch_cfg<2, 1, 1, 4, 4, 1>(a, st);  // 64 x 128, deeper rings
-        case 23: return launch_cfg<2, 1, 1, 4, 6, 1>(a, st);
-        case 24: return launch_cfg<1, 2, 1, 4, 4, 1>(a, st);  // 32 x 256, deeper ring
-        case 30: return launch_cfg<3, 2, 2, 4, 2, 1>(a, st);  // 8 waves: 192 x 256, 96 x 64 per wave
-        case 31: return launch_cfg<2, 2, 2, 4, 2, 1>(a, st);  // 8 waves: 128 x 256, 64 x 64 per wave
-        case 32: return launch_cfg<2, 2, 4, 2, 2, 1>(a, st);  // 8 waves: 256 x 128
-        case 33: return launch_cfg<3, 1, 2, 4, 2, 1>(a, st);  // 8 waves: 192 x 128, 96 x 32 per wave
-        case 34: return launch_cfg<2, 2, 2, 4, 3, 1>(a, st);  // 8 waves: 128 x 256, three stages
-        case 35: return launch_cfg<1, 2, 2, 4, 2, 1>(a, st);  // 8 waves: 64 x 256, 32 x 64 per wave
-        case 36: return launch_cfg<2, 1, 2, 4, 2, 1>(a, st);  // 8 waves: 128 x 128, 64 x 32 per wave
-        default: break;
-        }
-    }
-#endif
     return launch_auto(a, st);
 }
 

@@ -3,7 +3,6 @@
 // group of channels (8 bf16 or 4 fp32) of one pixel and consecutive lanes walk the channel axis:
 // every access is a coalesced 16-byte vector, window neighbours are whole vectors, and the
 // cross-channel LRN window is completed with wavefront shuffles from the neighbouring lanes.
-#include <stdlib.h>
 #include <type_traits>
 #include <utility>
 
@@ -301,18 +300,6 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
             const unsigned cv_magic = (unsigned)((0x100000000ull + cv - 1) / cv), qcv_magic = (unsigned)((0x100000000ull + qcv - 1) / qcv);
             // workgroups per image for `strips_` strips
             auto groups_for = [&](int strips_) { return (int)(((long)strips_ * qcv + 255) / 256); };
-#ifdef DR_TUNE
-            if (const char* e = getenv("DR_POOL_PR")) {
-                const int pr = atoi(e) > 0 ? atoi(e) : 1, st_ = (yd.h + pr - 1) / pr;
-                const dim3 gt((unsigned)((long)yd.n * groups_for(st_)));
-#define DR_PT(PR, S) hipLaunchKernelGGL((maxpool3_front_kernel<T, PR, S>), dim3((gt.x + 7) / 8 * 8), dim3(256), 0, st, (const T*)x, (T*)y, xd.c, xd.h, xd.w, yd.h, yd.w, st_, groups_for(st_), cv_magic, qcv_magic, p.pad_h, gt.x)
-                bool done = true;
-                if (p.stride_h == 1) { if (pr == 1) DR_PT(1, 1); else if (pr == 2) DR_PT(2, 1); else if (pr == 4) DR_PT(4, 1); else if (pr == 7) DR_PT(7, 1); else done = false; }
-                else { if (pr == 1) DR_PT(1, 2); else if (pr == 2) DR_PT(2, 2); else if (pr == 4) DR_PT(4, 2); else done = false; }
-#undef DR_PT
-                if (done) return check_launch("maxpool");
-            }
-#endif
             // strips of 7 rows for the 14 x 14 and 7 x 7 stride-1 layers (measured 10 % faster there than strips of 4)
             const bool seven = p.stride_h == 1 && yd.h % 7 == 0 && yd.h <= 14;
             const int PRF = p.stride_h == 1 ? (seven ? 7 : 4) : 2, strips = (yd.h + PRF - 1) / PRF;

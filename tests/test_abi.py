@@ -71,6 +71,10 @@ def test_argument_validation_runs_before_any_launch():
     assert L.dr_concat(2, xds, ptrs, _t(1, 6, 4, 4), fake, None) == B.DR_ERR_SHAPE
     assert L.dr_concat(9, xds, ptrs, _t(1, 5, 4, 4), fake, None) == B.DR_ERR_SHAPE
     assert L.dr_softmax_fwd(_t(2, 10, 2, 1), fake, fake, None) == B.DR_ERR_SHAPE
+    # inner product: i runs over (c, h, w), which a channels-last map larger than 1x1 does not store in that order
+    nhwc = B.dr_tensor(2, 8, 3, 3, B.DR_F32, B.DR_NHWC)
+    assert L.dr_fc_fwd(nhwc, fake, fake, None, _t(2, 5, 1, 1), fake, None) == B.DR_ERR_UNSUPPORTED
+    assert "channels-last" in B.last_error()
 
 
 def test_sizes_beyond_the_kernels_index_range_are_refused_on_the_host():

@@ -242,6 +242,96 @@ def test_bottleneck_fold_matches_original_in_fp64():
     assert (y0 >= 0).all() and (y0 > 0).any()
 
 
+def _bn_of(q, y, eps):
+    return oracle.bn(y, q["gamma"], q["beta"], q["mean"], q["var"], eps)
+
+
+def _manual_bottleneck(x, q, project, eps, fold, rnd):
+    """Sec. 4.2's bottleneck written out call by call from the single-layer oracle functions: main path 1x1 -> 3x3
+    (pad 1) -> 1x1, each followed by BN(+Scale), a ReLU after the first two; shortcut = x, or conv1x1 + BN of x on a
+    projection block; output = ReLU(main + shortcut).  q: the block's parameter dicts in workload order (conv a, bn a,
+    conv b, bn b, conv c, bn c[, conv p, bn p]).  fold: each conv+BN pair as the one conv of Lemma 2.
+    rnd: applied to every tensor a layer leaves in memory -- in the original form after each conv, BN and the
+    final add (ReLU of a rounded value is exact); in the folded form the only layers left are the tensor layers,
+    each with what was merged into it (its ReLU; for the last one the shortcut sum and its ReLU), so there is one
+    rounding per conv."""
+    def unit(inp, i, pad, relu_after, last_with=None):
+        cq, bq = q[i], q[i + 1]
+        if fold:
+            wf, bf = oracle.fold_bn(cq["w"], cq["b"], bq["gamma"], bq["beta"], bq["mean"], bq["var"], eps)
+            y = oracle.conv2d(inp, wf, bf, 1, pad)
+            if last_with is not None:
+                return rnd(oracle.add_relu(y, last_with))
+            return rnd(oracle.relu(y) if relu_after else y)
+        y = rnd(oracle.conv2d(inp, cq["w"], cq["b"], 1, pad))
+        y = rnd(_bn_of(bq, y, eps))
+        if last_with is not None:
+            return rnd(oracle.add_relu(y, last_with))
+        return oracle.relu(y) if relu_after else y
+    a = unit(x, 0, 0, True)
+    b = unit(a, 2, 1, True)
+    sc = unit(x, 6, 0, False) if project else x
+    return unit(b, 4, 0, False, last_with=sc)
+
+
+@pytest.mark.parametrize("project", [True, False])
+@pytest.mark.parametrize("fold", [False, True])
+@pytest.mark.parametrize("mirror", [False, True])
+def test_bottleneck_against_manual_chain(project, fold, mirror):
+    # an asymmetric block (mid != in != out unless identity) so that swapped operands or a wrong shortcut show
+    cin, mid, out = (10, 6, 14) if project else (14, 6, 14)
+    layers = [workloads.bottleneck(mid, out, project)]
+    q = []
+    workloads._walk(np.random.default_rng(77), layers, cin, "bf16" if mirror else "f32", q)
+    x = np.abs(rng.standard_normal((2, cin, 5, 6)))
+    if mirror:
+        x = oracle.round_bf16(x)
+    rnd = oracle.round_bf16 if mirror else (lambda a: a)
+    want = _manual_bottleneck(x, q, project, workloads.BN_EPS, fold, rnd)
+    got = oracle.forward(layers, q, x, mirror_bf16=mirror, fold=fold)
+    assert got.shape == (2, out, 5, 6)
+    assert np.array_equal(got, want)
+    # the chain is sensitive to what it pins: dropping the middle ReLU or taking the shortcut from the wrong tensor changes it
+    assert (want > 0).any() and (want == 0).any()
+    if mirror:
+        exact = oracle.forward(layers, q, x, fold=fold)
+        assert not np.array_equal(got, exact) and np.abs(got - exact).max() < 0.1 * np.abs(exact).max()
+        assert np.array_equal(oracle.round_bf16(got), got)          # what is stored is representable
+
+
+def test_mirrored_forward_rounds_after_every_stored_layer():
+    """bf16 storage rule: every tensor a layer writes is rounded once (nearest even); arithmetic inside a layer is exact
+    fp64.  Pinned on a conv -> ReLU -> LRN -> pool -> conv -> ReLU -> avgpool -> fc -> softmax chain written out by hand."""
+    R = oracle.round_bf16
+    layers = [workloads.conv(6, 3, 1, 1), ("relu", {}), workloads.lrn(), workloads.maxpool(3, 2),
+              workloads.conv(5, 1), ("relu", {}), ("avgpool", {"k": 3}), ("fc", {"out": 4}), ("softmax", {})]
+    q = []
+    workloads._walk(np.random.default_rng(5), layers, 3, "bf16", q)
+    x = R(rng.standard_normal((2, 3, 6, 6)))
+    trace = []
+    got = oracle.forward(layers, q, x, mirror_bf16=True, trace=trace)
+    steps = []
+    t = R(oracle.conv2d(x, q[0]["w"], q[0]["b"], 1, 1)); steps.append(t)
+    t = oracle.relu(t); steps.append(t)                  # exact on rounded values
+    t = R(oracle.lrn(t, 5, 1e-4, 0.75, 1.0)); steps.append(t)
+    t = oracle.maxpool(t, 3, 2, 0); steps.append(t)      # a selection: exact
+    t = R(oracle.conv2d(t, q[1]["w"], q[1]["b"], 1, 0)); steps.append(t)
+    t = oracle.relu(t); steps.append(t)
+    t = R(oracle.avgpool(t, 3)); steps.append(t)
+    logits = R(oracle.fc(t, q[2]["w"], q[2]["b"])); steps.append(logits)
+    want = oracle.softmax(logits); steps.append(want)    # probabilities stay fp32 in the library: not rounded to bf16
+    assert np.array_equal(got, want)
+    assert len(trace) == len(steps)
+    for (kind, out), ref in zip(trace, steps):           # every stored tensor, not only the last
+        assert np.array_equal(out, ref), kind
+    # moving or dropping a rounding is visible at this size
+    unrounded = oracle.forward(layers, q, x)
+    assert not np.array_equal(unrounded, want)
+    t2 = oracle.relu(oracle.conv2d(x, q[0]["w"], q[0]["b"], 1, 1))       # first rounding dropped
+    t2 = R(oracle.lrn(t2, 5, 1e-4, 0.75, 1.0))
+    assert not np.array_equal(t2, trace[2][1])
+
+
 # ------------------------------------------------------------------ tail layers, bf16 rounding
 def test_avgpool_fc_softmax():
     x = rng.standard_normal((2, 3, 7, 7))
@@ -268,6 +358,16 @@ def test_round_bf16():
              255.5: 256.0, 254.5: 254.0}
     for v, r in cases.items():
         assert oracle.round_bf16(np.array([v]))[0] == r, v
+    # subnormals of the format (spacing 2^-133 below 2^-126), its largest finite value, and the tie above it
+    big = (2.0 - 2.0 ** -7) * 2.0 ** 127
+    edge = {2.0 ** -133: 2.0 ** -133, 2.0 ** -134: 0.0, 3 * 2.0 ** -134: 2.0 ** -132, 2.0 ** -134 * 1.01: 2.0 ** -133,
+            5 * 2.0 ** -134: 2.0 ** -132, 2.0 ** -126 - 2.0 ** -134: 2.0 ** -126, 2.0 ** -127 + 2.0 ** -133: 2.0 ** -127 + 2.0 ** -133,
+            big: big, big + 2.0 ** 118: big, (2.0 - 2.0 ** -8) * 2.0 ** 127: np.inf, -(2.0 - 2.0 ** -8) * 2.0 ** 127: -np.inf,
+            big + 2.0 ** 119 - 2.0 ** 90: big, np.inf: np.inf}
+    for v, r in edge.items():
+        assert oracle.round_bf16(np.array([v]))[0] == r, v
+    assert np.isnan(oracle.round_bf16(np.array([np.nan]))[0])
+    assert np.signbit(oracle.round_bf16(np.array([-2.0 ** -134]))[0]) or oracle.round_bf16(np.array([-2.0 ** -134]))[0] == 0.0
     # against the bit-level rule of the storage format on random fp32 values
     x = (rng.standard_normal(20000) * np.exp(rng.uniform(-30, 30, 20000))).astype(np.float32)
     assert np.array_equal(oracle.round_bf16(x).astype(np.float32), workloads.round_to_bf16(x))
