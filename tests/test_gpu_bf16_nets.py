@@ -1,14 +1,22 @@
 """GPU parity of the bf16 configurations (ResNet-50 conv2_x stage, GoogLeNet-v1) through net_fwd:
-channels-last bf16 tensors, fp32 accumulation, against the oracle in mirrored mode (fp64 arithmetic,
-every layer output rounded to bf16 as the storage format demands).
+channels-last bf16 tensors, fp32 accumulation, against the oracle.
 
-Two bars.  Layer by layer ("teacher forced": every top-level layer of the network gets the
-oracle's input for that layer) the bf16 tolerance of 2e-2 applies as it stands to single layers, and
-times sqrt(2), sqrt(7) or sqrt(3) to an inception module / original / folded bottleneck, which round
-2, 7 or 3 times on their deepest path.  End to end the two
-sides take independent rounding decisions in every layer; a flipped decision is one bf16 unit
-(2^-8 relative) that later layers carry along, so the bound grows like the square root of the
-number of roundings on the deepest path: tolerance 2e-2 * sqrt(depth)."""
+Three gates, all at the stated bf16 tolerance of 2e-2 (max relative error, see util.rel_err).
+ * Layer by layer ("teacher forced"): every top-level layer of the network -- single layers, whole inception
+   modules, whole bottlenecks -- runs on the GPU on the oracle's input for that layer and matches the oracle's
+   output for it.
+ * GoogLeNet end to end, on the network's output before the softmax (the classifier's 1000 values per image),
+   all 128 images of the benchmark's batch: GPU against the oracle in mirrored mode (fp64 arithmetic, every
+   stored tensor rounded to bf16).  After the softmax a relative error of a probability is an absolute error
+   of a logit, so the probabilities are recorded but are no gate; the library's softmax is checked as a layer.
+ * The GPU is no further from the exact result (fp64, nothing rounded) than the mirrored oracle is: rms within
+   1.1x, worst element within 1.5x.
+The ResNet stage ends in a 256 x 56 x 56 map per image, 10^8 values per batch.  Its typical deviation from the
+mirrored oracle is 1e-3, and the third gate holds to four digits, but the worst single value of 10^8 cannot be
+held to 2e-2: two correct implementations take a few of the 2^-9 rounding decisions of the stored tensors
+differently (fp32 against fp64 sums), and one such unit on a large activation under a large filter tap is a
+few percent of the output's rms.  There the worst value is held to 2e-2 sqrt(roundings on the deepest path)
+and the share of values beyond 2e-2 to one in a million.  Every measured figure is listed in the run's summary."""
 import math
 
 import numpy as np
@@ -17,7 +25,7 @@ import pytest
 import oracle
 import workloads
 from paper_1708_04728_amd import binding as B, graph as G
-from util import TOL_BF16, rel_err
+from util import TOL_BF16, close, note, oracle_in_chunks, rel_err, rms_err
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -85,9 +93,7 @@ def teacher_forced(layers, params, x, folded=False, fuse_relu=False, inception_m
             got = run_net_bf16(sub, sub_params, cur, fuse_relu=fuse_relu, inception_mode=inception_mode, folded=folded)
         want = tr[i + span - 1][1]
         err = rel_err(got, want)
-        # roundings on the deepest path inside this top-level layer
-        inner = {"inception": 2, "bottleneck": 3 if folded else 7}.get(layers[i][0], 1)
-        assert err < TOL_BF16 * math.sqrt(inner), (i, layers[i][0], err)
+        assert note("layer %02d %s, on the oracle's input" % (i, layers[i][0]), err, TOL_BF16), (i, layers[i][0], err)
         worst = max(worst, err)
         cur = want if want.ndim == 4 else want.reshape(want.shape[0], -1, 1, 1)
         pos += sum(counts[i:i + span])
@@ -103,17 +109,19 @@ def test_config4_resnet_stage_original_and_folded():
     got = run_net_bf16(layers, params, x)
     assert got.shape == (2, 256, 28, 28)
     # deepest path: 3 bottlenecks x (3 x (conv, BN) + residual sum) = 21 roundings
-    assert rel_err(got, ref) < TOL_BF16 * math.sqrt(21)
+    assert close(got, ref, TOL_BF16 * math.sqrt(21), "original end to end")
 
     fp = folded_params(params)
     _, ref_f = teacher_forced(layers, fp, x, folded=True)
     got_f = run_net_bf16(layers, fp, x, folded=True)
-    assert rel_err(got_f, ref_f) < TOL_BF16 * math.sqrt(9)    # 3 bottlenecks x 3 convolutions
+    assert close(got_f, ref_f, TOL_BF16 * math.sqrt(9), "folded end to end")   # 3 bottlenecks x 3 convolutions
     # Lemma 2: the folded network computes the same function, up to the bf16 rounding of the folded
     # filters and of the (fewer) intermediate tensors
-    assert rel_err(got_f, got) < TOL_BF16 * math.sqrt(21 + 9)
+    assert close(got_f, got, TOL_BF16 * math.sqrt(21 + 9), "folded vs original, both on the gpu")
     exact = oracle.forward(layers, params, x)
-    assert rel_err(ref_f, exact) < TOL_BF16 * math.sqrt(9) and rel_err(ref, exact) < TOL_BF16 * math.sqrt(21)
+    assert against_exact_and_mirrored("original, 2 images 28x28", got, ref, exact, TOL_BF16 * math.sqrt(21))
+    # (the folded network's exact reference uses the folded filters as rounded to bf16: the same function as the GPU computes)
+    assert against_exact_and_mirrored("folded, 2 images 28x28", got_f, ref_f, oracle.forward(layers, fp, x, fold="given"), TOL_BF16 * math.sqrt(9))
 
 
 def test_config4_full_spatial_one_image():
@@ -123,7 +131,59 @@ def test_config4_full_spatial_one_image():
     ref = oracle.forward(layers, fp, x, mirror_bf16=True, fold="given")
     got = run_net_bf16(layers, fp, x, folded=True)
     assert got.shape == (1, 256, 56, 56)
-    assert rel_err(got, ref) < TOL_BF16 * math.sqrt(9)
+    assert close(got, ref, TOL_BF16 * math.sqrt(9))
+
+
+def against_exact_and_mirrored(tag, got, mirrored, exact, gate):
+    """End-to-end figures of one output tensor.  Gates: GPU against the mirrored oracle, worst element below `gate` and
+    rms below the plain tolerance; the GPU no further from the exact fp64 result than the mirrored oracle is (rms within
+    1.1x; worst element within 1.5x: the two worst cases are maxima over different rounding decisions)."""
+    ok = note(tag + ": gpu vs mirrored oracle, max rel", rel_err(got, mirrored), gate)
+    ok &= note(tag + ": gpu vs mirrored oracle, rms", rms_err(got, mirrored), TOL_BF16)
+    e_g, e_m = rel_err(got, exact), rel_err(mirrored, exact)
+    r_g, r_m = rms_err(got, exact), rms_err(mirrored, exact)
+    note(tag + ": gpu vs exact, max rel", e_g, 1.0)                       # recorded; the gates are the two ratios below
+    note(tag + ": mirrored oracle vs exact, max rel", e_m, 1.0)
+    note(tag + ": gpu vs exact, rms", r_g, 1.0)
+    note(tag + ": mirrored oracle vs exact, rms", r_m, 1.0)
+    ok &= note(tag + ": (gpu vs exact) / (mirrored vs exact), rms", r_g / r_m, 1.1)
+    ok &= note(tag + ": (gpu vs exact) / (mirrored vs exact), max rel", e_g / e_m, 1.5)
+    return bool(ok)
+
+
+def share_beyond(got, ref, tol):
+    """Fraction of the elements whose error, relative to max(|ref|, rms(ref)), exceeds tol."""
+    ref = np.asarray(ref, dtype=np.float64)
+    den = np.maximum(np.abs(ref), np.sqrt(np.mean(ref * ref)))
+    return float(np.mean(np.abs(np.asarray(got, dtype=np.float64) - ref) / den > tol))
+
+
+def googlenet_end_to_end(form, x, tag):
+    """Logits (the classifier's output, before the softmax) and probabilities of GoogLeNet on the GPU against the oracle
+    in mirrored and in exact mode."""
+    slim = form == "slim"
+    layers = workloads.CONFIGS[5][form]
+    assert layers[-1][0] == "softmax"
+    params = workloads.make_params(5, form)
+    mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if slim else 0
+    n = x.shape[0]
+    probs = run_net_bf16(layers, params, x, fuse_relu=slim, inception_mode=mode).reshape(n, 1000)
+    logits = run_net_bf16(layers[:-1], params, x, fuse_relu=slim, inception_mode=mode).reshape(n, 1000)
+    assert np.isfinite(probs).all() and (probs >= 0).all() and np.isfinite(logits).all()
+    np.testing.assert_allclose(probs.sum(axis=1), 1.0, rtol=1e-3)
+    mir = oracle_in_chunks(lambda c: oracle.forward(layers[:-1], params, c, mirror_bf16=True).reshape(c.shape[0], 1000), x)
+    exact = oracle_in_chunks(lambda c: oracle.forward(layers[:-1], params, c).reshape(c.shape[0], 1000), x)
+    # the stated bf16 bar, as it stands, on the network's output before the softmax
+    assert against_exact_and_mirrored(tag + " logits", logits, mir, exact, TOL_BF16)
+    # the library's softmax on its own logits, against the oracle's softmax of the same logits: a single layer
+    assert close(probs, oracle.softmax(logits), 1e-3, tag + " softmax of the gpu's logits")
+    pm = oracle.softmax(mir)
+    note(tag + " probabilities: gpu vs mirrored oracle, max rel", rel_err(probs, pm), 1.0)     # recorded, not a gate (see the header)
+    # the decision the network exists for: both sides pick the same class unless the top two are close
+    top = np.sort(pm, axis=1)[:, -2:]
+    decided = (top[:, 1] - top[:, 0]) > 0.1 * top[:, 1]
+    assert (np.argmax(probs, axis=1) == np.argmax(pm, axis=1))[decided].all()
+    return probs
 
 
 @pytest.mark.parametrize("form", ["original", "slim"])
@@ -133,18 +193,8 @@ def test_config5_googlenet(form):
     x = workloads.make_input(5, 2)
     slim = form == "slim"
     mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if slim else 0
-    worst, ref = teacher_forced(layers, params, x, fuse_relu=slim, inception_mode=mode)
-    got = run_net_bf16(layers, params, x, fuse_relu=slim, inception_mode=mode)
-    assert got.shape == (2, 1000, 1, 1)
-    got = got.reshape(2, 1000)
-    np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-3)
-    # deepest path: stem (3 conv + 2 LRN, or 3 conv) + 9 modules x 2 convolutions + avg-pool + classifier
-    depth = (3 if slim else 5) + 18 + 2
-    assert rel_err(got, ref) < TOL_BF16 * math.sqrt(depth)
-    # the decision the network exists for: both sides pick the same class unless the top two tie
-    top = np.sort(ref, axis=1)[:, -2:]
-    decided = (top[:, 1] - top[:, 0]) > 0.1 * top[:, 1]
-    assert (np.argmax(got, axis=1) == np.argmax(ref, axis=1))[decided].all()
+    teacher_forced(layers, params, x, fuse_relu=slim, inception_mode=mode)       # the gate: every layer at the plain tolerance
+    googlenet_end_to_end(form, x, "2 images")
 
 
 @pytest.mark.parametrize("form", ["original", "slim"])
@@ -167,7 +217,7 @@ def test_inception_stacked_first_steps(form, module):
     ref = oracle.forward([layer], params, x, mirror_bf16=True)
     base = B.DR_FUSE_RELU | B.DR_FUSE_CONCAT
     plain = run_net_bf16([layer], params, x, inception_mode=base)
-    assert rel_err(plain, ref) < TOL_BF16 * math.sqrt(2)
+    assert close(plain, ref, TOL_BF16)
     for mode in (base | B.DR_FUSE_STACK, B.DR_FUSE_RELU | B.DR_FUSE_STACK):
         got = run_net_bf16([layer], params, x, inception_mode=mode)
         assert np.array_equal(got, plain), (form, module, mode)
@@ -184,17 +234,17 @@ def test_inception_stacked_first_steps(form, module):
 def test_config5_googlenet_original_structure_fused():
     """The original structure with every fusion that leaves the function unchanged: ReLU and concat in the
     convolution stores, stacked first steps, LRN and pooling of the stem in one pass each.  Same network,
-    same parameters, same oracle as the layer-by-layer form; fewer intermediate roundings."""
-    layers = workloads.CONFIGS[5]["original"]
+    same parameters, same oracle as the layer-by-layer form; fewer intermediate roundings.  Compared before the
+    softmax."""
+    layers = workloads.CONFIGS[5]["original"][:-1]
     params = workloads.make_params(5, "original")
     x = workloads.make_input(5, 2)
     ref = oracle.forward(layers, params, x, mirror_bf16=True).reshape(2, 1000)
     mode = B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK
     got = run_net_bf16(layers, params, x, fuse_relu=True, inception_mode=mode, fuse_nontensor="all").reshape(2, 1000)
-    np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-3)
-    assert rel_err(got, ref) < TOL_BF16 * math.sqrt(5 + 18 + 2)
+    assert close(got, ref, TOL_BF16, "fused original structure vs mirrored oracle, logits")
     plain = run_net_bf16(layers, params, x).reshape(2, 1000)
-    assert rel_err(got, plain) < TOL_BF16 * math.sqrt(5 + 18 + 2)
+    assert close(got, plain, TOL_BF16, "fused vs layer by layer, both on the gpu, logits")
 
 
 @pytest.mark.parametrize("form", ["original", "slim"])
@@ -258,38 +308,32 @@ def test_config5_googlenet_as_a_hip_graph(form):
 # The whole batch runs on the GPU; the oracle recomputes a few of the images (images are independent), and
 # properties that hold for every image are checked on all of them.
 
-def test_config5_googlenet_full_batch_sampled():
+@pytest.mark.parametrize("form", ["original", "slim"])
+def test_config5_googlenet_full_batch(form):
+    """All 128 images of the benchmark's batch through the oracle, once in mirrored and once in exact mode."""
     x = workloads.make_input(5)
     assert x.shape == (128, 3, 224, 224)
-    pick = [0, 77, 127]
-    for form in ("original", "slim"):
-        slim = form == "slim"
-        layers = workloads.CONFIGS[5][form]
-        params = workloads.make_params(5, form)
-        mode = (B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if slim else 0
-        got = run_net_bf16(layers, params, x, fuse_relu=slim, inception_mode=mode).reshape(128, 1000)
-        assert np.isfinite(got).all() and (got >= 0).all()
-        np.testing.assert_allclose(got.sum(axis=1), 1.0, rtol=1e-3)
-        ref = oracle.forward(layers, params, x[pick], mirror_bf16=True).reshape(len(pick), 1000)
-        depth = (3 if slim else 5) + 18 + 2
-        assert rel_err(got[pick], ref) < TOL_BF16 * math.sqrt(depth)
+    googlenet_end_to_end(form, x, "128 images")
 
 
-def test_config4_resnet_stage_full_batch_sampled():
+@pytest.mark.parametrize("form", ["original", "folded"])
+def test_config4_resnet_stage_full_batch(form):
+    """All 128 images of config 4 through the oracle (mirrored and exact)."""
     x = workloads.make_input(4)
     assert x.shape == (128, 64, 56, 56)
-    pick = [0, 127]
     layers = workloads.CONFIGS[4]["original"]
     params = workloads.make_params(4)
-    got = run_net_bf16(layers, params, x)
+    folded = form == "folded"
+    p = folded_params(params) if folded else params
+    fold = "given" if folded else False
+    got = run_net_bf16(layers, p, x, folded=folded)
     assert got.shape == (128, 256, 56, 56) and np.isfinite(got).all() and (got >= 0).all()
-    ref = oracle.forward(layers, params, x[pick], mirror_bf16=True)
-    assert rel_err(got[pick], ref) < TOL_BF16 * math.sqrt(21)
-    fp = folded_params(params)
-    got_f = run_net_bf16(layers, fp, x, folded=True)
-    ref_f = oracle.forward(layers, fp, x[pick], mirror_bf16=True, fold="given")
-    assert np.isfinite(got_f).all() and (got_f >= 0).all()
-    assert rel_err(got_f[pick], ref_f) < TOL_BF16 * math.sqrt(9)
+    mir = oracle_in_chunks(lambda c: oracle.forward(layers, p, c, mirror_bf16=True, fold=fold), x, 8)
+    exact = oracle_in_chunks(lambda c: oracle.forward(layers, p, c, fold=fold), x, 8)
+    # 10^8 outputs: the worst of them carries a rounding decision taken differently upstream on a large activation through
+    # a large filter tap (a few percent of the output's rms); they are rare, and the typical deviation is 1e-3
+    assert against_exact_and_mirrored("128 images", got, mir, exact, TOL_BF16 * math.sqrt(9 if folded else 21))
+    assert note("128 images: share of outputs further than 2e-2 from the mirrored oracle", share_beyond(got, mir, TOL_BF16), 1e-6)
 
 
 @pytest.mark.parametrize("case", [
@@ -317,6 +361,6 @@ def test_small_channel_first_layer_through_net(case):
     ref = oracle.forward(layers, params, x)
     got = run_net_bf16(layers, params, x, fuse_relu=True)
     assert got.shape == ref.shape
-    assert rel_err(got, ref) < TOL_BF16
+    assert close(got, ref, TOL_BF16)
     got2 = run_net_bf16(layers, params, x, fuse_relu=False)
     assert np.array_equal(got, got2)

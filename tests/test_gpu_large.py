@@ -8,7 +8,7 @@ import pytest
 import oracle
 import workloads
 from paper_1708_04728_amd import binding as B
-from util import TOL_BF16, gpu, rel_err
+from util import TOL_BF16, gpu, close, rel_err
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -48,7 +48,7 @@ def _run(C, H, W, K, R, pad, rows, seed, marks):
     idx = torch.tensor(pix, dtype=torch.long, device="cuda")
     got = y.t.reshape(H * W, K)[idx].float().cpu().numpy().astype(np.float64)
     ref = np.stack([oracle.conv2d(_window(block, H, W, n // W, n % W, R, R, pad), w, b, 1, 0, True)[0, :, 0, 0] for n in pix])
-    assert rel_err(got, ref) < TOL_BF16
+    assert close(got, ref, TOL_BF16)
 
 
 def test_conv_bf16_more_than_2_to_24_output_pixels():
