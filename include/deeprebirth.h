@@ -103,6 +103,18 @@ int dr_conv2d_workspace_bytes(const dr_tensor* xd, const dr_conv* cd, size_t* by
 int dr_conv2d_fwd_ws(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
                      const dr_tensor* yd, void* y, int y_c_offset, void* ws, size_t ws_bytes, void* stream);
 
+/* dr_conv2d_fwd_ws for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid it): the scratch is an array inside the library, DR_STATIC_SCRATCH_BYTES per GPU
+ * the library runs on, held until the process ends.  The call allocates and frees nothing and gives the same
+ * bits as dr_conv2d_fwd_ws.  A layer whose partial sums need more (dr_conv2d_workspace_bytes says how much) is
+ * refused with DR_ERR_WORKSPACE before anything is enqueued; a layer that would not be cut needs none and runs
+ * as in dr_conv2d_fwd.  All calls on one GPU share that GPU's array (it keeps the last call's contents; the
+ * kernels write every value they later read, so nothing is cleared): calls that overlap in time on one GPU,
+ * on different streams or from different threads, race on it -- order them on one stream. */
+#define DR_STATIC_SCRATCH_BYTES (8u << 20)
+int dr_conv2d_fwd_static(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
+                         const dr_tensor* yd, void* y, int y_c_offset, void* stream);
+
 /* Reorders a filter tensor from KCRS to KRSC on the device: w_krsc[j][r][s][c] = w_kcrs[j][c][r][s]
  * (cd->k, c, r, s give the shape; dtype DR_F32 or DR_BF16; the two buffers must not overlap).
  * Returns DR_ERR_UNSUPPORTED when cd->c is not a multiple of 16 (fp32) or 8 (bf16): such filters

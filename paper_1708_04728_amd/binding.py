@@ -87,6 +87,7 @@ _SIGNATURES = {
     "dr_conv2d_fwd": ([_P(dr_tensor), _vp, _P(dr_conv), _vp, _vp, _P(dr_tensor), _vp, _i, _vp], _i),
     "dr_conv2d_workspace_bytes": ([_P(dr_tensor), _P(dr_conv), _P(_z)], _i),
     "dr_conv2d_fwd_ws": ([_P(dr_tensor), _vp, _P(dr_conv), _vp, _vp, _P(dr_tensor), _vp, _i, _vp, _z, _vp], _i),
+    "dr_conv2d_fwd_static": ([_P(dr_tensor), _vp, _P(dr_conv), _vp, _vp, _P(dr_tensor), _vp, _i, _vp], _i),
     "dr_pack_filters": ([_P(dr_conv), _i, _vp, _vp, _vp], _i),
     "dr_slim_conv_fwd": ([_P(dr_tensor), _vp, _P(dr_conv), _i, _i, _vp, _vp, _P(dr_tensor), _vp, _i, _vp], _i),
     "dr_relu": ([_P(dr_tensor), _vp, _vp, _vp], _i),
@@ -237,6 +238,16 @@ def conv2d_fwd_ws(x, cd, w, bias, y, ws, y_c_offset=0, stream=None):
     xd, yd = desc(x), desc(y)
     nbytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(lib().dr_conv2d_fwd_ws(xd, _ptr(x), cd, _ptr(w), _ptr(bias), yd, _ptr(y), y_c_offset, _ptr(ws), nbytes, _stream(stream)))
+    return y
+
+
+STATIC_SCRATCH_BYTES = 8 << 20      # DR_STATIC_SCRATCH_BYTES
+
+
+def conv2d_fwd_static(x, cd, w, bias, y, y_c_offset=0, stream=None):
+    """dr_conv2d_fwd_ws on the library's own scratch: nothing is allocated by the call."""
+    xd, yd = desc(x), desc(y)
+    _check(lib().dr_conv2d_fwd_static(xd, _ptr(x), cd, _ptr(w), _ptr(bias), yd, _ptr(y), y_c_offset, _stream(stream)))
     return y
 
 

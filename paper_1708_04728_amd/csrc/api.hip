@@ -8,6 +8,7 @@
 #include <new>
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "dr_internal.h"
@@ -701,6 +702,41 @@ int net_plan(const dr_net& net, const dr_tensor& xd, NetPlan* plan)
 }  // namespace
 }  // namespace dr
 
+// ---- scratch of dr_conv2d_fwd_static: the library's own, for callers that cannot allocate ---------------------
+// One array per GPU the library runs on, held until the process ends.  In host code `scratch` is only the
+// symbol's stand-in, not a device address: each device's copy is looked up once, with that device current, and
+// the looked-up pointer is what host code uses from then on (kernel arguments).
+static __device__ __align__(256) unsigned char scratch[DR_STATIC_SCRATCH_BYTES];
+
+namespace dr {
+namespace {
+void* static_scratch(const char* who, int* status)
+{
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static void* ptr[MAX_DEV];                       // device address of `scratch` on each device, NULL until asked
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) {
+        *status = fail(DR_ERR_HIP, "%s: no current device (or more than %d devices)", who, MAX_DEV);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            *status = fail(DR_ERR_HIP, "%s: hipGetSymbolAddress(scratch) on device %d: %s", who, dev, hipGetErrorString(e));
+            return nullptr;
+        }
+        ptr[dev] = p;
+    }
+    *status = DR_OK;
+    return ptr[dev];
+}
+}  // namespace
+}  // namespace dr
+
 using namespace dr;
 
 // =====================================================================================================
@@ -804,6 +840,28 @@ int dr_conv2d_fwd_ws(const dr_tensor* xd, const void* x, const dr_conv* cd, cons
     if (need && (!ws || ws_bytes < need)) return fail(DR_ERR_WORKSPACE, "%s: needs %zu bytes of workspace, got %zu", who, need, ws ? ws_bytes : (size_t)0);
     if (need && ((uintptr_t)ws & 255) != 0) return fail(DR_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned", who);
     return conv_run(who, *xd, x, *cd, w, bias, nullptr, 0, *yd, y, y_c_offset, (hipStream_t)stream, 0, need ? ws : nullptr, need);
+}
+
+int dr_conv2d_fwd_static(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
+                         const dr_tensor* yd, void* y, int y_c_offset, void* stream)
+{
+    const char* who = "dr_conv2d_fwd_static";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    DR_TRY(check_conv_desc(who, cd));
+    if (xd->c != cd->c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd->c, cd->c);
+    const size_t need = conv_scratch_bytes(*xd, *cd);
+    if (need > (size_t)DR_STATIC_SCRATCH_BYTES)
+        return fail(DR_ERR_WORKSPACE, "%s: the layer's partial sums take %zu bytes, the library's scratch holds %zu (use dr_conv2d_fwd_ws)", who,
+                    need, (size_t)DR_STATIC_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if (need) {
+        int status = DR_OK;
+        ws = static_scratch(who, &status);
+        if (!ws) return status;
+    }
+    // every partial sum the second kernel reads is written by the first in the same call: nothing has to be cleared
+    return conv_run(who, *xd, x, *cd, w, bias, nullptr, 0, *yd, y, y_c_offset, (hipStream_t)stream, 0, ws, need);
 }
 
 int dr_pack_filters(const dr_conv* cd, int dtype, const void* w_kcrs, void* w_krsc, void* stream)
