@@ -80,6 +80,59 @@ def calibrate_copy():
     print(json.dumps({"calibration": "dr_relu", "bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 3}))
 
 
+def ceilings():
+    """What this GPU sustains on the resources the kernels are graded against, from the measuring kernels in
+    libdr_ceilings.so (register-only matrix instructions; a plain 16-byte copy at several sizes; reads of a buffer that
+    stays in the caches), timed with HIP events, best of five launches each.  One JSON line."""
+    import ctypes as C
+
+    import torch
+    lib = C.CDLL(os.path.join(ROOT, "paper_1708_04728_amd", "libdr_ceilings.so"))
+    vp, z, i = C.c_void_p, C.c_size_t, C.c_int
+    lib.drc_mfma_bf16.argtypes = lib.drc_mfma_f32.argtypes = [vp, i, i, vp]
+    lib.drc_copy16.argtypes = [vp, vp, z, i, vp]
+    lib.drc_read16.argtypes = [vp, vp, z, i, i, vp]
+    st = torch.cuda.current_stream()
+    sp = vp(st.cuda_stream)
+    out = torch.zeros(1024, dtype=torch.float32, device="cuda")
+
+    def best_ms(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            assert fn() == 0
+            e1.record(st)
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return min(ts)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    res = {"compute_units": cus, "mfma": {}, "copy": {}, "cache_read": {}}
+    iters = 20000
+    for wg_per_cu in (1, 2):
+        blocks = cus * wg_per_cu
+        ms = best_ms(lambda: lib.drc_mfma_bf16(vp(out.data_ptr()), iters, blocks, sp))
+        res["mfma"]["bf16_32x32x16_tflops_%dwave_per_simd" % wg_per_cu] = round(2.0 * 32 * 32 * 16 * 4 * iters * 4 * blocks / (ms * 1e-3) / 1e12, 1)
+        ms = best_ms(lambda: lib.drc_mfma_f32(vp(out.data_ptr()), iters, blocks, sp))
+        res["mfma"]["f32_32x32x2_tflops_%dwave_per_simd" % wg_per_cu] = round(2.0 * 32 * 32 * 2 * 4 * iters * 4 * blocks / (ms * 1e-3) / 1e12, 1)
+    for mib in (8, 32, 64, 128, 256, 512, 1024):
+        n = mib << 20
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        ms = best_ms(lambda: lib.drc_copy16(vp(src.data_ptr()), vp(dst.data_ptr()), n, cus * 8, sp))
+        res["copy"]["%d_MiB_read_plus_write_GBs" % mib] = round(2.0 * n / (ms * 1e-3) / 1e9, 1)
+        del src, dst
+    for kib in (64, 1024):
+        n = kib << 10
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        passes, blocks = (4096 if kib == 64 else 256), cus * 2
+        ms = best_ms(lambda: lib.drc_read16(vp(src.data_ptr()), vp(out.data_ptr()), n, passes, blocks, sp))
+        res["cache_read"]["%d_KiB_buffer_GBs" % kib] = round(float(n) * passes * blocks / (ms * 1e-3) / 1e9, 1)
+    print(json.dumps({"ceilings": res, "published": {"hbm_GBs": MI355X_HBM_GBS, "mfma_tflops": MI355X_MFMA_TFLOPS}}))
+
+
 def paper_variant_ms(wl, reps=20):
     """The module of Sec. 3.2 slimmed the way the paper's own example does it (3x3 reducer 96 -> 48, the 1x1
     branch absorbed into a 3x3 of 192 filters, the pool branch into a 5x5 of 64 filters), on config 2's input,
@@ -174,6 +227,44 @@ def conv_flops(rec):
 
 def is_tensor(rec):
     return rec[0].startswith("conv") or rec[0] == "fc"
+
+
+def launch_roof(rec, dtype):
+    """(roof in ms, which roof binds) of one traced launch: a tensor layer is bounded by the slower of its FLOPs at the
+    matrix-core peak of its dtype and its algorithmic bytes (input, filters, output once each) at the HBM peak; a
+    non-tensor layer by its algorithmic bytes at the HBM peak."""
+    esz = 2 if dtype == "bf16" else 4
+    nbytes = float(rec[7]) if rec[7] > 0 else 2.0 * rec[5] * esz
+    t_hbm = nbytes / (MI355X_HBM_GBS * 1e9) * 1e3
+    if rec[0].startswith("conv"):
+        t_mfma = conv_flops(rec) / (MI355X_MFMA_TFLOPS[dtype] * 1e12) * 1e3
+        return (t_mfma, "mfma") if t_mfma >= t_hbm else (t_hbm, "hbm")
+    return t_hbm, "hbm"
+
+
+def network_roofline(recs, dtype, forward_ms):
+    """Every launch of one forward graded against its own roof (launch_roof): the sums, the split into tensor and
+    non-tensor layers, and the launches that lose the most time against their roof.  `measured_ms` of the whole
+    forward is the forward's own best time (one graph launch); the per-launch times are HIP-event pairs of a
+    kernel-by-kernel pass, which include the gap between dependent launches."""
+    rows = []
+    for r in recs:
+        roof, bound = launch_roof(r, dtype)
+        rows.append((r, roof, bound))
+    def part(sel):
+        rs = [x for x in rows if sel(x[0])]
+        roof, meas = sum(x[1] for x in rs), sum(x[0][6] for x in rs)
+        return {"launches": len(rs), "roof_ms": round(roof, 4), "measured_ms": round(meas, 4), "frac": round(roof / max(meas, 1e-9), 3),
+                "mfma_bound": sum(1 for x in rs if x[2] == "mfma"), "hbm_bound": sum(1 for x in rs if x[2] == "hbm")}
+    roof_all = sum(x[1] for x in rows)
+    worst = sorted(rows, key=lambda x: x[1] - x[0][6])[:5]
+    def name(r):
+        return "%s %dx%d %d->%d n=%d" % (r[0], r[3], r[4], r[2], r[1], r[5]) if r[0].startswith("conv") else "%s n=%d" % (r[0], r[5])
+    return {"roof_ms": round(roof_all, 4), "measured_ms": round(forward_ms, 4), "frac": round(roof_all / max(forward_ms, 1e-9), 3),
+            "kernel_by_kernel_ms": round(sum(x[0][6] for x in rows), 4),
+            "tensor": part(is_tensor), "non_tensor": part(lambda r: not is_tensor(r)),
+            "most_time_lost": [{"launch": name(r), "bound": b, "roof_ms": round(roof, 5), "measured_ms": round(r[6], 5),
+                                "frac": round(roof / max(r[6], 1e-9), 3)} for r, roof, b in worst]}
 
 
 class Workload:
@@ -371,6 +462,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=5, choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--calibrate-copy", action="store_true", help="run only the known-size copy kernel (counter calibration)")
+    ap.add_argument("--ceilings", action="store_true", help="run only the machine-ceiling measurements (matrix-core issue, copy, cached reads)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--only", action="store_true", help="skip the summary of the other configurations")
     args = ap.parse_args()
@@ -392,6 +484,9 @@ def main():
     torch.cuda.set_device(0)
     if args.calibrate_copy:
         calibrate_copy()
+        return
+    if args.ceilings:
+        ceilings()
         return
     wl = Workload(args.config)
     dtype, batch = wl.dtype, wl.batch
@@ -518,7 +613,10 @@ def main():
         "non_tensor_hbm_gbs": round(nontensor_bytes / max(oo, 1e-9) / 1e6, 1) if oo > 0 else None,
         "non_tensor_hbm_gbs_launches_over_32MB": round(sum(nt_bytes(r) for r in big) / max(sum(r[6] for r in big), 1e-9) / 1e6, 1) if big else None,
         "non_tensor_by_kind": {k: {"launches": v[2], "ms": round(v[1], 4), "gbs": round(v[0] / max(v[1], 1e-9) / 1e6, 1)} for k, v in sorted(by_kind.items())},
-        "roofline": roofline,
+        "roofline": dict(roofline, network={"original": network_roofline(recs, dtype, form_ms["original"][0]),
+                                            "slim": network_roofline(recs_slim, dtype, form_ms["slim"][0]),
+                                            "note": "every launch against max(FLOP / matrix-core peak, algorithmic bytes / 8 TB/s); "
+                                                    "frac = sum of the roofs / measured time of the forward"}),
         "per_block_ms": wl.block_times() if args.config == 5 else None,
         "per_block_ms_paper_S5": {"conv1": [94.92, 8.424], "conv2": [153.8, 16.62], "inception_3a": [55.23, 21.17],
                                   "inception_3b": [98.41, 25.94], "inception_4a": [30.53, 16.80], "inception_4b": [32.60, 20.29],

@@ -8,6 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdeeprebirth.so")
+CEILINGS_LIB = os.path.join(HERE, "libdr_ceilings.so")      # measuring aids for bench.py --ceilings; not linked into the library
 SOURCES = ["api.hip", "conv_f32.hip", "conv_bf16.hip", "conv_bf16_dma.hip", "pointwise.hip", "pointwise_nhwc.hip", "train.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          # hipcc may otherwise pair fp32 operations into packed instructions
@@ -34,6 +35,12 @@ def build_library(verbose=False, jobs=4):
     tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
     os.replace(tmp, LIB)
+    tmp = CEILINGS_LIB + ".tmp%d" % os.getpid()
+    p = subprocess.run([hipcc] + FLAGS + ["-shared", os.path.join(CSRC, "ceilings.hip"), "-o", tmp], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if p.returncode != 0:
+        sys.stderr.write(p.stdout)
+        raise RuntimeError("hipcc failed on ceilings.hip")
+    os.replace(tmp, CEILINGS_LIB)
     return LIB
 
 
