@@ -147,6 +147,19 @@ int dr_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const d
  * tensors whose channel count is a multiple of 8 (bf16) / 4 (fp32) and at most 512 / 256, 16-byte aligned
  * pointers, a 3x3 pooling window of stride 1 or 2 with padding 0 or 1, local_size 5. */
 int dr_lrn_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_lrn* l, const dr_pool* p, const dr_tensor* yd, void* y, void* stream);
+
+/* The original form of a streamlined block (Sec. 3.1, Fig. 3: convolution, ReLU, LRN, max-pooling) in ONE kernel:
+ *   y = maxpool(lrn(relu(conv(x; w) + bias)))
+ * with the function of the four layers unchanged -- the fusion the paper's Discussion sets against slimming: it
+ * saves the passes over memory, not the convolution's arithmetic at the unpooled resolution.  A workgroup holds
+ * all filters of a patch of convolution outputs, lays the patch down in LDS in the precision the layer-by-layer
+ * form stores it in (bf16), normalises across channels there and stores only the pooled pixels.
+ * bf16, DR_NHWC tensors, KRSC filters, cd->k <= 192 and a multiple of 8, cd->c a multiple of 8, LRN window of 5,
+ * pooling 3x3 at stride 2 without padding (ceil-mode sizes); anything else: DR_ERR_UNSUPPORTED.  cd->relu is
+ * ignored (the ReLU is part of the block).  yd = {n, >= y_c_offset + cd->k, pooled h, pooled w}; channels
+ * [y_c_offset, y_c_offset + cd->k) are written.  No workspace. */
+int dr_conv_lrn_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
+                            const dr_lrn* l, const dr_pool* p, const dr_tensor* yd, void* y, int y_c_offset, void* stream);
 int dr_maxpool_lrn_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_lrn* l, const dr_tensor* yd, void* y, void* stream);
 
 /* Concatenation along channels, Eq. (11): y = [x_0; x_1; ...; x_{nb-1}].  xds/xs are host arrays
@@ -262,7 +275,8 @@ typedef enum {
     DR_LAYER_CONV = 0, DR_LAYER_RELU, DR_LAYER_LRN, DR_LAYER_MAXPOOL, DR_LAYER_INCEPTION,
     DR_LAYER_BOTTLENECK, DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX,
     DR_LAYER_LRN_MAXPOOL,    /* dr_lrn_maxpool_fwd: uses .lrn and .pool */
-    DR_LAYER_MAXPOOL_LRN     /* dr_maxpool_lrn_fwd: uses .pool and .lrn */
+    DR_LAYER_MAXPOOL_LRN,    /* dr_maxpool_lrn_fwd: uses .pool and .lrn */
+    DR_LAYER_CONV_LRN_MAXPOOL /* dr_conv_lrn_maxpool_fwd: uses .conv, .lrn and .pool; parameters: filters, bias */
 } dr_layer_kind;
 
 /* ResNet bottleneck (Sec. 4.2): 1x1 (mid) - 3x3 (mid) - 1x1 (out), each followed by BatchNorm
@@ -273,7 +287,7 @@ typedef struct { int mid, out, project, folded; float eps; int filter_layout; /*
 
 typedef struct {
     int kind;
-    dr_conv conv;            /* DR_LAYER_CONV */
+    dr_conv conv;            /* DR_LAYER_CONV, DR_LAYER_CONV_LRN_MAXPOOL */
     dr_lrn lrn;              /* DR_LAYER_LRN, DR_LAYER_LRN_MAXPOOL, DR_LAYER_MAXPOOL_LRN */
     dr_pool pool;            /* DR_LAYER_MAXPOOL, DR_LAYER_AVGPOOL, DR_LAYER_LRN_MAXPOOL, DR_LAYER_MAXPOOL_LRN */
     dr_inception inception;  /* DR_LAYER_INCEPTION */

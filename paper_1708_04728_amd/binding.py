@@ -24,7 +24,7 @@ DR_MAX_BRANCHES, DR_MAX_STEPS = 8, 4
 DR_STEP_CONV, DR_STEP_MAXPOOL = 0, 1
 DR_FUSE_RELU, DR_FUSE_CONCAT, DR_FUSE_STACK, DR_CONCURRENT_BRANCHES = 1, 2, 4, 8
 (DR_LAYER_CONV, DR_LAYER_RELU, DR_LAYER_LRN, DR_LAYER_MAXPOOL, DR_LAYER_INCEPTION, DR_LAYER_BOTTLENECK,
- DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX, DR_LAYER_LRN_MAXPOOL, DR_LAYER_MAXPOOL_LRN) = range(11)
+ DR_LAYER_AVGPOOL, DR_LAYER_FC, DR_LAYER_SOFTMAX, DR_LAYER_LRN_MAXPOOL, DR_LAYER_MAXPOOL_LRN, DR_LAYER_CONV_LRN_MAXPOOL) = range(12)
 
 
 class dr_tensor(C.Structure):
@@ -96,6 +96,7 @@ _SIGNATURES = {
     "dr_avgpool_fwd": ([_P(dr_tensor), _vp, _P(dr_pool), _P(dr_tensor), _vp, _vp], _i),
     "dr_lrn_maxpool_fwd": ([_P(dr_tensor), _vp, _P(dr_lrn), _P(dr_pool), _P(dr_tensor), _vp, _vp], _i),
     "dr_maxpool_lrn_fwd": ([_P(dr_tensor), _vp, _P(dr_pool), _P(dr_lrn), _P(dr_tensor), _vp, _vp], _i),
+    "dr_conv_lrn_maxpool_fwd": ([_P(dr_tensor), _vp, _P(dr_conv), _vp, _vp, _P(dr_lrn), _P(dr_pool), _P(dr_tensor), _vp, _i, _vp], _i),
     "dr_concat": ([_i, _P(dr_tensor), _P(_vp), _P(dr_tensor), _vp, _vp], _i),
     "dr_bn_fwd": ([_P(dr_tensor), _vp, _vp, _vp, _vp, _vp, _f, _i, _vp, _vp], _i),
     "dr_add_relu": ([_P(dr_tensor), _vp, _vp, _vp, _vp], _i),
@@ -286,6 +287,12 @@ def maxpool_fwd(x, pd, y, stream=None):
 def lrn_maxpool_fwd(x, ld, pd, y, stream=None):
     """y = maxpool(lrn(x)) in one pass; ld: dr_lrn, pd: dr_pool."""
     _check(lib().dr_lrn_maxpool_fwd(desc(x), _ptr(x), ld, pd, desc(y), _ptr(y), _stream(stream)))
+    return y
+
+
+def conv_lrn_maxpool_fwd(x, cd, w, bias, ld, pd, y, y_c_offset=0, stream=None):
+    """y = maxpool(lrn(relu(conv(x; w) + bias))) in one kernel (the original form of a streamlined block)."""
+    _check(lib().dr_conv_lrn_maxpool_fwd(desc(x), _ptr(x), cd, _ptr(w), _ptr(bias), ld, pd, desc(y), _ptr(y), y_c_offset, _stream(stream)))
     return y
 
 

@@ -69,7 +69,7 @@ TraceScope::TraceScope(const char* label, const ConvGeom* g, long long items, hi
         rec.k = g->K; rec.c = (int)c; rec.r = g->R; rec.s = g->S;
         rec.bytes = esz * ((long long)g->N * c * g->H * g->W + (long long)g->K * c * g->R * g->S + (long long)g->Ng * g->K * (g->res_ctot ? 2 : 1));
     }
-    else rec.bytes = bytes;
+    if (!g || bytes > 0) rec.bytes = bytes;          // (a caller that knows better: e.g. a block whose output is the pooled tensor)
     rec.items = items;
     slot = (int)g_trace.recs.size();
     g_trace.recs.push_back(rec);
@@ -195,6 +195,31 @@ int conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv&
     if (xd.dtype == DR_F32)
         return launch_conv_f32(g, (const float*)x, (const float*)w, bias, (const float*)residual, (float*)y, st, scratch, scratch_bytes);
     return launch_conv_bf16(g, (const uint16_t*)x, (const uint16_t*)w, bias, (const uint16_t*)residual, (uint16_t*)y, st);
+}
+
+// The streamlined block's original form in one kernel (see dr_conv_lrn_maxpool_fwd).
+int conv_block_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias, const dr_lrn& l,
+                   const dr_pool& p, const dr_tensor& yd, void* y, int y_c_offset, hipStream_t st)
+{
+    if (xd.c != cd.c) return fail(DR_ERR_SHAPE, "%s: input has %d channels, filters expect %d", who, xd.c, cd.c);
+    const dr_tensor c = conv_out(xd, cd);
+    const dr_tensor o = pool_out(c, p);
+    if (yd.n != o.n || yd.h != o.h || yd.w != o.w)
+        return fail(DR_ERR_SHAPE, "%s: output is %dx%dx%d per channel, the block produces %dx%dx%d", who, yd.n, yd.h, yd.w, o.n, o.h, o.w);
+    if (y_c_offset < 0 || y_c_offset + cd.k > yd.c)
+        return fail(DR_ERR_SHAPE, "%s: channels [%d,%d) do not fit an output of %d channels", who, y_c_offset, y_c_offset + cd.k, yd.c);
+    if (xd.dtype != DR_BF16 || yd.dtype != DR_BF16 || xd.layout != DR_NHWC || yd.layout != DR_NHWC || cd.filter_layout != DR_KRSC)
+        return fail(DR_ERR_UNSUPPORTED, "%s: bf16 channels-last tensors and KRSC filters only", who);
+    if ((double)cd.c * cd.r * cd.s >= 2147483648.0 || (double)c.n * c.h * c.w >= 2147483648.0) return fail(DR_ERR_UNSUPPORTED, "%s: problem too large", who);
+    if (tensor_elems(o) == 0 || cd.k == 0) return DR_OK;
+    if (!x || !w || !y) return fail(DR_ERR_NULL, "%s: x, w or y is NULL", who);
+    ConvGeom g = conv_geom(xd, cd, c);
+    g.relu = 1;
+    if (!conv_bf16_block_eligible(g, x, w, p, l) || yd.c % 8 != 0 || y_c_offset % 8 != 0 || ((uintptr_t)y & 15) != 0)
+        return fail(DR_ERR_UNSUPPORTED, "%s: needs at most 192 filters (a multiple of 8), channels a multiple of 8, an LRN window of 5, 3x3 pooling at "
+                    "stride 2 without padding, 16-byte aligned tensors below 2 GiB", who);
+    TraceScope trace("conv_lrn_pool", &g, g.Ng, st, (long long)(tensor_bytes(xd) + (size_t)cd.k * g.Kg * 2 + (size_t)o.n * o.h * o.w * cd.k * 2));
+    return launch_conv_bf16_block(g, (const uint16_t*)x, (const uint16_t*)w, bias, l, o.h, o.w, (uint16_t*)y, yd.c, y_c_offset, st);
 }
 
 // ---- bump allocator over the caller's workspace (also used in "measure" mode with base = NULL)
@@ -535,6 +560,7 @@ int param_count(const dr_layer_desc& L)
 {
     switch (L.kind) {
     case DR_LAYER_CONV: return 2;
+    case DR_LAYER_CONV_LRN_MAXPOOL: return 2;
     case DR_LAYER_FC: return 2;
     case DR_LAYER_INCEPTION: {
         int n = 0;
@@ -635,6 +661,13 @@ int layer_out(const dr_layer_desc& L, const dr_tensor& t, dr_tensor* o)
         if (L.lrn.local_size < 1) return fail(DR_ERR_SHAPE, "%s: LRN local_size %d", who, L.lrn.local_size);
         DR_TRY(check_pool_desc(who, &L.pool));
         *o = pool_out(t, L.pool);
+        return DR_OK;
+    case DR_LAYER_CONV_LRN_MAXPOOL:
+        DR_TRY(check_conv_desc(who, &L.conv));
+        if (L.conv.c != t.c) return fail(DR_ERR_SHAPE, "%s: convolution expects %d channels, gets %d", who, L.conv.c, t.c);
+        if (L.lrn.local_size < 1) return fail(DR_ERR_SHAPE, "%s: LRN local_size %d", who, L.lrn.local_size);
+        DR_TRY(check_pool_desc(who, &L.pool));
+        *o = pool_out(conv_out(t, L.conv), L.pool);
         return DR_OK;
     case DR_LAYER_AVGPOOL:
         DR_TRY(check_pool_desc(who, &L.pool));
@@ -950,6 +983,19 @@ int dr_lrn_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_lrn* l, cons
     return lrn_pool_entry("dr_lrn_maxpool_fwd", xd, x, l, p, yd, y, true, stream);
 }
 
+int dr_conv_lrn_maxpool_fwd(const dr_tensor* xd, const void* x, const dr_conv* cd, const void* w, const float* bias,
+                            const dr_lrn* l, const dr_pool* p, const dr_tensor* yd, void* y, int y_c_offset, void* stream)
+{
+    const char* who = "dr_conv_lrn_maxpool_fwd";
+    DR_TRY(check_tensor(who, "xd", xd));
+    DR_TRY(check_tensor(who, "yd", yd));
+    DR_TRY(check_conv_desc(who, cd));
+    if (!l || !p) return fail(DR_ERR_NULL, "%s: l or p is NULL", who);
+    if (l->local_size < 1) return fail(DR_ERR_SHAPE, "%s: LRN local_size %d", who, l->local_size);
+    DR_TRY(check_pool_desc(who, p));
+    return conv_block_run(who, *xd, x, *cd, w, bias, *l, *p, *yd, y, y_c_offset, (hipStream_t)stream);
+}
+
 int dr_maxpool_lrn_fwd(const dr_tensor* xd, const void* x, const dr_pool* p, const dr_lrn* l, const dr_tensor* yd, void* y, void* stream)
 {
     return lrn_pool_entry("dr_maxpool_lrn_fwd", xd, x, l, p, yd, y, false, stream);
@@ -1166,7 +1212,7 @@ int dr_net_create(const dr_layer_desc* layers, int n_layers, dr_net** out)
     if (!net) return fail(DR_ERR_HIP, "%s: out of host memory", who);
     net->layers.assign(layers, layers + n_layers);
     for (const dr_layer_desc& L : net->layers) {
-        if (L.kind < DR_LAYER_CONV || L.kind > DR_LAYER_MAXPOOL_LRN) {
+        if (L.kind < DR_LAYER_CONV || L.kind > DR_LAYER_CONV_LRN_MAXPOOL) {
             delete net;
             return fail(DR_ERR_UNSUPPORTED, "%s: unknown layer kind %d", who, L.kind);
         }
@@ -1298,6 +1344,9 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
                 return fail(DR_ERR_UNSUPPORTED, "%s: layer %zu: fused LRN / pooling needs channels-last tensors, a 3x3 window of stride 1 or 2, "
                             "an LRN window of 5 and at most 64 16-byte channel groups", who, i);
             DR_TRY(launch_pool_lrn_nhwc(t, cur, od, dst, L.pool, L.lrn, L.kind == DR_LAYER_LRN_MAXPOOL, st));
+            break;
+        case DR_LAYER_CONV_LRN_MAXPOOL:
+            DR_TRY(conv_block_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], L.lrn, L.pool, od, dst, 0, st));
             break;
         case DR_LAYER_AVGPOOL: DR_TRY(launch_avgpool(t, cur, od, dst, L.pool, st)); break;
         case DR_LAYER_INCEPTION: {

@@ -38,6 +38,7 @@
 #include <type_traits>
 
 #include "dr_internal.h"
+#include "dr_store.h"
 
 namespace dr {
 namespace {
@@ -79,7 +80,17 @@ struct DArgs {
     int split_end[3];
     uint16_t* y_seg[4];
     int ctot_seg[4];
+    // Block kernel (FUSE): the convolution's output never leaves the compute unit; what is stored is
+    // maxpool3x3s2(lrn5(relu(conv))), f_PP x f_QQ pixels per image, at channel f_coff of a tensor with f_ctot channels.
+    // A workgroup owns all filters of a patch of FUSE_SIDE x FUSE_SIDE convolution pixels (f_ty x f_tx patches per image).
+    int f_ty, f_tx, f_PP, f_QQ, f_ctot, f_coff, f_b075;
+    float f_a_over_n, f_beta, f_k;
+    uint16_t* f_y;
 };
+
+// Block kernel: pooled outputs per patch side, and the convolution pixels they need (3x3 windows at stride 2)
+constexpr int FUSE_POOLED = 7, FUSE_SIDE = 2 * FUSE_POOLED + 1, FUSE_PIXELS = FUSE_SIDE * FUSE_SIDE;
+constexpr int FUSE_PITCH = 400;     // bytes per staged pixel: 192 channels of bf16 + 16, so that 16 consecutive pixels cover every bank
 
 // Workgroup barrier between the slices.  A fence would make the compiler wait for every outstanding
 // load that writes LDS (vmcnt(0)), which is exactly the prefetch this kernel keeps in flight, so the
@@ -136,15 +147,6 @@ __device__ __forceinline__ void wait_lgkm()
 }
 __device__ __forceinline__ void touch(u32x4& v) { asm volatile("" : "+v"(v)); }
 
-// two fp32 -> two bf16 (round to nearest even, NaN stays NaN) in one 32-bit word: v_cvt_pk_bf16_f32
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
-}
-__device__ __forceinline__ uint32_t f32_to_bf16(float f) { return pack_bf16x2(f, 0.f) & 0xFFFFu; }
-
 // v / d for 0 <= v < 2^24 and 1 <= d <= 2^16, exact: (v * ceil(2^40 / d)) >> 40.  With m = (2^40 + e) / d,
 // 0 <= e < d, the product is v / d + v e / (d 2^40) and the second term is below 2^-16 <= 1 / d.
 __device__ __forceinline__ int div_small(int v, unsigned long long m)
@@ -157,16 +159,25 @@ __device__ __forceinline__ unsigned bit_range(int lo, int hi) { return hi >= lo 
 
 // A workgroup is WGM x WGN waves (4 or 8), each with a tile of TM x TN blocks of 32 x 32.  OCC: workgroups per
 // compute unit the register allocation must leave room for (512 / (OCC * waves / 4) registers per lane).
-template <int TM, int TN, int WGM, int WGN, int NS, bool TAP, int OCC>
+// KB: contraction elements per slice, 64 (LDS rows of 128 bytes, 8 chunks) or 32 (rows of 64 bytes, 4 chunks).  Half-depth
+// slices halve a stage, so that a wider tile keeps a ring of three or four stages at two workgroups per compute unit.
+// FUSE: the block kernel (Sec. 3.1, the streamlined block's original form in one pass): one patch of FUSE_SIDE x FUSE_SIDE
+// convolution pixels x all filters per workgroup; bias + ReLU, then the tile is laid down in LDS as bf16 (the precision
+// the layer-by-layer form stores it in), normalised across channels in place, and pooled from there.
+template <int TM, int TN, int WGM, int WGN, int NS, bool TAP, int OCC, int KB = 64, bool FUSE = false>
 __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(OCC * WGM * WGN / 4, OCC * WGM * WGN / 4)))
 void conv_bf16_dma_kernel(const DArgs a)
 {
-    constexpr int WAVES = WGM * WGN, RP = WAVES * 8;                     // rows one pass of loads covers (8 per wave)
+    constexpr int RB = KB * 2, CPR = KB / 8, RPB = 1024 / RB;            // bytes and chunks per LDS row; rows per 1 KiB load block
+    constexpr int WAVES = WGM * WGN, RP = WAVES * RPB;                   // rows one pass of loads covers
     constexpr int WM = TM * 32, WN = TN * 32, BM = WGM * WM, BN = WGN * WN;
-    constexpr int A_PER = BM / RP, B_PER = BN / RP, L = A_PER + B_PER;   // loads per lane and slice
-    constexpr int A_BYTES = BM * 128, STAGE = (BM + BN) * 128, PASS = RP * 128;
-    static_assert((WAVES == 4 || WAVES == 8) && BM % RP == 0 && BN % RP == 0 && NS >= 2 && (NS - 1) * L < 63 && BM <= 256,
-                  "bad configuration");
+    // loads per lane and slice; a filter block that is not a whole number of passes is padded (the extra rows fetch nothing)
+    constexpr int A_PER = (BM + RP - 1) / RP, B_PER = BN / RP, L = A_PER + B_PER;
+    constexpr int A_BYTES = A_PER * RP * RB, STAGE = A_BYTES + BN * RB, PASS = RP * RB;
+    constexpr int KSTEPS = KB / 16;                                      // matrix-instruction steps per slice
+    static_assert((KB == 64 || KB == 32) && (WAVES == 4 || WAVES == 8) && (BM % RP == 0 || KB == 32) && BN % RP == 0 && NS >= 2 &&
+                  (NS - 1) * L < 63 && BM <= 256, "bad configuration");
+    static_assert(!FUSE || (BN >= FUSE_PIXELS && BM * 2 + 16 <= FUSE_PITCH && FUSE_PIXELS * FUSE_PITCH <= NS * STAGE && KB == 64), "block kernel tile");
 
     __shared__ __attribute__((aligned(1024))) unsigned char ring[NS * STAGE];
     __shared__ __attribute__((aligned(1024))) float bias_lds[256];
@@ -179,13 +190,16 @@ void conv_bf16_dma_kernel(const DArgs a)
     const int half = lane >> 5, l32 = lane & 31;
     const int PQ = g.P * g.Q;
 
-    // loader: this lane fetches row lrow of every 32-row group, logical chunk lc of the slice
-    const int lrow = wave * 8 + (lane >> 3);
-    const int lc = (lane & 7) ^ ((lrow >> 1) & 7);
-    // reader: LDS byte offset of this lane's operand chunk for k-step 0; k-step ks flips bits 5..6
-    const int lane_x = (half << 4) ^ (((l32 >> 1) & 7) << 4);
-    const unsigned a_rd = ring_lds + (wm * WM + l32) * 128 + lane_x;
-    const unsigned b_rd = ring_lds + A_BYTES + (wn * WN + l32) * 128 + lane_x;
+    // Chunk j of row r is stored at chunk j ^ swz(r): 16 consecutive rows then cover every bank once, for the loads'
+    // writes as for the operand reads.  (Rows of 128 bytes: two rows per 256 bytes; rows of 64 bytes: four.)
+    auto swz = [](int r) { return KB == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
+    // loader: this lane fetches row lrow of every RP-row group, logical chunk lc of the slice
+    const int lrow = wave * RPB + lane / CPR;
+    const int lc = (lane % CPR) ^ swz(lrow);
+    // reader: LDS byte offset of this lane's operand chunk for k-step 0; k-step ks flips bits 5 (and 6)
+    const int lane_x = (half << 4) ^ (swz(l32) << 4);
+    const unsigned a_rd = ring_lds + (wm * WM + l32) * RB + lane_x;
+    const unsigned b_rd = ring_lds + A_BYTES + (wn * WN + l32) * RB + lane_x;
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, a.w_bytes, 0x00020000);
@@ -207,8 +221,8 @@ void conv_bf16_dma_kernel(const DArgs a)
     int a_voff[A_PER];            // byte offset of (filter m, chunk lc) or OOB
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
-        const int m = mt * BM + i * RP + lrow;
-        a_voff[i] = m < g.K ? (m * g.Kg + lc * 8) * 2 : OOB;
+        const int ml = i * RP + lrow, m = mt * BM + ml;
+        a_voff[i] = (ml < BM && m < g.K) ? (m * g.Kg + lc * 8) * 2 : OOB;
     }
     // The bias of the channel block travels like the operands, ahead of them: 4 bytes per lane straight
     // into LDS (zeros beyond the last filter and without a bias), so that nothing in the prologue waits
@@ -234,6 +248,23 @@ void conv_bf16_dma_kernel(const DArgs a)
     // step_q, so each coordinate wraps at most once per step).
     auto tile_setup = [&](int nt) __attribute__((always_inline)) {
         const int n_first = nt * BN + lrow;
+        if constexpr (FUSE) {
+            // row t of the tile is pixel (t / SIDE, t % SIDE) of patch (ty, tx) of image img; patches overlap by one row / column
+            const int per_img = a.f_ty * a.f_tx;
+            const int img = nt / per_img, rem = nt - img * per_img, ty = rem / a.f_tx, tx = rem - ty * a.f_tx;
+#pragma unroll
+            for (int i = 0; i < B_PER; ++i) {
+                const int t = lrow + i * RP, dy = t / FUSE_SIDE, dx = t - dy * FUSE_SIDE;
+                const int p = ty * (FUSE_SIDE - 1) + dy, q = tx * (FUSE_SIDE - 1) + dx;
+                const bool valid = t < FUSE_PIXELS && p < g.P && q < g.Q && img < g.N;
+                const int ih0 = p * g.sh - g.ph, iw0 = q * g.sw - g.pw;
+                b_base[i] = valid ? (((img * g.H + ih0) * g.W + iw0) * g.C + lc * 8) * 2 : 0;
+                const unsigned wv = bit_range(max(0, -iw0), min(g.S - 1, g.W - 1 - iw0));
+                const unsigned hv = valid ? bit_range(max(0, -ih0), min(g.R - 1, g.H - 1 - ih0)) : 0u;
+                b_mask[i] = (~wv & 0xFFFFu) | (hv << 16);
+            }
+            return;
+        }
         if (a.pointwise) {
 #pragma unroll
             for (int i = 0; i < B_PER; ++i) {
@@ -292,7 +323,7 @@ void conv_bf16_dma_kernel(const DArgs a)
 #pragma unroll
             for (int i = 0; i < B_PER; ++i)
                 load_to_lds16(rx, sb + i * PASS, (int)b_cur[i], soff_b);
-            ld_c += 8;
+            ld_c += CPR;
             if (ld_c == a.c8) {
                 ld_c = 0;
                 if (++ld_s == g.S) {
@@ -303,7 +334,7 @@ void conv_bf16_dma_kernel(const DArgs a)
         } else {
             if (ld_fresh) { row_setup(); ld_fresh = 0; }
             const int jl0 = ld_j0 + lc;                                            // this lane's chunk within the run of row ld_r
-            const bool straddle = a.flat && ld_j0 + 8 > a.run_chunks;             // (wave-uniform) the slice runs on into row ld_r + 1
+            const bool straddle = a.flat && ld_j0 + CPR > a.run_chunks;           // (wave-uniform) the slice runs on into row ld_r + 1
             const int soff_a = (ld_r * a.run_chunks + ld_j0) * 16;                // filter rows follow one another in memory
             const int run_off = ld_r * g.W * g.C * 2 + ld_j0 * 16;
             if (!straddle) {
@@ -338,7 +369,7 @@ void conv_bf16_dma_kernel(const DArgs a)
                     load_to_lds16(rx, sb + i * PASS, (int)off, 0);
                 }
             }
-            ld_j0 += 8;
+            ld_j0 += CPR;
             if (ld_j0 >= a.run_chunks) {
                 ld_j0 = a.flat ? ld_j0 - a.run_chunks : 0;
                 ld_fresh = 1;
@@ -361,24 +392,29 @@ void conv_bf16_dma_kernel(const DArgs a)
     // (slot = step % 4) three steps before the matrix cores use them, across slice boundaries, so that
     // the LDS latency hides behind about three steps of MFMAs.  LDS reads return in order: "at most the
     // reads of two steps outstanding" means the oldest of three steps in flight has arrived.
-    u32x4 fa[4][TM], fb[4][TN];
+    // (Half-depth slices: two k-steps per slice, two slots, each k-step fetched one step before its use -- a step of a
+    // wide wave tile is long enough to cover the LDS latency.)
+    constexpr int SLOTS = KB == 64 ? 4 : 2;
+    u32x4 fa[SLOTS][TM], fb[SLOTS][TN];
     auto fetch_step = [&](int stage, auto ks_c) __attribute__((always_inline)) {     // k-step KS of a stage -> slot KS
         constexpr int KS = decltype(ks_c)::value;
+        static_assert(KS < KSTEPS && KS < SLOTS, "k-step");
         const unsigned pa = (a_rd + stage * STAGE) ^ (KS * 32), pb = (b_rd + stage * STAGE) ^ (KS * 32);
+        constexpr int BLK = 32 * RB;                                       // one 32-row block of an operand
         fa[KS][0] = ds_read16<0>(pa);
-        if constexpr (TM > 1) fa[KS][1] = ds_read16<4096>(pa);
-        if constexpr (TM > 2) fa[KS][2] = ds_read16<8192>(pa);
-        if constexpr (TM > 3) fa[KS][3] = ds_read16<12288>(pa);
-        if constexpr (TM > 4) fa[KS][4] = ds_read16<16384>(pa);
-        if constexpr (TM > 5) fa[KS][5] = ds_read16<20480>(pa);
+        if constexpr (TM > 1) fa[KS][1] = ds_read16<BLK>(pa);
+        if constexpr (TM > 2) fa[KS][2] = ds_read16<2 * BLK>(pa);
+        if constexpr (TM > 3) fa[KS][3] = ds_read16<3 * BLK>(pa);
+        if constexpr (TM > 4) fa[KS][4] = ds_read16<4 * BLK>(pa);
+        if constexpr (TM > 5) fa[KS][5] = ds_read16<5 * BLK>(pa);
         fb[KS][0] = ds_read16<0>(pb);
-        if constexpr (TN > 1) fb[KS][1] = ds_read16<4096>(pb);
-        if constexpr (TN > 2) fb[KS][2] = ds_read16<8192>(pb);
-        if constexpr (TN > 3) fb[KS][3] = ds_read16<12288>(pb);
+        if constexpr (TN > 1) fb[KS][1] = ds_read16<BLK>(pb);
+        if constexpr (TN > 2) fb[KS][2] = ds_read16<2 * BLK>(pb);
+        if constexpr (TN > 3) fb[KS][3] = ds_read16<3 * BLK>(pb);
     };
     auto multiply_step = [&](auto ks_c) __attribute__((always_inline)) {              // waits for slot KS, multiplies it
         constexpr int KS = decltype(ks_c)::value;
-        wait_lgkm<2 * (TM + TN)>();
+        wait_lgkm<(SLOTS - 2) * (TM + TN) + (SLOTS == 2 ? TM + TN : 0)>();            // the reads of the younger steps may be pending
 #pragma unroll
         for (int i = 0; i < TM; ++i) touch(fa[KS][i]);
 #pragma unroll
@@ -463,6 +499,131 @@ void conv_bf16_dma_kernel(const DArgs a)
         }
     };
 
+    // ---- block kernel: what follows the contraction.  (a) bias + ReLU, rounded to bf16, into LDS as [pixel][channel] (the ring
+    // is free: every load has landed and, after the barrier, every operand read has returned); (b) across-channel
+    // normalisation in place: an item is 8 channels of a pixel, its window's two channels on either side come from the
+    // neighbouring items; results wait in registers until everybody has read; (c) 3x3 stride-2 maxima of the normalised
+    // pixels, clipped at the image's last row / column, 16 bytes per store.
+    auto epilogue_block = [&](int nt) __attribute__((always_inline)) {
+        constexpr int NTH = WAVES * 64;
+        unsigned char* stage_lds = ring;
+        const int groups = (g.K + 7) >> 3;                       // 16-byte channel groups per pixel
+        ring_barrier();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            u32x4 bv[2][2];
+            bv[0][0] = ds_read16<0>(bias_rd + i * 128);
+            bv[0][1] = ds_read16<16>(bias_rd + i * 128);
+            bv[1][0] = ds_read16<64>(bias_rd + i * 128);
+            bv[1][1] = ds_read16<80>(bias_rd + i * 128);
+            wait_lgkm<0>();
+            touch(bv[0][0]); touch(bv[0][1]); touch(bv[1][0]); touch(bv[1][1]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int t = wn * WN + j * 32 + l32;            // pixel row of the tile
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp) {
+                    float o[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][qp * 8 + e]),
+                                                                         __float_as_uint(acc[i][j][qp * 8 + 4 + e]), false, false);
+                        o[e] = __uint_as_float(sw[0]);
+                        o[4 + e] = __uint_as_float(sw[1]);
+                    }
+                    const int ml = wm * WM + half * 8 + i * 32 + qp * 16;     // first of this lane's 8 channels
+                    u32x4 pk;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        pk[e] = pack_bf16x2(fmaxf(o[2 * e] + __uint_as_float(bv[qp][(2 * e) >> 2][(2 * e) & 3]), 0.f),
+                                            fmaxf(o[2 * e + 1] + __uint_as_float(bv[qp][(2 * e + 1) >> 2][(2 * e + 1) & 3]), 0.f));
+                    if (t < FUSE_PIXELS && ml < g.K) *reinterpret_cast<u32x4*>(stage_lds + t * FUSE_PITCH + ml * 2) = pk;
+                }
+            }
+        }
+        __syncthreads();
+        // (b) normalisation, window of 5 channels: y_c = x_c (k + alpha / n (x_{c-2}^2 + ... + x_{c+2}^2))^-beta
+        constexpr int ITEMS_MAX = FUSE_PIXELS * 24, PER = (ITEMS_MAX + NTH - 1) / NTH;
+        u32x4 keep[PER];
+        const int items = FUSE_PIXELS * groups;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int it = tid + u * NTH;
+            keep[u] = u32x4{0u, 0u, 0u, 0u};
+            if (it < items) {
+                const int t = it / groups, gc = it - t * groups;
+                const unsigned char* src = stage_lds + t * FUSE_PITCH + gc * 16;
+                const u32x4 m = *reinterpret_cast<const u32x4*>(src);
+                const uint32_t lft = gc > 0 ? *reinterpret_cast<const uint32_t*>(src - 4) : 0u;
+                const uint32_t rgt = gc < groups - 1 ? *reinterpret_cast<const uint32_t*>(src + 16) : 0u;
+                float v[12];                                     // channels c0 - 2 .. c0 + 9
+                v[0] = __uint_as_float(lft << 16); v[1] = __uint_as_float(lft & 0xFFFF0000u);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[2 + 2 * e] = __uint_as_float(m[e] << 16); v[3 + 2 * e] = __uint_as_float(m[e] & 0xFFFF0000u); }
+                v[10] = __uint_as_float(rgt << 16); v[11] = __uint_as_float(rgt & 0xFFFF0000u);
+                // channels beyond the last filter do not exist (a ragged last group holds whatever the padded filter rows gave: zeros)
+                float sq[12];
+#pragma unroll
+                for (int e = 0; e < 12; ++e) sq[e] = v[e] * v[e];
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float ss = ((sq[e] + sq[e + 1]) + sq[e + 2]) + (sq[e + 3] + sq[e + 4]);
+                    o[e] = v[e + 2] * pow_neg_beta(fmaf(a.f_a_over_n, ss, a.f_k), a.f_beta, a.f_b075 != 0);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) keep[u][e] = pack_bf16x2(o[2 * e], o[2 * e + 1]);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int it = tid + u * NTH;
+            if (it < items) {
+                const int t = it / groups, gc = it - t * groups;
+                *reinterpret_cast<u32x4*>(stage_lds + t * FUSE_PITCH + gc * 16) = keep[u];
+            }
+        }
+        __syncthreads();
+        // (c) pooling
+        const int per_img = a.f_ty * a.f_tx;
+        const int img = nt / per_img, rem = nt - img * per_img, ty = rem / a.f_tx, tx = rem - ty * a.f_tx;
+        const int pitems = FUSE_POOLED * FUSE_POOLED * groups;
+        for (int it = tid; it < pitems; it += NTH) {
+            const int pp = it / groups, gc = it - pp * groups;
+            const int pa = pp / FUSE_POOLED, pb = pp - pa * FUSE_POOLED;
+            const int oy = ty * FUSE_POOLED + pa, ox = tx * FUSE_POOLED + pb;            // pooled pixel in the image
+            if (oy >= a.f_PP || ox >= a.f_QQ) continue;
+            float best[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+#pragma unroll
+            for (int wy = 0; wy < 3; ++wy)
+#pragma unroll
+                for (int wx = 0; wx < 3; ++wx) {
+                    const int dy = 2 * pa + wy, dx = 2 * pb + wx;
+                    if (ty * (FUSE_SIDE - 1) + dy < g.P && tx * (FUSE_SIDE - 1) + dx < g.Q) {
+                        const u32x4 m = *reinterpret_cast<const u32x4*>(stage_lds + (dy * FUSE_SIDE + dx) * FUSE_PITCH + gc * 16);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            best[2 * e] = fmaxf(best[2 * e], __uint_as_float(m[e] << 16));
+                            best[2 * e + 1] = fmaxf(best[2 * e + 1], __uint_as_float(m[e] & 0xFFFF0000u));
+                        }
+                    }
+                }
+            uint16_t* dst = a.f_y + ((size_t)(img * a.f_PP + oy) * a.f_QQ + ox) * a.f_ctot + a.f_coff + gc * 8;
+            if (gc * 8 + 7 < g.K) {
+                u32x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk[e] = pack_bf16x2(best[2 * e], best[2 * e + 1]);
+                *reinterpret_cast<u32x4*>(dst) = pk;
+            } else {
+                for (int e = 0; e < 8; ++e)
+                    if (gc * 8 + e < g.K) dst[e] = f32_to_bf16(best[e]);
+            }
+        }
+    };
+
     // ---- pipeline.  Slice k lives in ring stage k % NS.  Iteration gi multiplies slice gi; after its first
     // k-step the workgroup meets: slice gi + 1 has landed and slice gi has been read completely, so the
     // loads of slice gi + NS go out into the stage slice gi leaves, and the remaining three k-steps
@@ -476,14 +637,31 @@ void conv_bf16_dma_kernel(const DArgs a)
     else wait_vmcnt<0>();
     ring_barrier();
     fetch_step(0, IC<0>{});
-    fetch_step(0, IC<1>{});
-    fetch_step(0, IC<2>{});
+    if constexpr (KB == 64) {
+        fetch_step(0, IC<1>{});
+        fetch_step(0, IC<2>{});
+    }
 
     int gi = 0, stage = 0;
     for (int t = 0; t < my_tiles; ++t) {
         zero_acc();
         for (int sl = 0; sl < nslices; ++sl, ++gi) {
             const int next_stage = stage + 1 == NS ? 0 : stage + 1;
+            if constexpr (KB == 32) {
+                // two k-steps per slice: the second step's operands leave LDS while the first multiplies; the workgroup then
+                // meets (slice gi + 1 has landed, slice gi has been read completely), the loads of slice gi + NS go out into
+                // the stage slice gi leaves, and the first step of slice gi + 1 is fetched while the second multiplies
+                fetch_step(stage, IC<1>{});
+                multiply_step(IC<0>{});
+                if (gi + 1 < total) {
+                    if (gi + NS - 1 < total) wait_vmcnt<(NS - 2) * L>();
+                    else wait_vmcnt<0>();
+                    ring_barrier();
+                    if (issued < total) { issue_slice(stage); ++issued; }
+                }
+                fetch_step(next_stage, IC<0>{});      // (after the last slice: reads nobody uses)
+                multiply_step(IC<1>{});
+            } else {
             multiply_step(IC<0>{});
             fetch_step(stage, IC<3>{});
             // With three or more stages a slice's loads have a whole further iteration to land, and the waves of the
@@ -510,35 +688,49 @@ void conv_bf16_dma_kernel(const DArgs a)
             multiply_step(IC<3>{});
             if (NS >= 3 && slot == 3) issue_slice(stage);
             fetch_step(next_stage, IC<2>{});
+            }
             stage = next_stage;
         }
-        epilogue(nt0 + t * gn);
+        if constexpr (FUSE) epilogue_block(nt0 + t * gn);     // (one tile per workgroup: see launch_block)
+        else epilogue(nt0 + t * gn);
     }
     wait_lgkm<0>();
 }
 
-template <int TM, int TN, int WGM, int WGN, int NS, int OCC>
+template <int TM, int TN, int WGM, int WGN, int NS, int OCC, int KB = 64, bool FUSE = false>
 int launch_cfg(DArgs a, hipStream_t st)
 {
-    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, NTH = WGM * WGN * 64, RP = WGM * WGN * 8;
-    constexpr int LDS = NS * (BM + BN) * 128 + 1024;
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, NTH = WGM * WGN * 64, CPR = KB / 8, RP = WGM * WGN * (512 / KB);
+    constexpr int LDS = NS * ((BM + RP - 1) / RP * RP + BN) * KB * 2 + 1024;
+    // slices of KB contraction elements: whole taps when the channel count allows, else runs of a filter row's S * C values
+    // that go on into the next row when that saves slices (see the kernel's header)
+    a.slices_per_run = (a.run_chunks + CPR - 1) / CPR;
+    a.slices_per_tile = a.g.R * a.slices_per_run;
+    a.flat = 0;
+    if (a.stem_wp) {
+        a.slices_per_tile = 4;                        // (launch_conv_bf16_stem: two window rows per slice; 64-deep slices only)
+    } else if (a.g.C % KB != 0 && a.run_chunks >= CPR && (a.g.R * a.run_chunks + CPR - 1) / CPR < a.slices_per_tile) {
+        a.flat = 1;                                   // slices that run on across filter rows save at least one slice per tile
+        a.slices_per_tile = (a.g.R * a.run_chunks + CPR - 1) / CPR;
+    }
     a.step_img = RP / (a.g.P * a.g.Q);
     a.step_p = (RP % (a.g.P * a.g.Q)) / a.g.Q;
     a.step_q = RP % a.g.Q;
     static_assert(LDS <= 160 * 1024, "LDS ring too large");
     a.grid_m = (a.g.K + BM - 1) / BM;
-    a.grid_n = (a.g.Ng + BN - 1) / BN;
+    if (!FUSE) a.grid_n = (a.g.Ng + BN - 1) / BN;      // (block kernel: the caller has counted the patches)
     // workgroups per channel block: what the device holds at once, at most one per pixel tile (a layer
     // with fewer tiles than that runs in a single round)
     static_assert(OCC * LDS <= 160 * 1024, "the ring does not fit OCC times");
     int gn = device_cus() * OCC / a.grid_m;
     if (gn < 1) gn = 1;
     if (gn > a.grid_n) gn = a.grid_n;
+    if (FUSE) gn = a.grid_n;                           // one patch per workgroup: its epilogue needs the whole ring
     const unsigned G = (unsigned)(gn * a.grid_m);
-    if (a.g.C % 64 == 0)
-        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true, OCC>), dim3(G), dim3(NTH), 0, st, a);
+    if (a.g.C % KB == 0)
+        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true, OCC, KB, FUSE>), dim3(G), dim3(NTH), 0, st, a);
     else
-        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, false, OCC>), dim3(G), dim3(NTH), 0, st, a);
+        hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, false, OCC, KB, FUSE>), dim3(G), dim3(NTH), 0, st, a);
     return check_launch("conv_bf16");
 }
 
@@ -576,8 +768,6 @@ int launch_auto(DArgs a, hipStream_t st)
     return launch_cfg<2, 1, 1, 4, 3, 2>(a, st);                                 // 64 x 128 tiles
 }
 
-inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
-
 }  // namespace
 
 SharedDeviceScope::SharedDeviceScope(bool on) : on_(on) { if (on_) ++t_shared_device; }
@@ -590,29 +780,56 @@ bool conv_bf16_dma_eligible(const ConvGeom& g, const void* x, const void* w)
            wb < (1ull << 31) && aligned16(x) && aligned16(w);
 }
 
-int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
-                         const uint16_t* residual, uint16_t* y, hipStream_t st, const ConvSplit* split)
+static DArgs base_args(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias, const uint16_t* residual, uint16_t* y)
 {
-    DArgs a;
+    DArgs a{};
     a.x = x; a.w = w; a.bias = bias; a.res = residual; a.y = y; a.g = g;
     a.grid_m = a.grid_n = 0;
     a.x_bytes = (int)((size_t)g.N * g.C * g.H * g.W * 2);
     a.w_bytes = (int)((size_t)g.K * g.Kg * 2);
     a.c8 = g.C / 8;
     a.run_chunks = g.S * a.c8;
-    a.slices_per_run = (a.run_chunks + 7) / 8;
+    a.slices_per_run = 0;                             // (the slice plan depends on the slice depth: launch_cfg)
     a.magic_c8 = (unsigned)((0x100000000ull + a.c8 - 1) / a.c8);
     a.m_pq = ((1ull << 40) + (unsigned)(g.P * g.Q) - 1) / (unsigned)(g.P * g.Q);
     a.m_q = ((1ull << 40) + (unsigned)g.Q - 1) / (unsigned)g.Q;
     a.pointwise = g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0;
     a.stem_hp = a.stem_wp = 0;
-    a.slices_per_tile = g.R * a.slices_per_run;
-    a.flat = 0;
-    if (g.C % 64 != 0 && a.run_chunks >= 8 && (g.R * a.run_chunks + 7) / 8 < a.slices_per_tile) {
-        a.flat = 1;                                   // slices that run on across filter rows save at least one slice per tile
-        a.slices_per_tile = (g.R * a.run_chunks + 7) / 8;
-    }
+    a.slices_per_tile = 0; a.flat = 0;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y) && (!residual || (g.res_ctot % 8 == 0 && aligned16(residual)));
+    a.nsplit = 0;
+    for (int d = 0; d < 4; ++d) { a.y_seg[d] = nullptr; a.ctot_seg[d] = 0; if (d < 3) a.split_end[d] = 0x7FFFFFFF; }
+    return a;
+}
+
+// The block kernel: y = maxpool3x3s2(lrn5(relu(conv(x) + bias))), ceil-mode pooling without padding, for layers the
+// streaming kernel takes with at most 192 filters.  One workgroup of eight waves per patch of 15 x 15 convolution pixels
+// (7 x 7 pooled ones) x all filters; neighbouring patches share one row / column of convolution pixels, which both compute.
+bool conv_bf16_block_eligible(const ConvGeom& g, const void* x, const void* w, const dr_pool& p, const dr_lrn& l)
+{
+    return conv_bf16_dma_eligible(g, x, w) && g.K <= 192 && g.K % 8 == 0 && l.local_size == 5 && p.kh == 3 && p.kw == 3 && p.stride_h == 2 &&
+           p.stride_w == 2 && p.pad_h == 0 && p.pad_w == 0 && g.P >= 1 && g.Q >= 1;
+}
+
+int launch_conv_bf16_block(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias, const dr_lrn& l, int PP, int QQ,
+                           uint16_t* y, int y_ctot, int y_coff, hipStream_t st)
+{
+    DArgs a = base_args(g, x, w, bias, nullptr, nullptr);
+    a.f_ty = (PP + FUSE_POOLED - 1) / FUSE_POOLED;
+    a.f_tx = (QQ + FUSE_POOLED - 1) / FUSE_POOLED;
+    a.f_PP = PP; a.f_QQ = QQ; a.f_ctot = y_ctot; a.f_coff = y_coff;
+    a.f_a_over_n = l.alpha / (float)l.local_size; a.f_beta = l.beta; a.f_k = l.k; a.f_b075 = l.beta == 0.75f;
+    a.f_y = y;
+    const long tiles = (long)g.N * a.f_ty * a.f_tx;
+    if (tiles >= (1l << 24)) return fail(DR_ERR_UNSUPPORTED, "conv + lrn + maxpool: more than 2^24 patches");
+    a.grid_n = (int)tiles;
+    return launch_cfg<3, 2, 2, 4, 2, 1, 64, true>(a, st);       // 192 filters x 256 pixel rows, eight waves of 96 x 64
+}
+
+int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
+                         const uint16_t* residual, uint16_t* y, hipStream_t st, const ConvSplit* split)
+{
+    DArgs a = base_args(g, x, w, bias, residual, y);
     a.nsplit = 0;
     if (split && split->n > 1) {
         a.nsplit = split->n;

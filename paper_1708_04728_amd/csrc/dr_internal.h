@@ -69,6 +69,12 @@ struct ConvSplit { int n; ConvDest dst[4]; };
 int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
                          const uint16_t* residual, uint16_t* y, hipStream_t st, const ConvSplit* split = nullptr);
 
+// conv_bf16_dma.hip: convolution, ReLU, LRN (window of 5) and 3x3 stride-2 max-pooling in one kernel (the streamlined
+// block's original form, Sec. 3.1); y is the pooled tensor (PP x QQ pixels per image, y_ctot channels, written from y_coff)
+bool conv_bf16_block_eligible(const ConvGeom& g, const void* x, const void* w, const dr_pool& p, const dr_lrn& l);
+int launch_conv_bf16_block(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias, const dr_lrn& l, int PP, int QQ,
+                           uint16_t* y, int y_ctot, int y_coff, hipStream_t st);
+
 // conv_bf16_dma.hip: inputs of at most 4 channels through a padded 4-channel copy (see the definition)
 bool conv_bf16_stem_eligible(const ConvGeom& g);
 int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias,

@@ -16,6 +16,16 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 }
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) { return (uint16_t)(pack_bf16x2(f, 0.f) & 0xFFFFu); }
 
+// s^-beta for the normalisation layers (Eq. (3)): beta = 0.75 as rsqrt(s) * sqrt(rsqrt(s)), 1 ulp hardware approximations
+__device__ __forceinline__ float pow_neg_beta(float s, float beta, bool b075)
+{
+    if (b075) {
+        const float r = __builtin_amdgcn_rsqf(s);
+        return r * __builtin_amdgcn_sqrtf(r);
+    }
+    return powf(s, -beta);
+}
+
 template <typename T> struct Store;
 template <> struct Store<float> {
     static constexpr int VN = 4;   // elements per 16 bytes

@@ -45,16 +45,7 @@ int relu_launch(const void* a, const void* b, void* y, size_t count, hipStream_t
 }
 
 // ---- LRN ---------------------------------------------------------------------------------------------
-// s^(-beta); beta = 0.75 (the value every workload uses) needs no transcendental:
-// s^-0.75 = rsqrt(s) * sqrt(rsqrt(s)).
-__device__ __forceinline__ float pow_neg_beta(float s, float beta, bool b075)
-{
-    if (b075) {
-        const float r = __builtin_amdgcn_rsqf(s);          // 1 ulp hardware approximations: s >= k > 0 here
-        return r * __builtin_amdgcn_sqrtf(r);
-    }
-    return powf(s, -beta);
-}
+// (s^-beta: pow_neg_beta in dr_store.h)
 
 // One thread owns V adjacent pixels (one 16-byte vector, or one element when V == 1) of one image and a
 // run of CH channels.  It first issues all CH + NL - 1 loads of the run and its halo (independent, so

@@ -241,9 +241,10 @@ __global__ __launch_bounds__(256) void maxpool3_front_kernel(const T* __restrict
     const unsigned pg = block % (unsigned)pgroups, n = block / (unsigned)pgroups;
     const int item = (int)pg * 256 + (int)threadIdx.x;
     if (item >= pstrips * QCV) return;
-    const int strip = (int)__umulhi((unsigned)item, qcv_magic);
+    // (a divisor of 1 has no 32-bit magic number: ceil(2^32 / 1) does not fit)
+    const int strip = QCV == 1 ? item : (int)__umulhi((unsigned)item, qcv_magic);
     const int pair = item - strip * QCV;
-    const int q = (int)__umulhi((unsigned)pair, cv_magic);
+    const int q = CV == 1 ? pair : (int)__umulhi((unsigned)pair, cv_magic);
     const int cv = pair - q * CV;
     const int p0 = (int)strip * PR;
     const int w0 = q * STRIDE - pad, h0 = p0 * STRIDE - pad;
@@ -344,15 +345,6 @@ int pool_launch(const dr_tensor& xd, const void* x, const dr_tensor& yd, void* y
 }
 
 // ---- LRN -------------------------------------------------------------------------------------------------
-__device__ __forceinline__ float pow_neg_beta(float s, float beta, bool b075)
-{
-    if (b075) {                       // s^-0.75 = rsqrt(s) * sqrt(rsqrt(s)), 1 ulp hardware approximations
-        const float r = __builtin_amdgcn_rsqf(s);
-        return r * __builtin_amdgcn_sqrtf(r);
-    }
-    return powf(s, -beta);
-}
-
 // Window of 5 channels.  A pixel occupies LPP = C / V consecutive lanes of one wave (PPW pixels per
 // wave, the remaining lanes idle), so the two channels on either side of a lane's vector live in the
 // neighbouring lanes and arrive by shuffle; the first / last lane of a pixel sees zeros instead.

@@ -92,7 +92,9 @@ def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False, pac
     fuse_nontensor: a maxpool directly followed by an lrn becomes one layer that makes a single pass over the
                tensor (channels-last tensors only); "all": so does an lrn directly followed by a maxpool
                (measured slower than the two layers on their own at stride 2: every input pixel is
-               normalised, four per output, and that arithmetic, not memory, bounds it).
+               normalised, four per output, and that arithmetic, not memory, bounds it); "block": a
+               conv - relu - lrn - maxpool run (3x3 pooling at stride 2, at most 192 filters, bf16) becomes the one
+               kernel of dr_conv_lrn_maxpool_fwd, and a maxpool - lrn pair one pass as with True.
 
     fuse_relu: a conv directly followed by a relu becomes one conv with the ReLU in its store
                (the slim form always runs this way; for the original form it is the "fused"
@@ -104,6 +106,15 @@ def net_descs(layers, c_in, inception_mode=0, fuse_relu=False, folded=False, pac
         if kind == "conv":
             relu = fuse_relu and i + 1 < len(layers) and layers[i + 1][0] == "relu"
             L.kind, L.conv = B.DR_LAYER_CONV, conv_desc(p, c, relu, pack)
+            nxt = [k for k, _ in layers[i + 1:i + 4]]
+            if (fuse_nontensor == "block" and nxt == ["relu", "lrn", "maxpool"] and p["k"] <= 192 and p["k"] % 8 == 0 and c % 8 == 0 and
+                    pack == "bf16" and layers[i + 2][1]["n"] == 5 and (layers[i + 3][1]["k"], layers[i + 3][1]["stride"], layers[i + 3][1]["pad"]) == (3, 2, 0)):
+                # the streamlined block's original form as one kernel (dr_conv_lrn_maxpool_fwd)
+                ql, qp = layers[i + 2][1], layers[i + 3][1]
+                L.kind = B.DR_LAYER_CONV_LRN_MAXPOOL
+                L.lrn, L.pool = B.dr_lrn(ql["n"], ql["alpha"], ql["beta"], ql["k"]), B.pool_desc(qp["k"], qp["stride"], qp["pad"])
+                i += 3
+                relu = False
             c = p["k"]
             if relu:
                 i += 1

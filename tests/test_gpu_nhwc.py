@@ -97,7 +97,9 @@ def test_conv2d_bf16_channel_offset():
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", [(2, 64, 112, 112, 3, 2, 0), (2, 192, 28, 28, 3, 1, 1), (1, 480, 28, 28, 3, 2, 0),
-                                  (2, 6, 7, 9, 3, 2, 0), (1, 8, 5, 5, 2, 2, 1), (1, 16, 9, 9, 3, 3, 1), (2, 512, 14, 14, 3, 1, 1), (1, 832, 7, 7, 3, 1, 1)])
+                                  (2, 6, 7, 9, 3, 2, 0), (1, 8, 5, 5, 2, 2, 1), (1, 16, 9, 9, 3, 3, 1), (2, 512, 14, 14, 3, 1, 1), (1, 832, 7, 7, 3, 1, 1),
+                                  # one 16-byte channel group per pixel (8 bf16 or 4 fp32 channels): 3x3 windows at strides 2 and 1
+                                  (2, 8, 15, 15, 3, 2, 0), (2, 4, 15, 15, 3, 2, 0), (1, 8, 9, 14, 3, 1, 1), (1, 4, 3, 1, 3, 2, 0)])
 def test_maxpool_nhwc_bit_exact(dtype, case):
     N, C, H, W, k, s, pad = case
     x = -np.abs(_vals(np.random.default_rng(5), (N, C, H, W), dtype)) - np.float32(0.5)
