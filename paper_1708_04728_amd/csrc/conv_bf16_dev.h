@@ -1,0 +1,88 @@
+// Device helpers shared by the bf16 convolution kernels that stream their operands into LDS with buffer loads:
+// vector types, the out-of-range offset, the hand-made barrier and counter waits, loads that write LDS, LDS reads the
+// compiler does not see, and small exact divisions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+namespace dr {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr;
+template <int V> using IC = std::integral_constant<int, V>;
+
+constexpr int OOB = (int)0x80000000;
+
+// Workgroup barrier between the slices.  A fence would make the compiler wait for every outstanding
+// load that writes LDS (vmcnt(0)), which is exactly the prefetch this kernel keeps in flight, so the
+// ordering is spelled out instead: the compiler may not move memory accesses across either side
+// (the empty asm statements), this wave's own LDS reads have returned (lgkmcnt(0)), and the arrival of
+// the operand loads is awaited by the caller with wait_vmcnt.
+__device__ __forceinline__ void ring_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0); vmcnt and expcnt left at their maxima
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// One 16-byte buffer load per lane that writes LDS directly: lane l of the wave fills bytes
+// [16 l, 16 l + 16) of the 1 KiB block at `lds` (wave-uniform); lanes whose voff lies outside the
+// descriptor's range write zeros.  (Only the device pass may see the builtin: in the host pass it
+// fails to type-check without a diagnostic and takes the kernel's launch stub with it.)
+__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t r, unsigned char* lds, int voff, int soff)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)lds, 16, voff, soff, 0, 0);
+#endif
+}
+
+// The same with 4 bytes per lane: lane l fills bytes [4 l, 4 l + 4) of the 256-byte block at `lds`.
+__device__ __forceinline__ void load_to_lds4(__amdgpu_buffer_rsrc_t r, void* lds, int voff)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)lds, 4, voff, 0, 0, 0);
+#endif
+}
+
+// LDS reads the compiler does not see (see the header): the data is valid after wait_lgkm + touch.
+template <int OFF>
+__device__ __forceinline__ u32x4 ds_read16(unsigned addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_lgkm()
+{
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void touch(u32x4& v) { asm volatile("" : "+v"(v)); }
+
+// v / d for 0 <= v < 2^24 and 1 <= d <= 2^16, exact: (v * ceil(2^40 / d)) >> 40.  With m = (2^40 + e) / d,
+// 0 <= e < d, the product is v / d + v e / (d 2^40) and the second term is below 2^-16 <= 1 / d.
+__device__ __forceinline__ int div_small(int v, unsigned long long m)
+{
+    return (int)(((unsigned long long)(unsigned)v * m) >> 40);
+}
+
+// bits lo..hi set (hi < lo: none); lo, hi in 0..15
+__device__ __forceinline__ unsigned bit_range(int lo, int hi) { return hi >= lo ? (2u << hi) - (1u << lo) : 0u; }
+
+}  // namespace
+}  // namespace dr

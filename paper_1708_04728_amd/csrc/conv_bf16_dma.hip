@@ -39,18 +39,10 @@
 
 #include "dr_internal.h"
 #include "dr_store.h"
+#include "conv_bf16_dev.h"
 
 namespace dr {
 namespace {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void* lds_ptr;
-template <int V> using IC = std::integral_constant<int, V>;
-
-constexpr int OOB = (int)0x80000000;
 
 struct DArgs {
     const uint16_t* x;
@@ -69,6 +61,8 @@ struct DArgs {
     unsigned magic_c8;        // ceil(2^32 / c8)
     unsigned long long m_pq, m_q;   // ceil(2^40 / (P*Q)), ceil(2^40 / Q)
     int vec_ok;               // 16-byte stores / bias / residual accesses are aligned
+    int exact_store;          // every lane issues each of a tile's stores (lanes without an output store out of range): see the epilogue
+    int y_bytes;              // bytes of the output tensor (exact_store only: below 2^31)
     int pointwise;            // 1x1 filter, stride 1, no padding
     int step_img, step_p, step_q;   // the pixels one pass of loads covers (8 per wave) as (images, rows, columns) of the output
     int stem_hp, stem_wp;     // rows / pixels per row of the padded 4-channel input copy (0: ordinary input)
@@ -91,71 +85,6 @@ struct DArgs {
 // Block kernel: pooled outputs per patch side, and the convolution pixels they need (3x3 windows at stride 2)
 constexpr int FUSE_POOLED = 7, FUSE_SIDE = 2 * FUSE_POOLED + 1, FUSE_PIXELS = FUSE_SIDE * FUSE_SIDE;
 constexpr int FUSE_PITCH = 400;     // bytes per staged pixel: 192 channels of bf16 + 16, so that 16 consecutive pixels cover every bank
-
-// Workgroup barrier between the slices.  A fence would make the compiler wait for every outstanding
-// load that writes LDS (vmcnt(0)), which is exactly the prefetch this kernel keeps in flight, so the
-// ordering is spelled out instead: the compiler may not move memory accesses across either side
-// (the empty asm statements), this wave's own LDS reads have returned (lgkmcnt(0)), and the arrival of
-// the operand loads is awaited by the caller with wait_vmcnt.
-__device__ __forceinline__ void ring_barrier()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0); vmcnt and expcnt left at their maxima
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
-// s_waitcnt vmcnt(N) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
-}
-
-// One 16-byte buffer load per lane that writes LDS directly: lane l of the wave fills bytes
-// [16 l, 16 l + 16) of the 1 KiB block at `lds` (wave-uniform); lanes whose voff lies outside the
-// descriptor's range write zeros.  (Only the device pass may see the builtin: in the host pass it
-// fails to type-check without a diagnostic and takes the kernel's launch stub with it.)
-__device__ __forceinline__ void load_to_lds16(__amdgpu_buffer_rsrc_t r, unsigned char* lds, int voff, int soff)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)lds, 16, voff, soff, 0, 0);
-#endif
-}
-
-// The same with 4 bytes per lane: lane l fills bytes [4 l, 4 l + 4) of the 256-byte block at `lds`.
-__device__ __forceinline__ void load_to_lds4(__amdgpu_buffer_rsrc_t r, void* lds, int voff)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr)lds, 4, voff, 0, 0, 0);
-#endif
-}
-
-// LDS reads the compiler does not see (see the header): the data is valid after wait_lgkm + touch.
-template <int OFF>
-__device__ __forceinline__ u32x4 ds_read16(unsigned addr)
-{
-    u32x4 v;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
-    return v;
-}
-template <int N>
-__device__ __forceinline__ void wait_lgkm()
-{
-    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void touch(u32x4& v) { asm volatile("" : "+v"(v)); }
-
-// v / d for 0 <= v < 2^24 and 1 <= d <= 2^16, exact: (v * ceil(2^40 / d)) >> 40.  With m = (2^40 + e) / d,
-// 0 <= e < d, the product is v / d + v e / (d 2^40) and the second term is below 2^-16 <= 1 / d.
-__device__ __forceinline__ int div_small(int v, unsigned long long m)
-{
-    return (int)(((unsigned long long)(unsigned)v * m) >> 40);
-}
-
-// bits lo..hi set (hi < lo: none); lo, hi in 0..15
-__device__ __forceinline__ unsigned bit_range(int lo, int hi) { return hi >= lo ? (2u << hi) - (1u << lo) : 0u; }
 
 // A workgroup is WGM x WGN waves (4 or 8), each with a tile of TM x TN blocks of 32 x 32.  OCC: workgroups per
 // compute unit the register allocation must leave room for (512 / (OCC * waves / 4) registers per lane).
@@ -204,6 +133,7 @@ void conv_bf16_dma_kernel(const DArgs a)
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, a.w_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rbias = __builtin_amdgcn_make_buffer_rsrc((void*)a.bias, 0, a.bias ? g.K * 4 : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc((void*)a.y, 0, a.exact_store ? a.y_bytes : 0, 0x00020000);
 
     // ---- persistent walk: workgroup b keeps channel block mt = b % grid_m and visits the pixel tiles
     // nt0, nt0 + gn, ... (gn = workgroups per channel block).  Consecutive workgroup ids are dealt
@@ -499,6 +429,55 @@ void conv_bf16_dma_kernel(const DArgs a)
         }
     };
 
+    // The same store for the common case (one destination, no residual, aligned, filters a multiple of 8, output below 2 GiB) as
+    // buffer stores that EVERY lane issues: a lane without an output (beyond the last pixel or filter) stores at an offset
+    // outside the tensor, which the hardware drops.  A tile then leaves exactly E = 2 TM TN store instructions per wave in
+    // the memory counter, and the waits for the operand loads of the next slices can allow for them (stores and loads share
+    // one counter; an unknown number of stores would force those waits to let every store drain first).
+    constexpr int E = 2 * TM * TN;
+    auto epilogue_exact = [&](int nt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            u32x4 bv[2][2];
+            bv[0][0] = ds_read16<0>(bias_rd + i * 128);
+            bv[0][1] = ds_read16<16>(bias_rd + i * 128);
+            bv[1][0] = ds_read16<64>(bias_rd + i * 128);
+            bv[1][1] = ds_read16<80>(bias_rd + i * 128);
+            wait_lgkm<0>();
+            touch(bv[0][0]); touch(bv[0][1]); touch(bv[1][0]); touch(bv[1][1]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = nt * BN + wn * WN + j * 32 + l32;
+                const int nbase = (n * g.y_ctot + g.y_coff) * 2;
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp) {
+                    float o[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][qp * 8 + e]),
+                                                                         __float_as_uint(acc[i][j][qp * 8 + 4 + e]), false, false);
+                        o[e] = __uint_as_float(sw[0]);
+                        o[4 + e] = __uint_as_float(sw[1]);
+                    }
+                    const int mb = m_lane + i * 32 + qp * 16;     // first of this lane's 8 channels
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] += __uint_as_float(bv[qp][e >> 2][e & 3]);
+                    if (g.relu) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] = fmaxf(o[e], 0.f);
+                    }
+                    u32x4 pk;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) pk[e] = pack_bf16x2(o[2 * e], o[2 * e + 1]);
+                    const int voff = (n < g.Ng && mb < g.K) ? nbase + mb * 2 : OOB;
+#if defined(__HIP_DEVICE_COMPILE__)
+                    __builtin_amdgcn_raw_buffer_store_b128(pk, ry, voff, 0, 0);
+#endif
+                }
+            }
+        }
+    };
+
     // ---- block kernel: what follows the contraction.  (a) bias + ReLU, rounded to bf16, into LDS as [pixel][channel] (the ring
     // is free: every load has landed and, after the barrier, every operand read has returned); (b) across-channel
     // normalisation in place: an item is 8 channels of a pixel, its window's two channels on either side come from the
@@ -642,11 +621,23 @@ void conv_bf16_dma_kernel(const DArgs a)
         fetch_step(0, IC<2>{});
     }
 
+    // Slices multiplied since the last tile's stores went out.  For NS - 1 slices after a tile with exact stores its E stores are
+    // younger than the slice being awaited, like the NS - 2 slices of loads behind it: the wait allows for them.
+    constexpr bool ALLOW_STORES = (NS - 2) * L + E <= 63;
+    const bool exact = ALLOW_STORES && a.exact_store;
+    int since_epi = NS;
+    auto wait_next_slice = [&](int gi_) __attribute__((always_inline)) {      // this wave's loads of slice gi_ + 1 have landed
+        if (gi_ + NS - 1 < total) {
+            if (since_epi <= NS - 1) wait_vmcnt<ALLOW_STORES ? (NS - 2) * L + E : 0>();
+            else wait_vmcnt<(NS - 2) * L>();
+        } else wait_vmcnt<0>();
+    };
     int gi = 0, stage = 0;
     for (int t = 0; t < my_tiles; ++t) {
         zero_acc();
         for (int sl = 0; sl < nslices; ++sl, ++gi) {
             const int next_stage = stage + 1 == NS ? 0 : stage + 1;
+            ++since_epi;
             if constexpr (KB == 32) {
                 // two k-steps per slice: the second step's operands leave LDS while the first multiplies; the workgroup then
                 // meets (slice gi + 1 has landed, slice gi has been read completely), the loads of slice gi + NS go out into
@@ -654,8 +645,7 @@ void conv_bf16_dma_kernel(const DArgs a)
                 fetch_step(stage, IC<1>{});
                 multiply_step(IC<0>{});
                 if (gi + 1 < total) {
-                    if (gi + NS - 1 < total) wait_vmcnt<(NS - 2) * L>();
-                    else wait_vmcnt<0>();
+                    wait_next_slice(gi);
                     ring_barrier();
                     if (issued < total) { issue_slice(stage); ++issued; }
                 }
@@ -670,8 +660,7 @@ void conv_bf16_dma_kernel(const DArgs a)
             int slot = -1;
             if (gi + 1 < total) {
                 // this wave's loads of slice gi + 1 have landed once at most the NS - 2 slices behind it are pending
-                if (gi + NS - 1 < total) wait_vmcnt<(NS - 2) * L>();
-                else wait_vmcnt<0>();
+                wait_next_slice(gi);
                 ring_barrier();
                 if (issued < total) {
                     slot = NS >= 3 ? (wave & 3) : 0;
@@ -692,6 +681,7 @@ void conv_bf16_dma_kernel(const DArgs a)
             stage = next_stage;
         }
         if constexpr (FUSE) epilogue_block(nt0 + t * gn);     // (one tile per workgroup: see launch_block)
+        else if (exact) { epilogue_exact(nt0 + t * gn); since_epi = 0; }
         else epilogue(nt0 + t * gn);
     }
     wait_lgkm<0>();
@@ -799,6 +789,11 @@ static DArgs base_args(const ConvGeom& g, const uint16_t* x, const uint16_t* w, 
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y) && (!residual || (g.res_ctot % 8 == 0 && aligned16(residual)));
     a.nsplit = 0;
     for (int d = 0; d < 4; ++d) { a.y_seg[d] = nullptr; a.ctot_seg[d] = 0; if (d < 3) a.split_end[d] = 0x7FFFFFFF; }
+    // stores that every lane issues (see the kernel's epilogue): one destination, no residual, whole aligned channel groups, and
+    // byte offsets into the output that fit the buffer instruction's 31 bits
+    const double ybytes = (double)g.Ng * g.y_ctot * 2.0;
+    a.exact_store = y && a.vec_ok && !residual && g.K % 8 == 0 && ybytes < 2147483648.0;
+    a.y_bytes = a.exact_store ? (int)ybytes : 0;
     return a;
 }
 
@@ -833,6 +828,7 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
     a.nsplit = 0;
     if (split && split->n > 1) {
         a.nsplit = split->n;
+        a.exact_store = 0;                            // (several destinations: the ordinary store)
         int start = 0;
         for (int d = 0; d < 4; ++d) {
             if (d < split->n) {
@@ -883,6 +879,9 @@ int launch_conv_bf16_stem(const ConvGeom& real, const uint16_t* xp, int hp, int 
     a.stem_hp = hp; a.stem_wp = wp;
     a.nsplit = 0;
     a.vec_ok = g.y_ctot % 8 == 0 && g.y_coff % 8 == 0 && aligned16(y);
+    const double ybytes = (double)g.Ng * g.y_ctot * 2.0;
+    a.exact_store = a.vec_ok && g.K % 8 == 0 && ybytes < 2147483648.0;
+    a.y_bytes = a.exact_store ? (int)ybytes : 0;
     return launch_auto(a, st);
 }
 

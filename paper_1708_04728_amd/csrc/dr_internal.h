@@ -69,6 +69,12 @@ struct ConvSplit { int n; ConvDest dst[4]; };
 int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias,
                          const uint16_t* residual, uint16_t* y, hipStream_t st, const ConvSplit* split = nullptr);
 
+// conv_bf16_patch.hip: filters of several taps at stride 1, C % 64 == 0, maps at most 256 pixels wide whose patch of
+// TH + R - 1 input rows fits LDS: the tile's input patch is loaded once and every tap multiplies from there
+bool conv_bf16_patch_eligible(const ConvGeom& g, const void* x, const void* w, const void* y);
+// tm: 32-filter blocks per workgroup (2 or 3); 0 = the launcher's choice
+int launch_conv_bf16_patch(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias, uint16_t* y, hipStream_t st, int tm = 0);
+
 // conv_bf16_dma.hip: convolution, ReLU, LRN (window of 5) and 3x3 stride-2 max-pooling in one kernel (the streamlined
 // block's original form, Sec. 3.1); y is the pooled tensor (PP x QQ pixels per image, y_ctot channels, written from y_coff)
 bool conv_bf16_block_eligible(const ConvGeom& g, const void* x, const void* w, const dr_pool& p, const dr_lrn& l);
