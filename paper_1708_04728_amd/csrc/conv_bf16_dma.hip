@@ -214,7 +214,7 @@ void conv_bf16_dma_kernel(const DArgs a)
                 // packed small-channel input (see launch_conv_bf16_stem): chunk lc of a slice is pixel pair lc & 3 of
                 // window row lc >> 2; nothing is ever outside the padded copy
                 b_base[i] = ((img * a.stem_hp + p * g.sh + (lc >> 2)) * a.stem_wp + q * g.sw + 2 * (lc & 3)) * 8;
-                b_mask[i] = n < g.Ng ? 0xFFFFEu : 0xFFFFu;
+                b_mask[i] = n < g.Ng ? 0xFFFFFEu : 0xFFFFu;          // (every "filter row", at most 8, is inside)
             } else {
                 const int ih0 = p * g.sh - g.ph, iw0 = q * g.sw - g.pw;
                 b_base[i] = (((img * g.H + ih0) * g.W + iw0) * g.C + lc * 8) * 2;
@@ -698,7 +698,7 @@ int launch_cfg(DArgs a, hipStream_t st)
     a.slices_per_tile = a.g.R * a.slices_per_run;
     a.flat = 0;
     if (a.stem_wp) {
-        a.slices_per_tile = 4;                        // (launch_conv_bf16_stem: two window rows per slice; 64-deep slices only)
+        a.slices_per_tile = a.g.R;                    // (launch_conv_bf16_stem: one "filter row" per slice)
     } else if (a.g.C % KB != 0 && a.run_chunks >= CPR && (a.g.R * a.run_chunks + CPR - 1) / CPR < a.slices_per_tile) {
         a.flat = 1;                                   // slices that run on across filter rows save at least one slice per tile
         a.slices_per_tile = (a.g.R * a.run_chunks + CPR - 1) / CPR;
