@@ -231,6 +231,25 @@ def test_inception_stacked_first_steps(form, module):
     assert np.array_equal(G.to_host(y), plain)
 
 
+def test_inception_3a_paper_variant_bf16_full_batch():
+    """The module slimmed the way the paper's own example does it (Sec. 3.2: 3x3 reducer 96 -> 48, the 1x1 branch absorbed into
+    a 3x3 of 192 filters, the pool branch into a 5x5 of 64 filters) in the benchmark's dtype and layout, on a full batch of
+    128 maps of 28 x 28 x 192, every image against the mirrored oracle, in the execution modes the benchmark uses."""
+    layer = workloads.inception_3a_paper_variant()
+    params = [{"w": workloads.round_to_bf16(q["w"]), "b": q["b"]} for q in workloads.make_params(2, "slim", layers=[layer])]
+    rng = np.random.default_rng(31)
+    x = workloads.round_to_bf16(np.abs(rng.standard_normal((128, 192, 28, 28))).astype(np.float32))
+    ref = oracle_in_chunks(lambda c: oracle.forward([layer], params, c, mirror_bf16=True), x, 32)
+    assert ref.shape == (128, 256, 28, 28)
+    base = B.DR_FUSE_RELU | B.DR_FUSE_CONCAT
+    outs = []
+    for mode in (0, base, base | B.DR_FUSE_STACK):
+        got = run_net_bf16([layer], params, x, inception_mode=mode)
+        assert close(got, ref, TOL_BF16, "128 images, mode %d" % mode)
+        outs.append(got)
+    assert np.array_equal(outs[1], outs[2])          # stacked first steps: the same sums in the same order
+
+
 def test_config5_googlenet_original_structure_fused():
     """The original structure with every fusion that leaves the function unchanged: ReLU and concat in the
     convolution stores, stacked first steps, LRN and pooling of the stem in one pass each.  Same network,
