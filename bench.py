@@ -89,7 +89,7 @@ def ceilings():
     import torch
     lib = C.CDLL(os.path.join(ROOT, "paper_1708_04728_amd", "libdr_ceilings.so"))
     vp, z, i = C.c_void_p, C.c_size_t, C.c_int
-    lib.drc_mfma_bf16.argtypes = lib.drc_mfma_f32.argtypes = [vp, i, i, vp]
+    lib.drc_mfma_bf16.argtypes = lib.drc_mfma_f32.argtypes = lib.drc_mfma_bf16_data.argtypes = [vp, i, i, vp]
     lib.drc_copy16.argtypes = [vp, vp, z, i, vp]
     lib.drc_read16.argtypes = [vp, vp, z, i, i, vp]
     st = torch.cuda.current_stream()
@@ -115,6 +115,10 @@ def ceilings():
         blocks = cus * wg_per_cu
         ms = best_ms(lambda: lib.drc_mfma_bf16(vp(out.data_ptr()), iters, blocks, sp))
         res["mfma"]["bf16_32x32x16_tflops_%dwave_per_simd" % wg_per_cu] = round(2.0 * 32 * 32 * 16 * 4 * iters * 4 * blocks / (ms * 1e-3) / 1e12, 1)
+        ms = best_ms(lambda: lib.drc_mfma_bf16_data(vp(out.data_ptr()), iters, blocks, sp))
+        res["mfma"]["bf16_32x32x16_tflops_%dwave_per_simd_varying_operands" % wg_per_cu] = round(2.0 * 32 * 32 * 16 * 4 * iters * 4 * blocks / (ms * 1e-3) / 1e12, 1)
+        ticks = out[:2].tolist()
+        res["mfma"]["shader_clock_GHz_%dwave_per_simd_varying_operands" % wg_per_cu] = round(ticks[0] / max(ticks[1], 1.0) * 0.1, 3)
         ms = best_ms(lambda: lib.drc_mfma_f32(vp(out.data_ptr()), iters, blocks, sp))
         res["mfma"]["f32_32x32x2_tflops_%dwave_per_simd" % wg_per_cu] = round(2.0 * 32 * 32 * 2 * 4 * iters * 4 * blocks / (ms * 1e-3) / 1e12, 1)
     for mib in (8, 32, 64, 128, 256, 512, 1024):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdeeprebirth.so")
 CEILINGS_LIB = os.path.join(HERE, "libdr_ceilings.so")      # measuring aids for bench.py --ceilings; not linked into the library
-SOURCES = ["api.hip", "conv_f32.hip", "conv_bf16.hip", "conv_bf16_dma.hip", "conv_bf16_patch.hip", "pointwise.hip", "pointwise_nhwc.hip", "train.hip"]
+SOURCES = ["api.hip", "conv_f32.hip", "conv_bf16.hip", "conv_bf16_dma.hip", "conv_bf16_patch.hip", "conv_bf16_rows.hip", "pointwise.hip", "pointwise_nhwc.hip", "train.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          # hipcc may otherwise pair fp32 operations into packed instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

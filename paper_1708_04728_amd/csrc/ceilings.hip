@@ -29,6 +29,52 @@ __global__ __launch_bounds__(256) void mfma_bf16_kernel(float* out, int iters, f
     if (s == 12345.f) out[threadIdx.x] = s;          // keeps the loop alive; never true for the values used
 }
 
+// The two clocks a kernel can read: the shader clock (s_memtime) and the constant 100 MHz reference (s_memrealtime).
+// Their ratio over a stretch of code is the frequency the compute units ran at during it.
+__device__ __forceinline__ unsigned long long shader_ticks()
+{
+    unsigned long long t;
+    asm volatile("s_memtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
+    return t;
+}
+__device__ __forceinline__ unsigned long long reference_ticks()
+{
+    unsigned long long t;
+    asm volatile("s_memrealtime %0\n s_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
+    return t;
+}
+
+// The same instruction stream on operands that differ from lane to lane and from instruction to instruction (values
+// in [-1, 1) from a hash of the lane's id), as a real layer's do: what the matrix cores sustain when the multipliers see
+// changing data, and at which clock.  The first wave writes its shader-clock and reference-clock ticks to out[0], out[1].
+__global__ __launch_bounds__(256) void mfma_bf16_data_kernel(float* out, int iters)
+{
+    f32x16 acc[4];
+    bf16x8 va[4], vb[4];
+    unsigned h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+    for (int i = 0; i < 4; ++i)
+        for (int e = 0; e < 8; ++e) {
+            h = h * 1664525u + 1013904223u;
+            va[i][e] = (__bf16)((float)(int)(h >> 8 & 0xFFFF) * (1.f / 32768.f) - 1.f);
+            h = h * 1664525u + 1013904223u;
+            vb[i][e] = (__bf16)((float)(int)(h >> 8 & 0xFFFF) * (1.f / 32768.f) - 1.f);
+        }
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const unsigned long long s0 = shader_ticks(), r0 = reference_ticks();
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], vb[i], acc[i], 0, 0, 0);
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i) s += acc[i][0];
+    const unsigned long long s1 = shader_ticks(), r1 = reference_ticks();
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        out[0] = (float)(s1 - s0);
+        out[1] = (float)(r1 - r0);
+    }
+    if (s == 12345.f) out[2 + threadIdx.x] = s;
+}
+
 // The same with the fp32 instruction (32x32x2: 2 * 32 * 32 * 2 FLOP each).
 __global__ __launch_bounds__(256) void mfma_f32_kernel(float* out, int iters, float a)
 {
@@ -73,6 +119,15 @@ int drc_mfma_bf16(float* out, int iters, int blocks, void* stream)
 {
     if (!out || iters < 1 || blocks < 1) return 2;
     hipLaunchKernelGGL(mfma_bf16_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, iters, 1.f);
+    return done();
+}
+
+// The same count of FLOP on lane-varying operands; out[0], out[1] receive the first wave's shader-clock and
+// 100 MHz reference-clock ticks over the loop (out: at least 2 KiB).
+int drc_mfma_bf16_data(float* out, int iters, int blocks, void* stream)
+{
+    if (!out || iters < 1 || blocks < 1) return 2;
+    hipLaunchKernelGGL(mfma_bf16_data_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, out, iters);
     return done();
 }
 

@@ -370,6 +370,7 @@ int launch_conv_bf16(const ConvGeom& g, const uint16_t* x, const uint16_t* w, co
     TraceScope trace("conv_bf16", &g, g.Ng, st);
     // several taps at stride 1 on few channels: the input patch of a tile is loaded once for all taps (conv_bf16_patch.hip)
     if (!residual && conv_bf16_patch_eligible(g, x, w, y)) return launch_conv_bf16_patch(g, x, w, bias, y, st);
+    if (!residual && conv_bf16_rows_eligible(g, x, w, y)) return launch_conv_bf16_rows(g, x, w, bias, y, st);
     if (conv_bf16_dma_eligible(g, x, w)) return launch_conv_bf16_dma(g, x, w, bias, residual, y, st);
     const size_t xb = (size_t)g.N * g.C * g.H * g.W * 2, wb = (size_t)g.K * g.Kg * 2;
     if (g.nhwc && g.w_krsc && g.C % 8 == 0 && xb < (1ull << 31) && wb < (1ull << 31)) {

@@ -7,6 +7,8 @@
 
 #include <type_traits>
 
+#include "dr_store.h"
+
 namespace dr {
 namespace {
 
@@ -83,6 +85,57 @@ __device__ __forceinline__ int div_small(int v, unsigned long long m)
 
 // bits lo..hi set (hi < lo: none); lo, hi in 0..15
 __device__ __forceinline__ unsigned bit_range(int lo, int hi) { return hi >= lo ? (2u << hi) - (1u << lo) : 0u; }
+
+// Bias + ReLU + bf16 store of a wave's TM x TN blocks of 32 filters x 32 pixels held in the matrix instruction's result
+// layout (lane = pixel l32 of the block and half h; register v = filter 8 (v / 4) + 4 h + v % 4 of the block).  Two lanes
+// that hold the same pixel exchange halves so that each ends up with 8 consecutive filters, 16 bytes of the pixel's
+// channel run.  bias_rd: LDS address of the filter block's biases (128 floats) plus 32 h bytes; m_lane: first filter
+// of the workgroup's block plus 8 h; nbase[j]: byte offset of the pixel's first channel written; n_ok[j]: the pixel
+// exists.  Every lane issues all 2 TM TN stores (those without a destination with an offset outside the buffer), so the
+// memory counter holds an exact number of them afterwards.
+template <int TM, int TN>
+__device__ __forceinline__ void store_blocks(const f32x16 (&acc)[TM][TN], unsigned bias_rd, int m_lane, int K, int relu,
+                                             __amdgpu_buffer_rsrc_t ry, const int (&nbase)[TN], const bool (&n_ok)[TN])
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        u32x4 bv[2][2];
+        bv[0][0] = ds_read16<0>(bias_rd + i * 128);
+        bv[0][1] = ds_read16<16>(bias_rd + i * 128);
+        bv[1][0] = ds_read16<64>(bias_rd + i * 128);
+        bv[1][1] = ds_read16<80>(bias_rd + i * 128);
+        wait_lgkm<0>();
+        touch(bv[0][0]); touch(bv[0][1]); touch(bv[1][0]); touch(bv[1][1]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int qp = 0; qp < 2; ++qp) {
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][qp * 8 + e]),
+                                                                     __float_as_uint(acc[i][j][qp * 8 + 4 + e]), false, false);
+                    o[e] = __uint_as_float(sw[0]);
+                    o[4 + e] = __uint_as_float(sw[1]);
+                }
+                const int mb = m_lane + i * 32 + qp * 16;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] += __uint_as_float(bv[qp][e >> 2][e & 3]);
+                if (relu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = fmaxf(o[e], 0.f);
+                }
+                u32x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk[e] = pack_bf16x2(o[2 * e], o[2 * e + 1]);
+                const int voff = (n_ok[j] && mb < K) ? nbase[j] + mb * 2 : OOB;
+#if defined(__HIP_DEVICE_COMPILE__)
+                __builtin_amdgcn_raw_buffer_store_b128(pk, ry, voff, 0, 0);
+#endif
+            }
+        }
+    }
+}
 
 }  // namespace
 }  // namespace dr

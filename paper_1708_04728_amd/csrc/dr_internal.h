@@ -74,6 +74,10 @@ int launch_conv_bf16_dma(const ConvGeom& g, const uint16_t* x, const uint16_t* w
 bool conv_bf16_patch_eligible(const ConvGeom& g, const void* x, const void* w, const void* y);
 // tm: 32-filter blocks per workgroup (2 or 3); 0 = the launcher's choice
 int launch_conv_bf16_patch(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias, uint16_t* y, hipStream_t st, int tm = 0);
+// conv_bf16_rows.hip: the same idea for up to 64 channels (a multiple of 16) on maps of any size: a tile is a run of
+// output rows of the whole batch's row stack, image borders inside it allowed
+bool conv_bf16_rows_eligible(const ConvGeom& g, const void* x, const void* w, const void* y);
+int launch_conv_bf16_rows(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias, uint16_t* y, hipStream_t st);
 
 // conv_bf16_dma.hip: convolution, ReLU, LRN (window of 5) and 3x3 stride-2 max-pooling in one kernel (the streamlined
 // block's original form, Sec. 3.1); y is the pooled tensor (PP x QQ pixels per image, y_ctot channels, written from y_coff)

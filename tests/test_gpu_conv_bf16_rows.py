@@ -1,0 +1,106 @@
+"""GPU parity of the row-stack patch convolution kernel (bf16 NHWC, several taps at stride 1 on maps with 16, 32, 48 or 64
+channels: a tile is a run of output rows of the whole batch's row stack -- image borders inside it allowed -- whose input
+patch is loaded into LDS once) against the fp64 oracle.  The library picks the kernel by rule, restated in `takes` below;
+every case satisfies it (and not the rule of the 64-channel patch kernel, which the library asks first), so what is
+compared is this kernel.  The cases put image borders at every position inside a tile, several images in one tile,
+tiles that end behind the last image, ragged filter blocks, filter rows whose last 64-deep slice is partly empty, and
+rectangular filters."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from paper_1708_04728_amd import binding as B
+from test_gpu_conv_bf16_patch import rows_per_tile as patch_kernel_rows
+from util import TOL_BF16, case_seed, close, empty_nhwc, gpu, gpu_nhwc, host_nhwc
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+CUS = 256
+
+
+def takes(N, C, H, W, K, R, S, stride, pad):
+    """The rule of the library's launcher, restated: stacked output rows per tile, 0 = the layer goes elsewhere."""
+    P, Q = oracle.conv_out_size(H, R, stride, pad), oracle.conv_out_size(W, S, stride, pad)
+    if C % 16 or C > 64 or K % 8 or stride != 1 or R * S < 2 or R > 7 or S > 7 or P < 2 or Q < 2 or Q > 256:
+        return 0
+    tm = 3 if (K + 95) // 96 * 96 <= (K + 63) // 64 * 64 else 2
+    budget = 80 * 1024 - (2 * tm * 32 * 128 + 512 + 1024)
+    th = min(256 // Q, N * P)
+    while th >= 1:
+        segs = min(N, (th + P - 2) // P + 1)
+        patch = ((th + (R - 1) * segs) * (W + 2 * pad) * (C // 8 + 1) * 16 + 4095) // 4096 * 4096
+        if patch <= budget:
+            break
+        th -= 1
+    if th < 1 or th * Q * 4 < 256 * 3:
+        return 0
+    tiles, blocks = (N * P + th - 1) // th, (K + tm * 32 - 1) // (tm * 32)
+    return th if tiles * blocks * 4 >= CUS else 0
+
+
+# N, C, H, W, K, R, S, stride, pad
+CASES = [
+    (12, 16, 28, 28, 128, 5, 5, 1, 2),     # GoogLeNet 3a's slim 5x5: 9 rows per tile, image borders at every offset; 25 k-steps = 6 slices + 1 step
+    (8, 32, 28, 28, 288, 5, 5, 1, 2),      # 3b's: three blocks of 96 filters
+    (40, 16, 14, 14, 304, 5, 5, 1, 2),     # 4a's: 18 rows per tile, up to three images in a tile; 304 = 3 x 96 + 16 filters
+    (84, 32, 14, 14, 72, 5, 5, 1, 2),      # ragged single block of 96
+    (70, 32, 7, 7, 320, 5, 5, 1, 2),       # 7 x 7 maps: 36 rows per tile, six images in a tile, the last tile ends behind the batch
+    (64, 48, 7, 7, 320, 3, 3, 1, 1),       # 48 channels (three k-steps per tap)
+    (80, 64, 10, 10, 136, 3, 3, 1, 1),     # 64 channels on maps too small for the 64-channel patch kernel: 22 rows per tile, four images
+    (70, 16, 9, 30, 40, 3, 5, 1, 1),       # 3x5 filter, padding 1: output 7 x 28
+    (25, 32, 12, 17, 200, 2, 2, 1, 0),     # 2x2 filter without padding: output 11 x 16, 16 rows per tile
+    (24, 16, 10, 100, 24, 3, 3, 1, 1),     # wide map: two rows of 100 per tile
+    (20, 32, 31, 23, 96, 7, 1, 1, 3),      # 7x1 filter, padded by 3 both ways
+]
+
+
+def _check(case, relu, bias, images=None):
+    N, C, H, W, K, R, S, stride, pad = case
+    assert takes(*case) > 0, "the case must be one the row-stack kernel takes"
+    assert patch_kernel_rows(C, H, W, K, R, S, stride, pad) == 0, "... and the 64-channel patch kernel does not"
+    rng = np.random.default_rng(case_seed(case))
+    x = workloads.round_to_bf16(rng.standard_normal((N, C, H, W)).astype(np.float32))
+    w = workloads.round_to_bf16(rng.standard_normal((K, C, R, S)).astype(np.float32) * np.float32(np.sqrt(2.0 / (C * R * S))))
+    b = (rng.standard_normal(K) * 0.1).astype(np.float32) if bias else None
+    P, Q = oracle.conv_out_size(H, R, stride, pad), oracle.conv_out_size(W, S, stride, pad)
+    # written at a channel offset of a wider tensor (a branch of a module writing its part of the concatenated output)
+    ctot, coff = K + 24, 16
+    y = B.NHWC(torch.full((N, P, Q, ctot), -5.0, dtype=torch.bfloat16, device="cuda"))
+    B.conv2d_fwd(gpu_nhwc(x, "bf16"), B.conv_desc(K, C, R, S, stride, pad, relu, B.DR_KRSC), B.pack_filters(gpu(w, "bf16")),
+                 gpu(b) if bias else None, y, y_c_offset=coff)
+    torch.cuda.synchronize()
+    got = host_nhwc(y)
+    assert not np.isnan(got).any()
+    assert (got[:, :coff] == -5.0).all() and (got[:, coff + K:] == -5.0).all()
+    pick = list(range(N)) if images is None else images
+    ref = oracle.conv2d(x[pick], w, b, stride, pad, relu)
+    assert close(got[pick, coff:coff + K], ref, TOL_BF16)
+    assert close(got[pick, coff:coff + K], oracle.round_bf16(ref), 2.0 ** -7, "within one bf16 unit of the oracle")
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_conv_rows(case):
+    _check(case, relu=case_seed(case) % 2 == 0, bias=case_seed(case) % 3 != 0)
+
+
+def test_conv_rows_many_tiles_per_workgroup():
+    # 128 images of 28 x 28 with one block of filters: 399 tiles on 256 x 2 workgroup slots; with three blocks 1197 on
+    # 510, so workgroups walk two or three tiles and the next tile's patch is requested before the last one's store
+    _check((128, 32, 28, 28, 96, 5, 5, 1, 2), relu=True, bias=True, images=[0, 1, 63, 126, 127])
+    _check((128, 16, 28, 28, 264, 5, 5, 1, 2), relu=False, bias=True, images=[0, 77, 127])
+
+
+def test_layers_the_rule_leaves_out_still_match():
+    # few tiles (the streaming kernel's smaller tiles fill the device better) and 24 channels (not a multiple of 16)
+    for case in [(1, 16, 28, 28, 32, 5, 5, 1, 2), (4, 24, 14, 14, 64, 5, 5, 1, 2)]:
+        assert takes(*case) == 0
+        N, C, H, W, K, R, S, stride, pad = case
+        rng = np.random.default_rng(case_seed(case))
+        x = workloads.round_to_bf16(rng.standard_normal((N, C, H, W)).astype(np.float32))
+        w = workloads.round_to_bf16(rng.standard_normal((K, C, R, S)).astype(np.float32) * np.float32(np.sqrt(2.0 / (C * R * S))))
+        y = empty_nhwc((N, K, oracle.conv_out_size(H, R, stride, pad), oracle.conv_out_size(W, S, stride, pad)), "bf16")
+        B.conv2d_fwd(gpu_nhwc(x, "bf16"), B.conv_desc(K, C, R, S, stride, pad, False, B.DR_KRSC), B.pack_filters(gpu(w, "bf16")), None, y)
+        torch.cuda.synchronize()
+        assert close(host_nhwc(y), oracle.conv2d(x, w, None, stride, pad, False), TOL_BF16)
