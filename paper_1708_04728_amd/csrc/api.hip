@@ -279,6 +279,8 @@ int padded_conv_run(const char* who, const dr_tensor& xd, const void* x, const d
             g.c_logical = 0;
             DR_TRY(launch_stem_pack_bf16(x, xbuf, xd.n, xd.c, xd.h, xd.w, cd.pad_h, cd.pad_w, hp, wp, st));
             DR_TRY(launch_stem_filters_bf16(w, wbuf, cd.k, cd.c, cd.r, cd.s, g.w_krsc, st));
+            if (conv_bf16_rows_stem_eligible(g, hp, wp, xbuf, y))
+                return launch_conv_bf16_rows_stem(g, (const uint16_t*)xbuf, hp, wp, (const uint16_t*)wbuf, bias, (uint16_t*)y, st);
             return launch_conv_bf16_stem(g, (const uint16_t*)xbuf, hp, wp, (const uint16_t*)wbuf, bias, (uint16_t*)y, st);
         }
     }

@@ -38,12 +38,17 @@ struct RArgs {
     int grid_m, tiles;                   // filter blocks, pixel tiles
     int x_bytes, w_bytes, y_bytes;
     int TH, THQ;                         // stacked output rows per tile, outputs per tile
-    int PW, NP, CCH, J;                  // patch row pitch (pixels); chunks per patch pixel (C / 8 + 1); C / 8; C / 16
-    int PR;                              // rows of an image with its padding: P + R - 1
+    int PW, NP, CCH, J;                  // patch row pitch (pixels); chunks per patch pixel (C / 8 + 1); C / 8; k-steps per tap
+    int PR;                              // rows of an image as the patch sees it: with its padding, H + 2 pad_h (packed input: hp)
     int rows_max, passes;                // patch rows of a tile (the most any tile needs); 4 KiB load passes
     int U, nslices, tail_chunks;         // k-steps; filter slices; 16-byte chunks of a filter's row in the last slice
-    int row_skip;                        // bytes from behind the last tap of a filter row to tap 0 of the next patch row
-    unsigned magic_np, magic_pw, magic_q, magic_p, magic_pr;   // ceil(2^32 / d) for d = NP, PW, Q, P, PR
+    int Kg;                              // elements of a filter's row in memory
+    int taps_per_row;                    // taps the k-steps walk along a patch row before the next filter row
+    int tap_skip, row_skip;              // bytes from behind a tap's last k-step to the next tap / on top of that to the next filter row
+    int row_mul, D;                      // patch row of output row dp in image img0 + io, filter row 0: row_mul dp + io D
+    int row_chunks, px_chunks;           // chunks per patch row; chunks from one output pixel's window to the next one's
+    int packed, wp;                      // input is the padded 4-channel copy xp[N][PR][wp][4] (see launch_conv_bf16_rows_stem)
+    unsigned magic_np, magic_pw, magic_q, magic_p, magic_pr, magic_rc;   // ceil(2^32 / d) for d = NP, PW, Q, P, PR, row_chunks
 };
 
 // TM: 32-filter blocks per workgroup (all four waves share them); a wave owns 64 of the tile's 256 pixel rows.
@@ -101,7 +106,7 @@ void conv_bf16_rows_kernel(const RArgs a)
 #pragma unroll
     for (int i = 0; i < A_PER; ++i) {
         const int m = mt * BM + i * 32 + lrow;
-        a_voff[i] = m < g.K ? (m * g.Kg + lc * 8) * 2 : OOB;
+        a_voff[i] = m < g.K ? (m * a.Kg + lc * 8) * 2 : OOB;
     }
     if (wave * 64 < BM) {
         const int ml = wave * 64 + lane, m = mt * BM + ml;
@@ -123,6 +128,19 @@ void conv_bf16_rows_kernel(const RArgs a)
     // patch of the tile that starts at row p0 of image img0: chunk c of patch pixel pp goes to chunk pp NP + c; the lanes
     // on the padding chunk, on pixels outside the image (or behind the last image) and behind the patch fetch zeros
     auto issue_patch = [&](int img0, int p0) __attribute__((always_inline)) {
+        if (a.packed) {
+            // rows of the padded copy as they are: chunk cc of patch row prow is pixel pair cc of row row_mul p0 + prow
+            for (int pass = 0; pass < a.passes; ++pass) {
+                const int p = pass * 256 + tid;
+                const int prow = (int)__umulhi((unsigned)p, a.magic_rc), cc = p - prow * a.row_chunks;
+                const int pr = a.row_mul * p0 + prow;
+                const int io = (int)__umulhi((unsigned)pr, a.magic_pr), img = img0 + io;
+                const bool ok = prow < a.rows_max && img < g.N;
+                const int voff = ok ? ((img * a.PR + (pr - io * a.PR)) * a.wp * 4 + cc * 8) * 2 : OOB;
+                load_to_lds16(rx, patch + pass * 4096 + wave * 1024, voff, 0);
+            }
+            return;
+        }
         for (int pass = 0; pass < a.passes; ++pass) {
             const int p = pass * 256 + tid;
             const int pp = (int)__umulhi((unsigned)p, a.magic_np), c = p - pp * a.NP;
@@ -149,8 +167,8 @@ void conv_bf16_rows_kernel(const RArgs a)
         koff += 32;
         if (++kj == a.J) {
             kj = 0;
-            koff += 16;
-            if (++ks_ == g.S) { ks_ = 0; koff += a.row_skip; }
+            koff += a.tap_skip;
+            if (++ks_ == a.taps_per_row) { ks_ = 0; koff += a.row_skip; }
         }
         return ret;
     };
@@ -199,7 +217,7 @@ void conv_bf16_rows_kernel(const RArgs a)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int io = (int)__umulhi((unsigned)(p0 + dp[j]), a.magic_p);
-            pb[j] = patch_lds + (unsigned)(((dp[j] + io * (g.R - 1)) * a.PW + qq[j]) * a.NP + half) * 16u;
+            pb[j] = patch_lds + (unsigned)((a.row_mul * dp[j] + io * a.D) * a.row_chunks + qq[j] * a.px_chunks + half) * 16u;
         }
         ku = 0; kj = 0; ks_ = 0; koff = 0;
         // the patch and the first filter slice have landed: behind them are filter slice 1 and, from the second tile on, the stores
@@ -264,17 +282,17 @@ void conv_bf16_rows_kernel(const RArgs a)
 
 constexpr int LDS_PER_CU = 160 * 1024;
 
-template <int TM>
+template <int TM, int OCC>
 int launch_rows(RArgs a, int patch_bytes, hipStream_t st)
 {
-    constexpr int BM = TM * 32, OCC = 2;
+    constexpr int BM = TM * 32;
     a.grid_m = (a.g.K + BM - 1) / BM;
     int gn = device_cus() * OCC / a.grid_m;
     if (gn < 1) gn = 1;
     if (gn > a.tiles) gn = a.tiles;
     static bool sized = false;                           // (benign race: every thread sets the same value)
     if (!sized) {
-        if (hipFuncSetAttribute((const void*)conv_bf16_rows_kernel<TM, OCC>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_PER_CU / OCC) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)conv_bf16_rows_kernel<TM, OCC>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_PER_CU / 2) != hipSuccess)
             return fail(DR_ERR_HIP, "conv_bf16_rows: cannot size the patch");
         sized = true;
     }
@@ -283,7 +301,7 @@ int launch_rows(RArgs a, int patch_bytes, hipStream_t st)
 }
 
 struct RowsPlan {
-    int tm, TH, rows_max, NP, patch_bytes;
+    int tm, occ, TH, rows_max, NP, patch_bytes;
 };
 
 // Filter block, rows per tile and patch size; false when the layer is not for this kernel.
@@ -312,7 +330,46 @@ bool rows_plan(const ConvGeom& g, RowsPlan& pl)
     // (layers with fewer go to the streaming kernel and its smaller tiles)
     if (th < 1 || th * g.Q * 4 < ROWS_BN * 3) return false;
     const long long tiles = (stack + th - 1) / th, blocks = (g.K + pl.tm * 32 - 1) / (pl.tm * 32);
-    return tiles * blocks * 4 >= device_cus();
+    if (tiles * blocks * 4 < device_cus()) return false;
+    // a third (fourth) workgroup per compute unit where LDS and registers (64-filter blocks) have room and there are tiles for it
+    const int per_wg = 2 * pl.tm * 32 * 128 + 512 + 1024 + pl.patch_bytes;
+    pl.occ = 2;
+    if (3 * per_wg <= LDS_PER_CU && tiles * blocks > 2 * device_cus()) pl.occ = 3;
+    if (pl.tm == 2 && 4 * per_wg <= LDS_PER_CU && tiles * blocks > 3 * device_cus()) pl.occ = 4;
+    return true;
+}
+
+unsigned magic(int d) { return (unsigned)((0x100000000ull + (unsigned)d - 1) / (unsigned)d); }
+
+// Rows per tile, patch rows and bytes for the padded 4-channel copy; false when the layer is not for this kernel.
+bool stem_plan(const ConvGeom& g, int hp, int wp, RowsPlan& pl)
+{
+    if (!g.nhwc || g.C > 4 || g.R > 8 || g.S > 8 || g.sw % 2 != 0 || g.sw > 8 || g.sh < 1 || g.K % 8 != 0 || g.res_ctot) return false;
+    if (g.P < 2 || g.Q < 2 || g.Q > ROWS_BN || wp % 8 != 0 || hp < (g.P - 1) * g.sh + 8 || wp < (g.Q - 1) * g.sw + 8) return false;
+    if (hp > 32768 || (double)g.N * hp * hp >= 4294967296.0 || (double)g.N * g.P * g.P >= 4294967296.0) return false;
+    const int pad96 = (g.K + 95) / 96 * 96, pad64 = (g.K + 63) / 64 * 64;
+    pl.tm = pad96 <= pad64 ? 3 : 2;
+    pl.NP = 0;
+    const int budget = LDS_PER_CU / 2 - (2 * pl.tm * 32 * 128 + 512 + 1024);
+    const long long stack = (long long)g.N * g.P;
+    int th = ROWS_BN / g.Q;
+    if (th > stack) th = (int)stack;
+    for (; th >= 1; --th) {
+        int segs = g.P % th == 0 ? 1 : (th + g.P - 2) / g.P + 1;
+        if (segs > g.N) segs = g.N;
+        pl.rows_max = g.sh * (th - 1) + (segs - 1) * (hp - g.sh * g.P) + 8;
+        pl.patch_bytes = (pl.rows_max * (wp / 2) * 16 + 4095) / 4096 * 4096;
+        if (pl.patch_bytes <= budget) break;
+    }
+    pl.TH = th;
+    if (th < 1 || th * g.Q * 4 < ROWS_BN * 3) return false;
+    const long long tiles = (stack + th - 1) / th, blocks = (g.K + pl.tm * 32 - 1) / (pl.tm * 32);
+    if (tiles * blocks * 4 < device_cus()) return false;
+    const int per_wg = 2 * pl.tm * 32 * 128 + 512 + 1024 + pl.patch_bytes;
+    pl.occ = 2;
+    if (3 * per_wg <= LDS_PER_CU && tiles * blocks > 2 * device_cus()) pl.occ = 3;
+    if (pl.tm == 2 && 4 * per_wg <= LDS_PER_CU && tiles * blocks > 3 * device_cus()) pl.occ = 4;
+    return true;
 }
 
 }  // namespace
@@ -346,10 +403,65 @@ int launch_conv_bf16_rows(const ConvGeom& g, const uint16_t* x, const uint16_t* 
     a.U = g.Kg / 16;
     a.nslices = (a.U + 3) / 4;
     a.tail_chunks = g.Kg / 8 - 8 * (a.nslices - 1);
+    a.Kg = g.Kg;
+    a.taps_per_row = g.S;
+    a.tap_skip = 16;                                     // over the padding chunk
     a.row_skip = (a.PW - g.S) * a.NP * 16;
-    auto magic = [](int d) { return (unsigned)((0x100000000ull + (unsigned)d - 1) / (unsigned)d); };
+    a.row_mul = 1; a.D = g.R - 1;
+    a.row_chunks = a.PW * a.NP; a.px_chunks = a.NP;
+    a.packed = 0; a.wp = 0;
     a.magic_np = magic(a.NP); a.magic_pw = magic(a.PW); a.magic_q = magic(g.Q); a.magic_p = magic(g.P); a.magic_pr = magic(a.PR);
-    return pl.tm == 3 ? launch_rows<3>(a, pl.patch_bytes, st) : launch_rows<2>(a, pl.patch_bytes, st);
+    a.magic_rc = magic(a.row_chunks);
+    if (pl.tm == 3) return pl.occ == 3 ? launch_rows<3, 3>(a, pl.patch_bytes, st) : launch_rows<3, 2>(a, pl.patch_bytes, st);
+    return pl.occ == 4 ? launch_rows<2, 4>(a, pl.patch_bytes, st) : pl.occ == 3 ? launch_rows<2, 3>(a, pl.patch_bytes, st) : launch_rows<2, 2>(a, pl.patch_bytes, st);
+}
+
+// The network's first layer (3 channels): the input is the padded 4-channel copy xp[N][hp][wp][4] (one pixel is 8 bytes, a
+// 16-byte chunk a pixel pair; wp a multiple of 8, the padding in place) and the filters are wp8[K][8][8][4] with zeros
+// beyond R, S, C, as for the streaming kernel's form of this layer.  A window row is 8 taps x 4 channels = two k-steps of
+// consecutive chunks, so the patch needs neither a pixel pitch nor padding chunks: its rows are the copy's rows as they
+// are, the window of output pixel q starts stride_w / 2 chunks after that of pixel q - 1 (lanes read consecutive chunks),
+// and the k-steps walk two chunks along a row and then one row down.  Per tile the loads are the rows under the tile once
+// (10 rows of 116 chunks for two output rows of 112 at stride 2) instead of 128 bytes per output pixel and slice.
+bool conv_bf16_rows_stem_eligible(const ConvGeom& g, int hp, int wp, const void* xp, const void* y)
+{
+    const double xb = (double)g.N * hp * wp * 8.0, yb = (double)g.Ng * g.y_ctot * 2.0;
+    if (xb >= 2147483648.0 || yb >= 2147483648.0 || g.Ng >= (1 << 24)) return false;
+    if (((uintptr_t)xp & 15) || ((uintptr_t)y & 15) || g.y_ctot % 8 != 0 || g.y_coff % 8 != 0) return false;
+    RowsPlan pl;
+    return stem_plan(g, hp, wp, pl);
+}
+
+int launch_conv_bf16_rows_stem(const ConvGeom& g, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias, uint16_t* y,
+                               hipStream_t st)
+{
+    TraceScope trace("conv_bf16", &g, g.Ng, st);
+    RowsPlan pl;
+    if (!stem_plan(g, hp, wp, pl)) return fail(DR_ERR_UNSUPPORTED, "conv_bf16_rows: layer not eligible");
+    RArgs a{};
+    a.x = xp; a.w = wp8; a.bias = bias; a.y = y; a.g = g;
+    a.x_bytes = (int)((size_t)g.N * hp * wp * 8);
+    a.w_bytes = (int)((size_t)g.K * 256 * 2);
+    a.y_bytes = (int)((size_t)g.Ng * g.y_ctot * 2);
+    a.TH = pl.TH;
+    a.THQ = pl.TH * g.Q;
+    a.tiles = (int)(((long long)g.N * g.P + pl.TH - 1) / pl.TH);
+    a.PW = wp; a.NP = 1; a.CCH = 1; a.J = 2;
+    a.PR = hp;
+    a.rows_max = pl.rows_max;
+    a.passes = pl.patch_bytes / 4096;
+    a.U = 16; a.nslices = 4; a.tail_chunks = 8;
+    a.Kg = 256;
+    a.taps_per_row = 1;
+    a.row_chunks = wp / 2; a.px_chunks = g.sw / 2;
+    a.tap_skip = a.row_chunks * 16 - 64;                 // from behind a window row's 64 bytes to the next row's window
+    a.row_skip = 0;
+    a.row_mul = g.sh; a.D = hp - g.sh * g.P;
+    a.packed = 1; a.wp = wp;
+    a.magic_np = magic(1 + 1); a.magic_pw = magic(wp); a.magic_q = magic(g.Q); a.magic_p = magic(g.P); a.magic_pr = magic(hp);
+    a.magic_rc = magic(a.row_chunks);
+    if (pl.tm == 3) return pl.occ == 3 ? launch_rows<3, 3>(a, pl.patch_bytes, st) : launch_rows<3, 2>(a, pl.patch_bytes, st);
+    return pl.occ == 4 ? launch_rows<2, 4>(a, pl.patch_bytes, st) : pl.occ == 3 ? launch_rows<2, 3>(a, pl.patch_bytes, st) : launch_rows<2, 2>(a, pl.patch_bytes, st);
 }
 
 }  // namespace dr

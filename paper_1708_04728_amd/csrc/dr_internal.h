@@ -78,6 +78,10 @@ int launch_conv_bf16_patch(const ConvGeom& g, const uint16_t* x, const uint16_t*
 // output rows of the whole batch's row stack, image borders inside it allowed
 bool conv_bf16_rows_eligible(const ConvGeom& g, const void* x, const void* w, const void* y);
 int launch_conv_bf16_rows(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias, uint16_t* y, hipStream_t st);
+// ... and for the padded 4-channel copy of a 3-channel input (xp, wp8 as for launch_conv_bf16_stem)
+bool conv_bf16_rows_stem_eligible(const ConvGeom& g, int hp, int wp, const void* xp, const void* y);
+int launch_conv_bf16_rows_stem(const ConvGeom& g, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias, uint16_t* y,
+                               hipStream_t st);
 
 // conv_bf16_dma.hip: convolution, ReLU, LRN (window of 5) and 3x3 stride-2 max-pooling in one kernel (the streamlined
 // block's original form, Sec. 3.1); y is the pooled tensor (PP x QQ pixels per image, y_ctot channels, written from y_coff)

@@ -104,3 +104,50 @@ def test_layers_the_rule_leaves_out_still_match():
         B.conv2d_fwd(gpu_nhwc(x, "bf16"), B.conv_desc(K, C, R, S, stride, pad, False, B.DR_KRSC), B.pack_filters(gpu(w, "bf16")), None, y)
         torch.cuda.synchronize()
         assert close(host_nhwc(y), oracle.conv2d(x, w, None, stride, pad, False), TOL_BF16)
+
+
+def stem_takes(N, C, H, W, K, R, stride, pad):
+    """The launcher's rule for the packed 4-channel input of a first layer, restated: stacked output rows per tile or 0."""
+    P, Q = oracle.conv_out_size(H, R, stride, pad), oracle.conv_out_size(W, R, stride, pad)
+    if C > 4 or R > 8 or stride % 2 or stride > 8 or K % 8 or P < 2 or Q < 2 or Q > 256:
+        return 0
+    hp = max(H + 2 * pad, (P - 1) * stride + 8)
+    wp = (max(W + 2 * pad, (Q - 1) * stride + 8) + 7) // 8 * 8
+    tm = 3 if (K + 95) // 96 * 96 <= (K + 63) // 64 * 64 else 2
+    budget = 80 * 1024 - (2 * tm * 32 * 128 + 512 + 1024)
+    th = min(256 // Q, N * P)
+    while th >= 1:
+        segs = 1 if P % th == 0 else min(N, (th + P - 2) // P + 1)
+        rows = stride * (th - 1) + (segs - 1) * (hp - stride * P) + 8
+        if (rows * (wp // 2) * 16 + 4095) // 4096 * 4096 <= budget:
+            break
+        th -= 1
+    if th < 1 or th * Q * 4 < 256 * 3:
+        return 0
+    return th if ((N * P + th - 1) // th) * ((K + tm * 32 - 1) // (tm * 32)) * 4 >= CUS else 0
+
+
+@pytest.mark.parametrize("case", [
+    # N, C, H, W, K, R, stride, pad
+    (16, 3, 64, 60, 64, 7, 2, 3),     # the GoogLeNet / ResNet first layer's shape class: 8 rows of 30 per tile, tiles inside images
+    (40, 3, 81, 77, 24, 7, 4, 3),     # stride 4 (slim form), 21 x 20 outputs: 12 rows per tile across image borders
+    (48, 1, 37, 39, 40, 3, 2, 0),     # one channel, 3x3, no padding
+    (40, 4, 40, 40, 72, 5, 2, 2),     # four channels, 5x5
+    (3, 3, 224, 224, 64, 7, 2, 3),    # the benchmark's size: two rows of 112 per tile
+])
+def test_first_layer_packed_input(case):
+    """A first layer with up to 4 input channels inside dr_net_fwd: the row-stack kernel on the padded 4-channel copy."""
+    from test_gpu_bf16_nets import run_net_bf16
+    N, C, H, W, K, R, stride, pad = case
+    assert stem_takes(*case) > 0
+    rng = np.random.default_rng(case_seed(case))
+    x = workloads.round_to_bf16(rng.standard_normal((N, C, H, W)).astype(np.float32))
+    w = workloads.round_to_bf16(rng.standard_normal((K, C, R, R)).astype(np.float32) * np.float32(np.sqrt(2.0 / (C * R * R))))
+    b = (rng.standard_normal(K) * 0.1).astype(np.float32)
+    layers = [workloads.conv(K, R, stride, pad), workloads.relu()]
+    params = [{"w": w, "b": b}]
+    ref = oracle.forward(layers, params, x)
+    got = run_net_bf16(layers, params, x, fuse_relu=True)
+    assert got.shape == ref.shape
+    assert close(got, ref, TOL_BF16)
+    assert close(got, oracle.round_bf16(ref), 2.0 ** -7, "within one bf16 unit of the oracle")
