@@ -41,17 +41,29 @@ WORKLOAD_NAMES = {
 }
 
 
-KERNEL_SOURCES = {"conv_bf16": "conv_bf16_dma.hip", "conv_f32": "conv_f32.hip"}
+# sources a launch's kernel can come from, by trace label (the bf16 convolution picks one of several kernels by rule)
+KERNEL_SOURCES = {"conv_bf16": ["conv_bf16.hip", "conv_bf16_dma.hip", "conv_bf16_patch.hip", "conv_bf16_rows.hip", "conv_bf16_dev.h"],
+                  "conv_f32": ["conv_f32.hip"]}
+
+
+def kernel_source_hash(label):
+    """SHA-256 over the source files of the kernels behind a trace label, or None for a label without an entry."""
+    srcs = KERNEL_SOURCES.get(label)
+    if srcs is None:
+        return None
+    h = hashlib.sha256()
+    for src in srcs:
+        with open(os.path.join(ROOT, "paper_1708_04728_amd", "csrc", src), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
 def measured_traffic(kernel_desc, label):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or
-    None when there is no summary for this kernel or its source has changed since it was taken."""
-    src = KERNEL_SOURCES.get(label)
-    if src is None:
+    None when there is no summary for this kernel or its sources have changed since it was taken."""
+    sha = kernel_source_hash(label)
+    if sha is None:
         return None
-    with open(os.path.join(ROOT, "paper_1708_04728_amd", "csrc", src), "rb") as f:
-        sha = hashlib.sha256(f.read()).hexdigest()
     pdir = os.path.join(ROOT, "profiles")
     for name in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
         if not name.endswith("_hbm_traffic.md"):
@@ -135,6 +147,30 @@ def ceilings():
         ms = best_ms(lambda: lib.drc_read16(vp(src.data_ptr()), vp(out.data_ptr()), n, passes, blocks, sp))
         res["cache_read"]["%d_KiB_buffer_GBs" % kib] = round(float(n) * passes * blocks / (ms * 1e-3) / 1e9, 1)
     print(json.dumps({"ceilings": res, "published": {"hbm_GBs": MI355X_HBM_GBS, "mfma_tflops": MI355X_MFMA_TFLOPS}}))
+
+
+def layer_trace(cfg_id):
+    """For a run under `rocprofv3 --kernel-trace`: every form's forward four times, kernel by kernel with the branches of
+    a module in turn, each forward preceded by a marker kernel (torch's cos_ on 7 floats), so that the kernels of the
+    trace between two markers can be matched, in order, with the launches the library reports for that form.  Prints
+    one JSON line: per form the launches as [label, K, C, R, S, items, algorithmic bytes]."""
+    import torch
+    wl = Workload(cfg_id, serial_branches=True)
+    for _ in range(3):
+        wl.step()
+    torch.cuda.synchronize()
+    labels = {form: [list(r[:6]) + [r[7]] for r in wl.trace(form)] for form in wl.forms}
+    torch.cuda.synchronize()
+    marker = torch.zeros(7, device="cuda")
+    for form in wl.forms:
+        for _ in range(4):
+            marker.cos_()
+            torch.cuda.synchronize()
+            wl.run(form)
+            torch.cuda.synchronize()
+    marker.cos_()
+    torch.cuda.synchronize()
+    print(json.dumps({"layer_trace": labels, "config": cfg_id, "forwards_per_form": 4, "marker": "cos"}))
 
 
 def paper_variant_ms(wl, reps=20, x=None):
@@ -316,7 +352,7 @@ def network_roofline(recs, dtype, forward_ms):
 class Workload:
     """Both forms of one configuration, resident on the GPU."""
 
-    def __init__(self, cfg_id, batch=None):
+    def __init__(self, cfg_id, batch=None, serial_branches=False):
         import numpy as np
         import torch
 
@@ -356,7 +392,7 @@ class Workload:
                     params_host.append({"w": workloads.round_to_bf16(wf) if bf16 else wf, "b": bf})
             else:
                 params_host = workloads.make_params(cfg_id, src_form)
-            net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if (slim or fused) else B.DR_CONCURRENT_BRANCHES,
+            net = B.Net(G.net_descs(layers, c_in, inception_mode=(B.DR_FUSE_RELU | B.DR_FUSE_CONCAT | B.DR_FUSE_STACK) if (slim or fused) else (0 if serial_branches else B.DR_CONCURRENT_BRANCHES),
                                     fuse_relu=slim or fused, folded=folded, pack=self.dtype,
                                     fuse_nontensor="block" if form == "block" else (fused and bf16)))
             xd = B.desc(self.x)
@@ -517,6 +553,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--calibrate-copy", action="store_true", help="run only the known-size copy kernel (counter calibration)")
     ap.add_argument("--ceilings", action="store_true", help="run only the machine-ceiling measurements (matrix-core issue, copy, cached reads)")
+    ap.add_argument("--layer-trace", action="store_true", help="run only the marked forwards for a rocprofv3 kernel trace (see layer_trace)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--only", action="store_true", help="skip the summary of the other configurations")
     args = ap.parse_args()
@@ -541,6 +578,9 @@ def main():
         return
     if args.ceilings:
         ceilings()
+        return
+    if args.layer_trace:
+        layer_trace(args.config)
         return
     wl = Workload(args.config)
     dtype, batch = wl.dtype, wl.batch
