@@ -751,6 +751,11 @@ int launch_auto(DArgs a, hipStream_t st)
         if ((Ng + 255) / 256 < device_cus()) return launch_cfg<1, 1, 1, 4, 2, 3>(a, st);   // 32 x 128 tiles
         return launch_cfg<1, 2, 1, 4, 2, 2>(a, st);                                        // 32 x 256 tiles
     }
+    // several taps and 97..128 filters on enough pixels for one round of 256-pixel tiles: one workgroup holds all filters of
+    // its pixels (128 x 64 per wave, half-depth slices so that three stages fit), so every pixel row is fetched once per tap
+    // instead of twice (GoogLeNet 3a's 3x3 96 -> 128 on 28 x 28: 41 -> 34 us against 64 x 128 and 128 x 128 tiles)
+    if (a.g.R * a.g.S > 1 && K > 96 && K <= 128 && (Ng + 255) / 256 >= device_cus() && (Ng + 255) / 256 <= 2 * device_cus())
+        return launch_cfg<4, 2, 1, 4, 3, 2, 32>(a, st);                          // 128 x 256 tiles
     const float c64 = tile_rounds(K, Ng, 64, 128) * (0.44f + 2.f), c96 = tile_rounds(K, Ng, 96, 128) * (0.44f + 3.f);
     const float r128 = tile_rounds(K, Ng, 128, 128), c128 = r128 * (0.44f + 4.f);   // pays only when it saves a round
     if (r128 <= 1.f && c128 < c64 && c128 < c96) return launch_cfg<2, 2, 2, 2, 2, 2>(a, st);   // 128 x 128 tiles, 64 x 64 per wave

@@ -73,6 +73,8 @@ CASES = [
     (1, 32, 96, 96, 288, 5, 5, 1, 2),       # 288 filters, slices running over filter rows
     (1, 64, 200, 200, 24, 1, 1, 1, 0),      # K <= 32 and 40 000 pixels: 32 x 128 tiles
     (1, 16, 200, 200, 24, 3, 3, 1, 1),      # the same with slices running over filter rows
+    (8, 24, 100, 100, 104, 3, 3, 1, 1),     # 104 filters on 80 000 pixels: one round of 128 x 256 tiles (128 x 64 per wave, half-depth slices)
+    (8, 64, 200, 200, 128, 3, 3, 2, 1),     # the same tile with slices inside one tap, stride 2, 128 filters
 ]
 
 
