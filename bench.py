@@ -78,6 +78,30 @@ def measured_traffic(kernel_desc, label):
     return None
 
 
+NON_TENSOR_SOURCES = ["pointwise_nhwc.hip", "pointwise.hip", "dr_store.h"]
+
+
+def non_tensor_from_kernel_trace(cfg_id):
+    """Non-tensor throughput from KERNEL durations (the committed rocprofv3 kernel trace of `bench.py --layer-trace`,
+    profiles/layers_config<N>_kernel_trace.md), which leave out the gap between dependent launches that the HIP-event pairs
+    of this process include; None when there is no such summary or the non-tensor kernels' sources have changed since."""
+    path = os.path.join(ROOT, "profiles", "layers_config%d_kernel_trace.md" % cfg_id)
+    if not os.path.isfile(path):
+        return None
+    h = hashlib.sha256()
+    for src in NON_TENSOR_SOURCES:
+        with open(os.path.join(ROOT, "paper_1708_04728_amd", "csrc", src), "rb") as f:
+            h.update(f.read())
+    fields = dict(re.findall(r"^([a-z_0-9]+):\s*(.+?)\s*$", open(path).read(), re.M))
+    if fields.get("non_tensor_source_sha256") != h.hexdigest():
+        return None
+    try:
+        return {"all_gbs": float(fields["non_tensor_gbs_all"]), "launches_over_32MB_gbs": float(fields["non_tensor_gbs_over_32mb"]),
+                "source": "profiles/layers_config%d_kernel_trace.md (rocprofv3 kernel durations)" % cfg_id}
+    except (KeyError, ValueError):
+        return None
+
+
 def calibrate_copy():
     """One read + one write of 256 MiB, three times, through the library's ReLU kernel."""
     import torch
@@ -709,6 +733,7 @@ def main():
                                "slim": round(100.0 * fs / max(cs, 1e-9) / 1e9 / MI355X_MFMA_TFLOPS[dtype], 1)},
         "non_tensor_hbm_gbs": round(nontensor_bytes / max(oo, 1e-9) / 1e6, 1) if oo > 0 else None,
         "non_tensor_hbm_gbs_launches_over_32MB": round(sum(nt_bytes(r) for r in big) / max(sum(r[6] for r in big), 1e-9) / 1e6, 1) if big else None,
+        "non_tensor_hbm_gbs_kernel_trace": non_tensor_from_kernel_trace(args.config),
         "non_tensor_by_kind": {k: {"launches": v[2], "ms": round(v[1], 4), "gbs": round(v[0] / max(v[1], 1e-9) / 1e6, 1)} for k, v in sorted(by_kind.items())},
         "roofline": dict(roofline, network={"original": network_roofline(recs, dtype, form_ms["original"][0]),
                                             "slim": network_roofline(recs_slim, dtype, form_ms["slim"][0]),
