@@ -314,7 +314,13 @@ int dr_net_workspace_bytes(const dr_net* net, const dr_tensor* xd, size_t* bytes
 
 /* Runs the layer list on x.  params: host array of dr_net_num_params device pointers.  The output
  * has the dtype of the input except after a softmax layer (fp32).  ws: at least
- * dr_net_workspace_bytes, 256-byte aligned. */
+ * dr_net_workspace_bytes, 256-byte aligned.
+ * Layers run one after the other with one exception, which changes no value: a bf16 NHWC
+ * convolution on at most 4 input channels (a network's first layer) with at most 64 filters and
+ * a 1x1 convolution with at most 64 filters right behind it run as ONE kernel when the first
+ * layer's kernel takes the pair; the tensor between them (rounded to bf16 as it would be stored)
+ * stays in registers and is never written.  Per-layer timing then books the kernel under the
+ * first of the two layers and gives the second 0. */
 int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params,
                const dr_tensor* yd, void* y, void* ws, size_t ws_bytes, void* stream);
 

@@ -246,9 +246,56 @@ bool conv_wants_padding(const dr_tensor& xd, const dr_conv& cd)
 {
     return xd.dtype == DR_BF16 && xd.layout == DR_NHWC && cd.c % 8 != 0 && cd.c < 8;
 }
-int padded_conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias,
-                    const dr_tensor& yd, void* y, Arena& ar, hipStream_t st)
+// A 1x1 convolution right behind such a layer (stride 1, no padding, at most 64 filters over at most 64) can run in the
+// same kernel: the layer's output tile stays in registers and is multiplied from there (conv_bf16_rows.hip, TAIL).
+bool conv_tail_ok(const dr_conv& cd, const dr_conv& next)
 {
+    return next.r == 1 && next.s == 1 && next.stride_h == 1 && next.stride_w == 1 && next.pad_h == 0 && next.pad_w == 0 && next.c == cd.k &&
+           cd.k <= 64 && cd.k % 8 == 0 && next.k <= 64 && next.k % 8 == 0 && next.k >= 8;
+}
+// tail != NULL: yd / y are the 1x1 convolution's output; *fused says whether the pair ran (as one kernel) -- when the
+// kernel does not take the pair nothing has been run and the caller runs the two layers one after the other.
+int padded_conv_run(const char* who, const dr_tensor& xd, const void* x, const dr_conv& cd, const void* w, const float* bias,
+                    const dr_tensor& yd, void* y, Arena& ar, hipStream_t st, const dr_conv* tail = nullptr, const void* w2 = nullptr,
+                    const float* b2 = nullptr, bool* fused = nullptr)
+{
+    if (fused) *fused = false;
+    if (tail) {
+        // (the pair or nothing)
+        const dr_tensor o1 = conv_out(xd, cd);
+        if (!(cd.c <= 4 && cd.r <= 8 && cd.s <= 8 && cd.stride_w % 2 == 0 && (double)o1.h * o1.w <= 65536.0 && (double)o1.n * o1.h * o1.w < 16777216.0)) return DR_OK;
+        const int hp = std::max(xd.h + 2 * cd.pad_h, (o1.h - 1) * cd.stride_h + 8);
+        const int wp = (std::max(xd.w + 2 * cd.pad_w, (o1.w - 1) * cd.stride_w + 8) + 7) / 8 * 8;
+        const size_t xbytes = (size_t)xd.n * hp * wp * 8;
+        if (xbytes >= (1ull << 31) || !x || !w || !w2 || !y || xd.c != cd.c) return DR_OK;
+        const dr_tensor o2 = conv_out(o1, *tail);
+        if (yd.n != o2.n || yd.h != o2.h || yd.w != o2.w || yd.c != tail->k || yd.dtype != xd.dtype || yd.layout != xd.layout) return DR_OK;
+        ConvGeom g;
+        g.N = xd.n; g.C = xd.c; g.H = xd.h; g.W = xd.w;
+        g.K = cd.k; g.R = cd.r; g.S = cd.s;
+        g.sh = cd.stride_h; g.sw = cd.stride_w; g.ph = cd.pad_h; g.pw = cd.pad_w;
+        g.P = o1.h; g.Q = o1.w;
+        g.Kg = cd.c * cd.r * cd.s;
+        g.Ng = o1.n * o1.h * o1.w;
+        g.y_ctot = yd.c; g.y_coff = 0;
+        g.relu = cd.relu != 0;
+        g.res_ctot = 0;
+        g.w_krsc = cd.filter_layout == DR_KRSC;
+        g.nhwc = 1;
+        g.c_logical = 0;
+        const RowsTail rt{(const uint16_t*)w2, b2, tail->k, tail->relu != 0};
+        // (probe with the addresses the buffers will have: 256-byte aligned workspace pieces)
+        Arena probe = ar;
+        void* xbuf = probe.take(xbytes);
+        void* wbuf = probe.take((size_t)cd.k * 512);
+        if (!xbuf || !wbuf || !conv_bf16_rows_stem_eligible(g, hp, wp, xbuf, y, &rt)) return DR_OK;
+        ar = probe;
+        DR_TRY(launch_stem_pack_bf16(x, xbuf, xd.n, xd.c, xd.h, xd.w, cd.pad_h, cd.pad_w, hp, wp, st));
+        DR_TRY(launch_stem_filters_bf16(w, wbuf, cd.k, cd.c, cd.r, cd.s, g.w_krsc, st));
+        DR_TRY(launch_conv_bf16_rows_stem(g, (const uint16_t*)xbuf, hp, wp, (const uint16_t*)wbuf, bias, (uint16_t*)y, st, &rt));
+        if (fused) *fused = true;
+        return DR_OK;
+    }
     if (cd.c <= 4 && cd.r <= 8 && cd.s <= 8 && cd.stride_w % 2 == 0 && (double)yd.h * yd.w <= 65536.0 && (double)yd.n * yd.h * yd.w < 16777216.0) {
         // packed form: 4 channels per pixel, padding laid out physically (launch_conv_bf16_stem)
         const int hp = std::max(xd.h + 2 * cd.pad_h, (yd.h - 1) * cd.stride_h + 8);
@@ -1327,8 +1374,24 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
         const int dst_buf = inplace ? cur_buf : (cur_buf == 0 ? 1 : 0);
         void* dst = last ? y : (void*)buf[dst_buf];
         Arena ar(scratch, plan.scratch_bytes, false);
+        void* skip_to = nullptr;                       // set when this layer and the next one ran as one kernel
         switch (L.kind) {
         case DR_LAYER_CONV:
+            if (conv_wants_padding(t, L.conv) && i + 1 < nl && net->layers[i + 1].kind == DR_LAYER_CONV && conv_tail_ok(L.conv, net->layers[i + 1].conv)) {
+                // this layer and the 1x1 convolution behind it as one kernel, written where the second one's output belongs
+                const bool last2 = i + 2 == nl;
+                void* dst2 = last2 ? y : (void*)buf[dst_buf];
+                bool fused = false;
+                DR_TRY(padded_conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], plan.outs[i + 1], dst2, ar, st,
+                                       &net->layers[i + 1].conv, params[pi + 2], (const float*)params[pi + 3], &fused));
+                if (fused) {
+                    if (net->timing && hipEventRecord(net->events[i + 1], st) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipEventRecord failed", who);
+                    pi += param_count(L);
+                    ++i;                               // (the loop's tail accounts for the second layer)
+                    skip_to = dst2;
+                    break;
+                }
+            }
             if (conv_wants_padding(t, L.conv))
                 DR_TRY(padded_conv_run(who, t, cur, L.conv, params[pi], (const float*)params[pi + 1], od, dst, ar, st));
             else {
@@ -1366,6 +1429,14 @@ int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* cons
             break;
         case DR_LAYER_SOFTMAX: DR_TRY(launch_softmax(t.dtype, cur, (float*)dst, t.n, t.c, st)); break;
         default: return fail(DR_ERR_UNSUPPORTED, "%s: unknown layer kind %d", who, L.kind);
+        }
+        if (skip_to) {
+            pi += param_count(net->layers[i]);
+            cur = skip_to;
+            cur_buf = i + 1 == nl ? -1 : dst_buf;
+            t = plan.outs[i];
+            if (net->timing && hipEventRecord(net->events[i + 1], st) != hipSuccess) return fail(DR_ERR_HIP, "%s: hipEventRecord failed", who);
+            continue;
         }
         pi += param_count(L);
         cur = dst;

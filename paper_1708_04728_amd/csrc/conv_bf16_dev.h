@@ -137,5 +137,47 @@ __device__ __forceinline__ void store_blocks(const f32x16 (&acc)[TM][TN], unsign
     }
 }
 
+// The first half of store_blocks without the store: bias + ReLU + bf16 pack of a wave's TM x TN blocks, returned as
+// hk[j][2 i + qp] = the 8 consecutive filters 32 i + 16 qp + 8 h .. of pixel l32 of pixel block j.  That is the layout of
+// the matrix instruction's SECOND operand for a contraction over those filters (k-step 2 i + qp holds filters
+// 16 (2 i + qp) .. + 15, a lane of half h the 8 from 8 h on, for the pixel of its column): a 1x1 convolution on the
+// layer's output can multiply straight from these registers.
+template <int TM, int TN>
+__device__ __forceinline__ void pack_blocks(const f32x16 (&acc)[TM][TN], unsigned bias_rd, int relu, u32x4 (&hk)[TN][2 * TM])
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        u32x4 bv[2][2];
+        bv[0][0] = ds_read16<0>(bias_rd + i * 128);
+        bv[0][1] = ds_read16<16>(bias_rd + i * 128);
+        bv[1][0] = ds_read16<64>(bias_rd + i * 128);
+        bv[1][1] = ds_read16<80>(bias_rd + i * 128);
+        wait_lgkm<0>();
+        touch(bv[0][0]); touch(bv[0][1]); touch(bv[1][0]); touch(bv[1][1]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int qp = 0; qp < 2; ++qp) {
+                float o[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][j][qp * 8 + e]),
+                                                                     __float_as_uint(acc[i][j][qp * 8 + 4 + e]), false, false);
+                    o[e] = __uint_as_float(sw[0]);
+                    o[4 + e] = __uint_as_float(sw[1]);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] += __uint_as_float(bv[qp][e >> 2][e & 3]);
+                if (relu) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = fmaxf(o[e], 0.f);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) hk[j][2 * i + qp][e] = pack_bf16x2(o[2 * e], o[2 * e + 1]);
+            }
+        }
+    }
+}
+
 }  // namespace
 }  // namespace dr

@@ -49,10 +49,19 @@ struct RArgs {
     int row_chunks, px_chunks;           // chunks per patch row; chunks from one output pixel's window to the next one's
     int packed, wp;                      // input is the padded 4-channel copy xp[N][PR][wp][4] (see launch_conv_bf16_rows_stem)
     unsigned magic_np, magic_pw, magic_q, magic_p, magic_pr, magic_rc;   // ceil(2^32 / d) for d = NP, PW, Q, P, PR, row_chunks
+    // a 1x1 convolution on the layer's output, in the same kernel (TAIL): filters w2[K2][K], bias2, ReLU flag; g.y_ctot and
+    // g.y_coff then describe ITS destination and the layer's own output is never written
+    const uint16_t* w2;
+    const float* bias2;
+    int K2, relu2, w2_bytes;
 };
 
 // TM: 32-filter blocks per workgroup (all four waves share them); a wave owns 64 of the tile's 256 pixel rows.
-template <int TM, int OCC>
+// TAIL: the workgroup holds ALL the layer's filters (K <= 32 TM) and a 1x1 convolution with at most 32 TM filters follows:
+// the tile's results -- bias, ReLU, rounded to bf16 as the stored tensor would be -- stay in registers, which already are
+// the second operand of a contraction over the layer's filters (pack_blocks), the 1x1 filters wait in LDS, and 2 TM k-steps
+// later the tile of the 1x1 convolution's output is stored instead.  The intermediate tensor is neither written nor read.
+template <int TM, int OCC, bool TAIL = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 void conv_bf16_rows_kernel(const RArgs a)
 {
@@ -61,6 +70,8 @@ void conv_bf16_rows_kernel(const RArgs a)
 
     __shared__ __attribute__((aligned(1024))) unsigned char aring[NS * A_BYTES];
     __shared__ __attribute__((aligned(1024))) float bias_lds[128];
+    __shared__ __attribute__((aligned(1024))) unsigned char w2s[TAIL ? BM * 128 : 16];   // 1x1 filters: rows of 64 k, swizzled like the ring
+    __shared__ __attribute__((aligned(16))) float bias2_lds[TAIL ? 128 : 4];
     extern __shared__ __attribute__((aligned(1024))) unsigned char patch[];
     const unsigned aring_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)aring;
     const unsigned patch_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)patch;
@@ -114,6 +125,17 @@ void conv_bf16_rows_kernel(const RArgs a)
     }
     const int m_lane = mt * BM + half * 8;
     const unsigned bias_rd = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)bias_lds + (half * 8) * 4;
+    if constexpr (TAIL) {
+        // the 1x1 filters and their biases, once per workgroup (older than every other load, so the first wait covers them)
+        const __amdgpu_buffer_rsrc_t rw2 = __builtin_amdgcn_make_buffer_rsrc((void*)a.w2, 0, a.w2_bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rb2 = __builtin_amdgcn_make_buffer_rsrc((void*)a.bias2, 0, a.bias2 ? a.K2 * 4 : 0, 0x00020000);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m2 = i * 32 + lrow;
+            load_to_lds16(rw2, w2s + i * 4096 + wave * 1024, (m2 < a.K2 && lc * 8 < g.K) ? (m2 * g.K + lc * 8) * 2 : OOB, 0);
+        }
+        if (wave * 64 < BM) load_to_lds4(rb2, bias2_lds + wave * 64, wave * 64 + lane < a.K2 ? (wave * 64 + lane) * 4 : OOB);
+    }
 
     // ---- loaders
     int ld_i = 0;                                      // the next filter slice to load (the same cycle for every tile)
@@ -275,14 +297,45 @@ void conv_bf16_rows_kernel(const RArgs a)
             n_ok[j] = nl[j] < a.THQ && nfirst + nl[j] < g.Ng;
             nbase[j] = ((nfirst + nl[j]) * g.y_ctot + g.y_coff) * 2;
         }
-        store_blocks<TM, TN>(acc, bias_rd, m_lane, g.K, g.relu, ry, nbase, n_ok);
+        if constexpr (TAIL) {
+            u32x4 hk[TN][2 * TM];
+            pack_blocks<TM, TN>(acc, bias_rd, g.relu, hk);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            const unsigned w2_rd = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)w2s + l32 * 128 +
+                                   ((half << 4) ^ (((l32 >> 1) & 7) << 4));
+#pragma unroll
+            for (int ks = 0; ks < 2 * TM; ++ks) {
+                // k-step ks of the 1x1 filters: chunk 2 ks + h of a row, i.e. bits 5.. of the unswizzled offset
+                u32x4 f2[TM];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) f2[i] = ds_read16<0>((w2_rd + i * 4096) ^ (ks * 32));
+                wait_lgkm<0>();
+#pragma unroll
+                for (int i = 0; i < TM; ++i) touch(f2[i]);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f2[i]),
+                                                                            __builtin_bit_cast(bf16x8, hk[j][ks]), acc[i][j], 0, 0, 0);
+            }
+            const unsigned bias2_rd = (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)bias2_lds + (half * 8) * 4;
+            store_blocks<TM, TN>(acc, bias2_rd, half * 8, a.K2, a.relu2, ry, nbase, n_ok);
+        } else {
+            store_blocks<TM, TN>(acc, bias_rd, m_lane, g.K, g.relu, ry, nbase, n_ok);
+        }
     }
     wait_lgkm<0>();
 }
 
 constexpr int LDS_PER_CU = 160 * 1024;
 
-template <int TM, int OCC>
+template <int TM, int OCC, bool TAIL = false>
 int launch_rows(RArgs a, int patch_bytes, hipStream_t st)
 {
     constexpr int BM = TM * 32;
@@ -292,11 +345,11 @@ int launch_rows(RArgs a, int patch_bytes, hipStream_t st)
     if (gn > a.tiles) gn = a.tiles;
     static bool sized = false;                           // (benign race: every thread sets the same value)
     if (!sized) {
-        if (hipFuncSetAttribute((const void*)conv_bf16_rows_kernel<TM, OCC>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_PER_CU / 2) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)conv_bf16_rows_kernel<TM, OCC, TAIL>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_PER_CU / 2) != hipSuccess)
             return fail(DR_ERR_HIP, "conv_bf16_rows: cannot size the patch");
         sized = true;
     }
-    hipLaunchKernelGGL((conv_bf16_rows_kernel<TM, OCC>), dim3((unsigned)(gn * a.grid_m)), dim3(256), (size_t)patch_bytes, st, a);
+    hipLaunchKernelGGL((conv_bf16_rows_kernel<TM, OCC, TAIL>), dim3((unsigned)(gn * a.grid_m)), dim3(256), (size_t)patch_bytes, st, a);
     return check_launch("conv_bf16_rows");
 }
 
@@ -342,15 +395,19 @@ bool rows_plan(const ConvGeom& g, RowsPlan& pl)
 unsigned magic(int d) { return (unsigned)((0x100000000ull + (unsigned)d - 1) / (unsigned)d); }
 
 // Rows per tile, patch rows and bytes for the padded 4-channel copy; false when the layer is not for this kernel.
-bool stem_plan(const ConvGeom& g, int hp, int wp, RowsPlan& pl)
+// (tail: a 1x1 convolution of K2 filters follows in the same kernel, see the kernel's TAIL)
+bool stem_plan(const ConvGeom& g, int hp, int wp, RowsPlan& pl, const RowsTail* tail = nullptr)
 {
+    if (tail && (g.K > 64 || tail->K2 > 64 || tail->K2 < 8 || tail->K2 % 8 != 0 || !tail->w2 || ((uintptr_t)tail->w2 & 15))) return false;
+    const int extra = tail ? 64 * 128 + 512 : 0;         // the 1x1 filters and biases in LDS
     if (!g.nhwc || g.C > 4 || g.R > 8 || g.S > 8 || g.sw % 2 != 0 || g.sw > 8 || g.sh < 1 || g.K % 8 != 0 || g.res_ctot) return false;
     if (g.P < 2 || g.Q < 2 || g.Q > ROWS_BN || wp % 8 != 0 || hp < (g.P - 1) * g.sh + 8 || wp < (g.Q - 1) * g.sw + 8) return false;
     if (hp > 32768 || (double)g.N * hp * hp >= 4294967296.0 || (double)g.N * g.P * g.P >= 4294967296.0) return false;
     const int pad96 = (g.K + 95) / 96 * 96, pad64 = (g.K + 63) / 64 * 64;
     pl.tm = pad96 <= pad64 ? 3 : 2;
     pl.NP = 0;
-    const int budget = LDS_PER_CU / 2 - (2 * pl.tm * 32 * 128 + 512 + 1024);
+    if (tail) pl.tm = 2;
+    const int budget = LDS_PER_CU / 2 - (2 * pl.tm * 32 * 128 + 512 + 1024) - extra;
     const long long stack = (long long)g.N * g.P;
     int th = ROWS_BN / g.Q;
     if (th > stack) th = (int)stack;
@@ -365,10 +422,10 @@ bool stem_plan(const ConvGeom& g, int hp, int wp, RowsPlan& pl)
     if (th < 1 || th * g.Q * 4 < ROWS_BN * 3) return false;
     const long long tiles = (stack + th - 1) / th, blocks = (g.K + pl.tm * 32 - 1) / (pl.tm * 32);
     if (tiles * blocks * 4 < device_cus()) return false;
-    const int per_wg = 2 * pl.tm * 32 * 128 + 512 + 1024 + pl.patch_bytes;
+    const int per_wg = 2 * pl.tm * 32 * 128 + 512 + 1024 + pl.patch_bytes + extra;
     pl.occ = 2;
     if (3 * per_wg <= LDS_PER_CU && tiles * blocks > 2 * device_cus()) pl.occ = 3;
-    if (pl.tm == 2 && 4 * per_wg <= LDS_PER_CU && tiles * blocks > 3 * device_cus()) pl.occ = 4;
+    if (pl.tm == 2 && !tail && 4 * per_wg <= LDS_PER_CU && tiles * blocks > 3 * device_cus()) pl.occ = 4;
     return true;
 }
 
@@ -423,21 +480,27 @@ int launch_conv_bf16_rows(const ConvGeom& g, const uint16_t* x, const uint16_t* 
 // are, the window of output pixel q starts stride_w / 2 chunks after that of pixel q - 1 (lanes read consecutive chunks),
 // and the k-steps walk two chunks along a row and then one row down.  Per tile the loads are the rows under the tile once
 // (10 rows of 116 chunks for two output rows of 112 at stride 2) instead of 128 bytes per output pixel and slice.
-bool conv_bf16_rows_stem_eligible(const ConvGeom& g, int hp, int wp, const void* xp, const void* y)
+//
+// tail (may be NULL): a 1x1 convolution on the layer's output (stride 1, no padding, K2 <= 64 filters over the layer's
+// K <= 64) computed in the same kernel; g.y_ctot / g.y_coff and y then describe the 1x1 convolution's destination.
+bool conv_bf16_rows_stem_eligible(const ConvGeom& g, int hp, int wp, const void* xp, const void* y, const RowsTail* tail)
 {
     const double xb = (double)g.N * hp * wp * 8.0, yb = (double)g.Ng * g.y_ctot * 2.0;
     if (xb >= 2147483648.0 || yb >= 2147483648.0 || g.Ng >= (1 << 24)) return false;
     if (((uintptr_t)xp & 15) || ((uintptr_t)y & 15) || g.y_ctot % 8 != 0 || g.y_coff % 8 != 0) return false;
     RowsPlan pl;
-    return stem_plan(g, hp, wp, pl);
+    return stem_plan(g, hp, wp, pl, tail);
 }
 
 int launch_conv_bf16_rows_stem(const ConvGeom& g, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias, uint16_t* y,
-                               hipStream_t st)
+                               hipStream_t st, const RowsTail* tail)
 {
-    TraceScope trace("conv_bf16", &g, g.Ng, st);
+    // (with a tail the trace gets two records: this layer with its input and filters as bytes, the 1x1 convolution -- no
+    // time of its own -- with its filters and its output)
+    const long long in_bytes = (long long)g.N * g.C * g.H * g.W * 2 + (long long)g.K * g.Kg * 2;
+    TraceScope trace("conv_bf16", &g, g.Ng, st, tail ? in_bytes : 0);
     RowsPlan pl;
-    if (!stem_plan(g, hp, wp, pl)) return fail(DR_ERR_UNSUPPORTED, "conv_bf16_rows: layer not eligible");
+    if (!stem_plan(g, hp, wp, pl, tail)) return fail(DR_ERR_UNSUPPORTED, "conv_bf16_rows: layer not eligible");
     RArgs a{};
     a.x = xp; a.w = wp8; a.bias = bias; a.y = y; a.g = g;
     a.x_bytes = (int)((size_t)g.N * hp * wp * 8);
@@ -460,6 +523,18 @@ int launch_conv_bf16_rows_stem(const ConvGeom& g, const uint16_t* xp, int hp, in
     a.packed = 1; a.wp = wp;
     a.magic_np = magic(1 + 1); a.magic_pw = magic(wp); a.magic_q = magic(g.Q); a.magic_p = magic(g.P); a.magic_pr = magic(hp);
     a.magic_rc = magic(a.row_chunks);
+    if (tail) {
+        a.w2 = tail->w2; a.bias2 = tail->bias2; a.K2 = tail->K2; a.relu2 = tail->relu2;
+        a.w2_bytes = tail->K2 * g.K * 2;
+        const int rc = pl.occ == 3 ? launch_rows<2, 3, true>(a, pl.patch_bytes, st) : launch_rows<2, 2, true>(a, pl.patch_bytes, st);
+        if (rc == DR_OK) {
+            ConvGeom g2 = g;
+            g2.C = g.K; g2.K = tail->K2; g2.R = g2.S = 1; g2.sh = g2.sw = 1; g2.ph = g2.pw = 0; g2.H = g.P; g2.W = g.Q; g2.Kg = g.K;
+            g2.relu = tail->relu2; g2.c_logical = 0;
+            TraceScope second("conv_bf16", &g2, g.Ng, st, (long long)g.Ng * tail->K2 * 2 + (long long)tail->K2 * g.K * 2);
+        }
+        return rc;
+    }
     if (pl.tm == 3) return pl.occ == 3 ? launch_rows<3, 3>(a, pl.patch_bytes, st) : launch_rows<3, 2>(a, pl.patch_bytes, st);
     return pl.occ == 4 ? launch_rows<2, 4>(a, pl.patch_bytes, st) : pl.occ == 3 ? launch_rows<2, 3>(a, pl.patch_bytes, st) : launch_rows<2, 2>(a, pl.patch_bytes, st);
 }

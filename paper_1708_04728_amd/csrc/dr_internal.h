@@ -79,9 +79,16 @@ int launch_conv_bf16_patch(const ConvGeom& g, const uint16_t* x, const uint16_t*
 bool conv_bf16_rows_eligible(const ConvGeom& g, const void* x, const void* w, const void* y);
 int launch_conv_bf16_rows(const ConvGeom& g, const uint16_t* x, const uint16_t* w, const float* bias, uint16_t* y, hipStream_t st);
 // ... and for the padded 4-channel copy of a 3-channel input (xp, wp8 as for launch_conv_bf16_stem)
-bool conv_bf16_rows_stem_eligible(const ConvGeom& g, int hp, int wp, const void* xp, const void* y);
+// tail (may be NULL): a 1x1 convolution (stride 1, no padding) on the layer's output, run in the same kernel; g.y_ctot,
+// g.y_coff and y then belong to its destination and the layer's own output is never written
+struct RowsTail {
+    const uint16_t* w2;      // [K2][K] filters
+    const float* bias2;      // may be NULL
+    int K2, relu2;
+};
+bool conv_bf16_rows_stem_eligible(const ConvGeom& g, int hp, int wp, const void* xp, const void* y, const RowsTail* tail = nullptr);
 int launch_conv_bf16_rows_stem(const ConvGeom& g, const uint16_t* xp, int hp, int wp, const uint16_t* wp8, const float* bias, uint16_t* y,
-                               hipStream_t st);
+                               hipStream_t st, const RowsTail* tail = nullptr);
 
 // conv_bf16_dma.hip: convolution, ReLU, LRN (window of 5) and 3x3 stride-2 max-pooling in one kernel (the streamlined
 // block's original form, Sec. 3.1); y is the pooled tensor (PP x QQ pixels per image, y_ctot channels, written from y_coff)

@@ -151,3 +151,61 @@ def test_first_layer_packed_input(case):
     assert got.shape == ref.shape
     assert close(got, ref, TOL_BF16)
     assert close(got, oracle.round_bf16(ref), 2.0 ** -7, "within one bf16 unit of the oracle")
+
+
+def tail_takes(N, C, H, W, K, R, stride, pad, K2):
+    """The launcher's rule for a first layer and the 1x1 convolution behind it as one kernel, restated."""
+    P, Q = oracle.conv_out_size(H, R, stride, pad), oracle.conv_out_size(W, R, stride, pad)
+    if C > 4 or R > 8 or stride % 2 or stride > 8 or K % 8 or K > 64 or K2 % 8 or K2 < 8 or K2 > 64 or P < 2 or Q < 2 or Q > 256:
+        return 0
+    hp = max(H + 2 * pad, (P - 1) * stride + 8)
+    wp = (max(W + 2 * pad, (Q - 1) * stride + 8) + 7) // 8 * 8
+    budget = 80 * 1024 - (2 * 64 * 128 + 512 + 1024) - (64 * 128 + 512)
+    th = min(256 // Q, N * P)
+    while th >= 1:
+        segs = 1 if P % th == 0 else min(N, (th + P - 2) // P + 1)
+        rows = stride * (th - 1) + (segs - 1) * (hp - stride * P) + 8
+        if (rows * (wp // 2) * 16 + 4095) // 4096 * 4096 <= budget:
+            break
+        th -= 1
+    if th < 1 or th * Q * 4 < 256 * 3:
+        return 0
+    return th if (N * P + th - 1) // th * 4 >= CUS else 0
+
+
+@pytest.mark.parametrize("case", [
+    # N, C, H, W, K, R, stride, pad, K2
+    (16, 3, 224, 224, 64, 7, 4, 3, 64),     # the slim GoogLeNet's first two layers (Table 2: conv1 merged, then conv2's 1x1 reduction)
+    (40, 3, 81, 77, 24, 7, 4, 3, 40),       # ragged filter counts on both sides, tiles across image borders
+    (48, 1, 37, 39, 40, 3, 2, 0, 8),        # one input channel, the smallest 1x1
+    (72, 4, 40, 40, 56, 5, 2, 2, 64),
+])
+@pytest.mark.parametrize("relus", [(True, True), (False, True), (True, False)])
+def test_first_layer_and_1x1_in_one_kernel(case, relus):
+    """dr_net_fwd runs a first layer on up to 4 channels and a 1x1 convolution right behind it as ONE kernel that never
+    writes the tensor between them.  Against the oracle's composition, and against the library's own two layers run as two
+    networks (the tensor between them stored in bf16): the fused kernel rounds it to bf16 as well."""
+    from test_gpu_bf16_nets import run_net_bf16
+    N, C, H, W, K, R, stride, pad, K2 = case
+    assert tail_takes(*case) > 0
+    rng = np.random.default_rng(case_seed(case))
+    x = workloads.round_to_bf16(rng.standard_normal((N, C, H, W)).astype(np.float32))
+    w1 = workloads.round_to_bf16(rng.standard_normal((K, C, R, R)).astype(np.float32) * np.float32(np.sqrt(2.0 / (C * R * R))))
+    w2 = workloads.round_to_bf16(rng.standard_normal((K2, K, 1, 1)).astype(np.float32) * np.float32(np.sqrt(2.0 / K)))
+    b1 = (rng.standard_normal(K) * 0.1).astype(np.float32)
+    b2 = (rng.standard_normal(K2) * 0.1).astype(np.float32)
+    first = [workloads.conv(K, R, stride, pad)] + ([workloads.relu()] if relus[0] else [])
+    second = [workloads.conv(K2, 1, 1, 0)] + ([workloads.relu()] if relus[1] else [])
+    params = [{"w": w1, "b": b1}, {"w": w2, "b": b2}]
+    got = run_net_bf16(first + second, params, x, fuse_relu=True)
+    # the oracle with the tensor between the layers rounded to bf16, as both forms of the library hold it
+    mid = oracle.round_bf16(oracle.forward(first, params[:1], x)).astype(np.float32)
+    ref = oracle.forward(second, params[1:], mid)
+    assert got.shape == ref.shape
+    assert close(got, ref, TOL_BF16)
+    assert close(got, oracle.round_bf16(ref), 2.0 ** -7, "within one bf16 unit of the oracle")
+    # ... and the two layers as two networks
+    mid_gpu = run_net_bf16(first, params[:1], x, fuse_relu=True)
+    two = run_net_bf16(second, params[1:], mid_gpu, fuse_relu=True)
+    # (the same matrix instruction on the same operands in the same order of k-steps: the values are the same bits)
+    assert np.array_equal(got, two), "%d of %d values differ from the two layers run one after the other" % (int((got != two).sum()), got.size)
