@@ -83,6 +83,60 @@ __device__ __forceinline__ int div_small(int v, unsigned long long m)
     return (int)(((unsigned long long)(unsigned)v * m) >> 40);
 }
 
+// The persistent walk of the convolution kernels.  A launch has gn workgroups per filter block (grid of gn grid_m) and
+// `tiles` pixel tiles per filter block.  Workgroup ids are dealt to the 8 dies in turn (id & 7); the renumbering b gives
+// each die a contiguous range, so that the grid_m workgroups of one pixel tile (b / grid_m the same) and its neighbours share
+// an L2.  Workgroup b keeps filter block b % grid_m and visits tiles nt0, nt0 + gn, ... for the tiles / gn whole rounds.
+// The tiles left over (fewer than gn) go to the workgroups with the LOWEST ids among those of the same filter block: ids
+// are handed out across dies and, within a die, across compute units before a unit gets its second workgroup, so the
+// left-over round lands on as many different units of all dies as it has tiles -- not on the first dies' units only, which
+// is what "tile nt0 + rounds gn if it exists" does and which makes the launch as long as if the round were full.
+// (the host fills WalkArgs: the division by grid_m runs as a multiplication by magic_gm = ceil(2^32 / grid_m), exact for the
+// workgroup counts of a launch, far below 2^16)
+struct WalkArgs {
+    int grid_m, gn, full, rem;            // filter blocks; workgroups per filter block; whole rounds tiles / gn; tiles left over
+    unsigned magic_gm;
+};
+inline WalkArgs make_walk(int grid_m, int gn, int tiles)
+{
+    WalkArgs w;
+    w.grid_m = grid_m; w.gn = gn; w.full = tiles / gn; w.rem = tiles - w.full * gn;
+    w.magic_gm = grid_m > 1 ? (unsigned)((0x100000000ull + (unsigned)grid_m - 1) / (unsigned)grid_m) : 0u;
+    return w;
+}
+struct TileWalk {
+    int mt, nt0, gn, full, last, count;   // filter block; first tile; stride; whole rounds; the left-over tile; tiles of this workgroup
+    __device__ __forceinline__ int tile(int t) const { return t < full ? nt0 + t * gn : last; }
+};
+__device__ __forceinline__ TileWalk tile_walk(const WalkArgs& k)
+{
+    const int G = k.gn * k.grid_m, die = (int)(blockIdx.x & 7), s = (int)(blockIdx.x >> 3), per = G >> 3, odd = G & 7;
+    const int bid = die * per + min(die, odd) + s;
+    TileWalk w;
+    w.gn = k.gn; w.full = k.full;
+    int u;                                              // workgroups of the same filter block with a lower id
+    if (k.grid_m == 1) {
+        w.mt = 0; w.nt0 = bid; u = (int)blockIdx.x;
+    } else {
+        w.nt0 = (int)__umulhi((unsigned)bid, k.magic_gm);
+        w.mt = bid - w.nt0 * k.grid_m;
+        u = 0;
+        if (k.rem) {
+            for (int x = 0; x < 8; ++x) {
+                // die x holds ids x, x + 8, ...: renumbered first + s' for s' < len; those below this id: s' < s, and s' = s when x < die
+                const int first = x * per + min(x, odd), len = per + (x < odd ? 1 : 0);
+                const int L = min(len, s + (x < die ? 1 : 0));
+                int r = w.mt - (first - (int)__umulhi((unsigned)first, k.magic_gm) * k.grid_m);   // the s' with (first + s') % grid_m == mt are r, r + grid_m, ...
+                if (r < 0) r += k.grid_m;
+                u += L > r ? (int)__umulhi((unsigned)(L - 1 - r), k.magic_gm) + 1 : 0;
+            }
+        }
+    }
+    w.last = k.full * k.gn + u;
+    w.count = k.full + (u < k.rem ? 1 : 0);
+    return w;
+}
+
 // bits lo..hi set (hi < lo: none); lo, hi in 0..15
 __device__ __forceinline__ unsigned bit_range(int lo, int hi) { return hi >= lo ? (2u << hi) - (1u << lo) : 0u; }
 

@@ -52,6 +52,7 @@ struct DArgs {
     uint16_t* y;
     ConvGeom g;
     int grid_m, grid_n;       // tiles along m (channel blocks) and along n (pixel tiles)
+    WalkArgs wk;              // the persistent walk over them (tile_walk)
     int x_bytes, w_bytes;
     int c8;                   // C / 8: chunks per tap
     int run_chunks;           // S * C / 8: chunks per filter row
@@ -135,15 +136,9 @@ void conv_bf16_dma_kernel(const DArgs a)
     const __amdgpu_buffer_rsrc_t rbias = __builtin_amdgcn_make_buffer_rsrc((void*)a.bias, 0, a.bias ? g.K * 4 : 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc((void*)a.y, 0, a.exact_store ? a.y_bytes : 0, 0x00020000);
 
-    // ---- persistent walk: workgroup b keeps channel block mt = b % grid_m and visits the pixel tiles
-    // nt0, nt0 + gn, ... (gn = workgroups per channel block).  Consecutive workgroup ids are dealt
-    // round-robin to the 8 XCDs; the remap gives each XCD a contiguous range of b, so that the
-    // workgroups sharing a pixel tile share an L2.
-    const int G = gridDim.x;
-    const int xcd = blockIdx.x & 7;
-    const int bid = xcd * (G >> 3) + min(xcd, G & 7) + (blockIdx.x >> 3);
-    const int mt = bid % a.grid_m, nt0 = bid / a.grid_m, gn = G / a.grid_m;
-    const int my_tiles = (a.grid_n - nt0 + gn - 1) / gn;
+    // ---- persistent walk (tile_walk)
+    const TileWalk walk = tile_walk(a.wk);
+    const int mt = walk.mt, my_tiles = walk.count;
     const int nslices = a.slices_per_tile;
     const int total = my_tiles * nslices;
 
@@ -169,7 +164,7 @@ void conv_bf16_dma_kernel(const DArgs a)
     int b_base[B_PER];            // byte offset of x[img][ih0][iw0][lc * 8] (may lie outside the tensor)
     unsigned b_mask[B_PER];       // bits 0..15: tap s is OUTSIDE the image row; bits 16..31: filter row r is inside
     unsigned b_cur[B_PER];        // TAP: offset of the current tap or OOB;  else: b_mask with the current row's verdict
-    int ld_nt = nt0, ld_r = 0, ld_j0 = 0, ld_s = 0, ld_c = 0;   // wave-uniform cursor of the next slice to load
+    int ld_t = 0, ld_nt = walk.tile(0), ld_r = 0, ld_j0 = 0, ld_s = 0, ld_c = 0;   // wave-uniform cursor of the next slice to load
     int ld_fresh = 1;             // TAP = false: the cursor has entered a new filter row (its verdicts are due)
 
     // Per-lane state of pixel tile nt.  A 1x1 filter at stride 1 without padding reads input pixel n for
@@ -258,7 +253,7 @@ void conv_bf16_dma_kernel(const DArgs a)
                 ld_c = 0;
                 if (++ld_s == g.S) {
                     ld_s = 0;
-                    if (++ld_r == g.R) { ld_r = 0; ld_nt += gn; tile_setup(ld_nt); }
+                    if (++ld_r == g.R) { ld_r = 0; ld_nt = walk.tile(++ld_t); tile_setup(ld_nt); }
                 }
             }
         } else {
@@ -303,7 +298,7 @@ void conv_bf16_dma_kernel(const DArgs a)
             if (ld_j0 >= a.run_chunks) {
                 ld_j0 = a.flat ? ld_j0 - a.run_chunks : 0;
                 ld_fresh = 1;
-                if (++ld_r == g.R) { ld_r = 0; ld_j0 = 0; ld_nt += gn; tile_setup(ld_nt); }
+                if (++ld_r == g.R) { ld_r = 0; ld_j0 = 0; ld_nt = walk.tile(++ld_t); tile_setup(ld_nt); }
             }
         }
     };
@@ -680,9 +675,9 @@ void conv_bf16_dma_kernel(const DArgs a)
             }
             stage = next_stage;
         }
-        if constexpr (FUSE) epilogue_block(nt0 + t * gn);     // (one tile per workgroup: see launch_block)
-        else if (exact) { epilogue_exact(nt0 + t * gn); since_epi = 0; }
-        else epilogue(nt0 + t * gn);
+        if constexpr (FUSE) epilogue_block(walk.tile(t));     // (one tile per workgroup: see launch_block)
+        else if (exact) { epilogue_exact(walk.tile(t)); since_epi = 0; }
+        else epilogue(walk.tile(t));
     }
     wait_lgkm<0>();
 }
@@ -717,6 +712,7 @@ int launch_cfg(DArgs a, hipStream_t st)
     if (gn > a.grid_n) gn = a.grid_n;
     if (FUSE) gn = a.grid_n;                           // one patch per workgroup: its epilogue needs the whole ring
     const unsigned G = (unsigned)(gn * a.grid_m);
+    a.wk = make_walk(a.grid_m, gn, a.grid_n);
     if (a.g.C % KB == 0)
         hipLaunchKernelGGL((conv_bf16_dma_kernel<TM, TN, WGM, WGN, NS, true, OCC, KB, FUSE>), dim3(G), dim3(NTH), 0, st, a);
     else

@@ -34,6 +34,7 @@ struct PArgs {
     uint16_t* y;
     ConvGeom g;
     int grid_m, tiles, tiles_per_img;    // filter blocks; pixel tiles in all, per image
+    WalkArgs wk;                         // the persistent walk over them (tile_walk)
     int x_bytes, w_bytes, y_bytes;
     int c8, cblks;                       // C / 8, C / 64
     int TH, THQ;                         // output rows per tile, outputs per tile
@@ -84,13 +85,9 @@ void conv_bf16_patch_kernel(const PArgs a)
     const __amdgpu_buffer_rsrc_t rbias = __builtin_amdgcn_make_buffer_rsrc((void*)a.bias, 0, a.bias ? g.K * 4 : 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc((void*)a.y, 0, a.y_bytes, 0x00020000);
 
-    // ---- persistent walk: workgroup b keeps filter block mt = b % grid_m and visits the tiles nt0, nt0 + gn, ...; workgroup
-    // ids are renumbered so that each of the 8 dies (which take consecutive ids in turn) gets a contiguous range
-    const int G = gridDim.x;
-    const int xcd = blockIdx.x & 7;
-    const int bid = xcd * (G >> 3) + min(xcd, G & 7) + (blockIdx.x >> 3);
-    const int mt = bid % a.grid_m, nt0 = bid / a.grid_m, gn = G / a.grid_m;
-    const int my_tiles = nt0 < a.tiles ? (a.tiles - nt0 + gn - 1) / gn : 0;
+    // ---- persistent walk (tile_walk)
+    const TileWalk walk = tile_walk(a.wk);
+    const int mt = walk.mt, my_tiles = walk.count;
     const int R_ = FIXED ? 3 : g.R, S_ = FIXED ? 3 : g.S, CB_ = FIXED ? 1 : a.cblks;
     const int nslices = R_ * S_ * CB_;                  // slice sl = (tap, channel block), channel block fastest
 
@@ -225,12 +222,12 @@ void conv_bf16_patch_kernel(const PArgs a)
 #pragma unroll
         for (int tp = 0; tp < 9; ++tp) b_setup(tp / 3, tp % 3, 0, b_tap[tp]);
     }
-    issue_patch(nt0);
+    issue_patch(walk.tile(0));
     issue_a(0);
     if (nslices > 1) issue_a(1);
     int gi = 0;
     for (int t = 0; t < my_tiles; ++t) {
-        const int tt = nt0 + t * gn;
+        const int tt = walk.tile(t);
         // the patch and the first filter slice have landed: behind them are filter slice 1 and, from the second tile on, the stores
         if (nslices > 1) {
             if (t > 0) wait_vmcnt<A_PER + E>();
@@ -286,7 +283,7 @@ void conv_bf16_patch_kernel(const PArgs a)
         }
         if (t + 1 < my_tiles) {
             ring_barrier();                              // everybody has read the patch and both filter stages for the last time
-            issue_patch(tt + gn);
+            issue_patch(walk.tile(t + 1));
             issue_a(gi & 1);
             if (nslices > 1) issue_a((gi & 1) ^ 1);
         }
@@ -304,6 +301,7 @@ int launch_patch(PArgs a, hipStream_t st)
     int gn = device_cus() * OCC / a.grid_m;
     if (gn < 1) gn = 1;
     if (gn > a.tiles) gn = a.tiles;
+    a.wk = make_walk(a.grid_m, gn, a.tiles);
     hipLaunchKernelGGL((conv_bf16_patch_kernel<TM, OCC, FX>), dim3((unsigned)(gn * a.grid_m)), dim3(256), 0, st, a);
     return check_launch("conv_bf16_patch");
 }

@@ -36,6 +36,7 @@ struct RArgs {
     uint16_t* y;
     ConvGeom g;
     int grid_m, tiles;                   // filter blocks, pixel tiles
+    WalkArgs wk;                         // the persistent walk over them (tile_walk)
     int x_bytes, w_bytes, y_bytes;
     int TH, THQ;                         // stacked output rows per tile, outputs per tile
     int PW, NP, CCH, J;                  // patch row pitch (pixels); chunks per patch pixel (C / 8 + 1); C / 8; k-steps per tap
@@ -102,13 +103,9 @@ void conv_bf16_rows_kernel(const RArgs a)
     const __amdgpu_buffer_rsrc_t rbias = __builtin_amdgcn_make_buffer_rsrc((void*)a.bias, 0, a.bias ? g.K * 4 : 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc((void*)a.y, 0, a.y_bytes, 0x00020000);
 
-    // ---- persistent walk: workgroup b keeps filter block mt = b % grid_m and visits the tiles nt0, nt0 + gn, ...; workgroup
-    // ids are renumbered so that each of the 8 dies (which take consecutive ids in turn) gets a contiguous range
-    const int G = gridDim.x;
-    const int xcd = blockIdx.x & 7;
-    const int bid = xcd * (G >> 3) + min(xcd, G & 7) + (blockIdx.x >> 3);
-    const int mt = bid % a.grid_m, nt0 = bid / a.grid_m, gn = G / a.grid_m;
-    const int my_tiles = nt0 < a.tiles ? (a.tiles - nt0 + gn - 1) / gn : 0;
+    // ---- persistent walk (tile_walk)
+    const TileWalk walk = tile_walk(a.wk);
+    const int mt = walk.mt, my_tiles = walk.count;
     const int nslices = a.nslices;
 
     if (my_tiles == 0) return;                          // (whole workgroup, before anything is in flight; the launcher leaves no such workgroup)
@@ -229,13 +226,13 @@ void conv_bf16_rows_kernel(const RArgs a)
         p0 = g0 - img0 * g.P;
     };
     int img0, p0;
-    tile_origin(nt0, img0, p0);
+    tile_origin(walk.tile(0), img0, p0);
     issue_patch(img0, p0);
     issue_a(0);
     if (nslices > 1) issue_a(1);
     int gi = 0;
     for (int t = 0; t < my_tiles; ++t) {
-        const int tt = nt0 + t * gn;
+        const int tt = walk.tile(t);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int io = (int)__umulhi((unsigned)(p0 + dp[j]), a.magic_p);
@@ -285,7 +282,7 @@ void conv_bf16_rows_kernel(const RArgs a)
         const int nfirst = tt * a.THQ;                   // (a tile is TH whole rows of the stack: its outputs are consecutive)
         if (t + 1 < my_tiles) {
             ring_barrier();                              // everybody has read the patch and both filter stages for the last time
-            tile_origin(tt + gn, img0, p0);
+            tile_origin(walk.tile(t + 1), img0, p0);
             issue_patch(img0, p0);
             issue_a(gi & 1);
             if (nslices > 1) issue_a((gi & 1) ^ 1);
@@ -349,6 +346,7 @@ int launch_rows(RArgs a, int patch_bytes, hipStream_t st)
             return fail(DR_ERR_HIP, "conv_bf16_rows: cannot size the patch");
         sized = true;
     }
+    a.wk = make_walk(a.grid_m, gn, a.tiles);
     hipLaunchKernelGGL((conv_bf16_rows_kernel<TM, OCC, TAIL>), dim3((unsigned)(gn * a.grid_m)), dim3(256), (size_t)patch_bytes, st, a);
     return check_launch("conv_bf16_rows");
 }
