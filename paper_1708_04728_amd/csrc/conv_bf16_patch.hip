@@ -9,7 +9,10 @@
 // patch pixel and block of 64 channels.  Output pixel (dp, q) of the tile reads, for tap (r, s), patch pixel
 // (dp + r) PW + q + s: the same per-lane base for every tap, plus a wave-uniform offset.  Per tile and 64 channels the
 // loads are then (TH + R - 1) PW input rows once plus the filter slices, instead of R S TH Q input rows plus the filter
-// slices -- for 3x3 on 56 x 56 x 64 with 96 filters per workgroup a third of the bytes per multiply-add.
+// slices -- for 3x3 on 56 x 56 x 64 with 96 filters per workgroup a third of the bytes per multiply-add.  Where it takes
+// fewer tiles per image a tile is a run of HALF rows instead (PArgs): nine half rows of a 56 x 56 map are 252 outputs over
+// at most five output rows, 13 tiles per image instead of 14; a lane's patch pixel then depends on whether its tile starts in
+// mid-row and is set at the top of every tile.
 //
 // Everything else is the streaming kernel's: filters go through a two-stage ring of 64-deep slices, one tap and channel
 // block per slice, in (r, s, c) order (the same order of accumulation: results are bit-identical); LDS rows are swizzled
@@ -24,7 +27,8 @@
 namespace dr {
 namespace {
 
-constexpr int PATCH_ROWS = 352;          // LDS rows of 128 bytes the patch may take (patch pixels x 64-channel blocks)
+constexpr int PATCH_ROWS = 352;          // LDS rows of 128 bytes the patch of a tile of whole rows may take (patch pixels x 64-channel blocks): the rule
+constexpr int PATCH_CAP = 416;           // ... and what the kernel holds (a tile of half rows covers one input row more: 7 x 58 on 56 x 56 maps)
 constexpr int PATCH_BN = 256;            // pixel rows of a tile in the matrix instructions (TH Q of them carry outputs)
 
 struct PArgs {
@@ -37,9 +41,12 @@ struct PArgs {
     WalkArgs wk;                         // the persistent walk over them (tile_walk)
     int x_bytes, w_bytes, y_bytes;
     int c8, cblks;                       // C / 8, C / 64
-    int TH, THQ;                         // output rows per tile, outputs per tile
+    // A tile is TH consecutive SEGMENTS of one image: a segment is an output row (sh = 0) or half of one (sh = 1, QS = Q / 2
+    // outputs), numbered row by row.  Half rows fill the 256 pixel rows of a tile better on some maps (56 x 56: 9 half rows =
+    // 252 outputs and 13 tiles per image, against 4 rows = 224 outputs and 14 tiles).
+    int TH, THQ, QS, sh, segs;           // segments per tile, outputs per tile (TH QS), outputs per segment, log2 segments per row, segments per image
     int PW, PPN, PPB;                    // patch row pitch (pixels), patch pixels, 32-row load passes per channel block
-    unsigned magic_pw, magic_q;          // ceil(2^32 / PW), ceil(2^32 / Q)
+    unsigned magic_pw, magic_qs;         // ceil(2^32 / PW), ceil(2^32 / QS)
 };
 
 // TM: 32-filter blocks per workgroup (all four waves share them); a wave owns 64 of the tile's 256 pixel rows.
@@ -54,7 +61,7 @@ void conv_bf16_patch_kernel(const PArgs a)
     static_assert(TM >= 1 && TM <= 4 && A_PER + E < 63, "bad configuration");
 
     __shared__ __attribute__((aligned(1024))) unsigned char aring[NS * A_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char patch[PATCH_ROWS * 128];
+    __shared__ __attribute__((aligned(1024))) unsigned char patch[PATCH_CAP * 128];
     __shared__ __attribute__((aligned(1024))) float bias_lds[128];
     const unsigned aring_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)aring;
     const unsigned patch_lds = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)patch;
@@ -69,16 +76,21 @@ void conv_bf16_patch_kernel(const PArgs a)
     const int lc = (lane & 7) ^ ((lrow >> 1) & 7);
     // reader of the filter tile: LDS byte offset of this lane's chunk for k-step 0; k-step ks flips bits 5..6
     const unsigned a_rd = aring_lds + l32 * 128 + ((half << 4) ^ (((l32 >> 1) & 7) << 4));
-    // reader of the patch: patch pixel of tap (0, 0) for the pixel this lane holds in block j (rows beyond the tile's outputs
-    // multiply pixel 0 again; nothing of them is stored)
-    int nl[TN], row0[TN];
+    // reader of the patch: the pixel this lane holds in block j is output col[j] of segment seg[j] of the tile (rows beyond the
+    // tile's outputs multiply pixel 0 again; nothing of them is stored); row0[j]: its patch pixel for tap (0, 0), set per tile
+    int nl[TN], seg[TN], col[TN], row0[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         nl[j] = wave * 64 + j * 32 + l32;
         const int nn = nl[j] < a.THQ ? nl[j] : 0;
-        const int dp = (int)__umulhi((unsigned)nn, a.magic_q);
-        row0[j] = dp * a.PW + (nn - dp * g.Q);
+        seg[j] = (int)__umulhi((unsigned)nn, a.magic_qs);
+        col[j] = nn - seg[j] * a.QS;
     }
+    // tile tt: image, first segment; the patch starts pad_h input rows above output row (first segment >> sh)
+    auto tile_origin = [&](int tt, int& img, int& s0) __attribute__((always_inline)) {
+        img = tt / a.tiles_per_img;
+        s0 = (tt - img * a.tiles_per_img) * a.TH;
+    };
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)a.x, 0, a.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void*)a.w, 0, a.w_bytes, 0x00020000);
@@ -116,7 +128,9 @@ void conv_bf16_patch_kernel(const PArgs a)
         if (++ld_i == nslices) ld_i = 0;
     };
     auto issue_patch = [&](int tt) __attribute__((always_inline)) {
-        const int img = tt / a.tiles_per_img, p0 = (tt - img * a.tiles_per_img) * a.TH;
+        int img, s0;
+        tile_origin(tt, img, s0);
+        const int p0 = s0 >> a.sh;
         for (int cb = 0; cb < CB_; ++cb)
             for (int pb = 0; pb < a.PPB; ++pb) {
                 const int pp = pb * 32 + lrow;                                  // patch pixel this lane fetches
@@ -168,9 +182,9 @@ void conv_bf16_patch_kernel(const PArgs a)
 
     // bias + ReLU + bf16 store of the tile's outputs; every lane issues all E stores (see the streaming kernel's epilogue)
     auto epilogue = [&](int tt) __attribute__((always_inline)) {
-        const int img = tt / a.tiles_per_img, p0 = (tt - img * a.tiles_per_img) * a.TH;
-        const int rows_left = g.P - p0;                                   // output rows of the image from this tile on
-        const int nfirst = (img * g.P + p0) * g.Q;
+        int img, s0;
+        tile_origin(tt, img, s0);
+        const int segs_left = a.segs - s0;                                // segments of the image from this tile on
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             u32x4 bv[2][2];
@@ -182,8 +196,9 @@ void conv_bf16_patch_kernel(const PArgs a)
             touch(bv[0][0]); touch(bv[0][1]); touch(bv[1][0]); touch(bv[1][1]);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const bool n_ok = nl[j] < a.THQ && nl[j] < rows_left * g.Q;
-                const int nbase = ((nfirst + nl[j]) * g.y_ctot + g.y_coff) * 2;
+                const bool n_ok = nl[j] < a.THQ && seg[j] < segs_left;
+                const int gs = s0 + seg[j], pr = gs >> a.sh;              // the segment within the image, its output row
+                const int nbase = (((img * g.P + pr) * g.Q + (gs - (pr << a.sh)) * a.QS + col[j]) * g.y_ctot + g.y_coff) * 2;
 #pragma unroll
                 for (int qp = 0; qp < 2; ++qp) {
                     float o[8];
@@ -218,16 +233,26 @@ void conv_bf16_patch_kernel(const PArgs a)
     // slice 2 of tile t + 1 ...  Loads return in order, so "at most n operations outstanding" with n the number issued after
     // the awaited load means that load has landed; the stores only ever make such a wait longer.
     unsigned b_tap[FIXED ? 9 : 1][TN];                  // FIXED: this lane's patch address for each of the nine taps
-    if constexpr (FIXED) {
-#pragma unroll
-        for (int tp = 0; tp < 9; ++tp) b_setup(tp / 3, tp % 3, 0, b_tap[tp]);
-    }
     issue_patch(walk.tile(0));
     issue_a(0);
     if (nslices > 1) issue_a(1);
     int gi = 0;
     for (int t = 0; t < my_tiles; ++t) {
         const int tt = walk.tile(t);
+        {
+            // where this lane's pixels lie in the tile's patch (with half rows that depends on whether the tile starts in mid-row)
+            int img, s0;
+            tile_origin(tt, img, s0);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int gs = s0 + seg[j], pr = gs >> a.sh;
+                row0[j] = (pr - (s0 >> a.sh)) * a.PW + (gs - (pr << a.sh)) * a.QS + col[j];
+            }
+            if constexpr (FIXED) {
+#pragma unroll
+                for (int tp = 0; tp < 9; ++tp) b_setup(tp / 3, tp % 3, 0, b_tap[tp]);
+            }
+        }
         // the patch and the first filter slice have landed: behind them are filter slice 1 and, from the second tile on, the stores
         if (nslices > 1) {
             if (t > 0) wait_vmcnt<A_PER + E>();
@@ -296,7 +321,7 @@ template <int TM, int FX>
 int launch_patch(PArgs a, hipStream_t st)
 {
     constexpr int BM = TM * 32, OCC = 2;
-    static_assert(OCC * (2 * BM * 128 + PATCH_ROWS * 128 + 1024) <= 160 * 1024, "two workgroups per compute unit must fit LDS");
+    static_assert(OCC * (2 * BM * 128 + PATCH_CAP * 128 + 1024) <= 160 * 1024, "two workgroups per compute unit must fit LDS");
     a.grid_m = (a.g.K + BM - 1) / BM;
     int gn = device_cus() * OCC / a.grid_m;
     if (gn < 1) gn = 1;
@@ -339,14 +364,27 @@ int launch_conv_bf16_patch(const ConvGeom& g, const uint16_t* x, const uint16_t*
     a.c8 = g.C / 8; a.cblks = g.C / 64;
     a.TH = patch_rows_per_tile(g);
     if (a.TH < 1) return fail(DR_ERR_UNSUPPORTED, "conv_bf16_patch: layer not eligible");
-    a.THQ = a.TH * g.Q;
-    a.tiles_per_img = (g.P + a.TH - 1) / a.TH;
-    a.tiles = g.N * a.tiles_per_img;
     a.PW = g.W + 2 * g.pw;
-    a.PPN = (a.TH + g.R - 1) * a.PW;
+    a.QS = g.Q; a.sh = 0; a.segs = g.P;
+    a.tiles_per_img = (g.P + a.TH - 1) / a.TH;
+    int patch_rows = a.TH + g.R - 1;
+    if (g.Q % 2 == 0 && g.Q / 2 >= 2) {
+        // tiles of half rows where that takes fewer tiles per image: th2 half rows span at most th2 / 2 + 1 output rows
+        int th2 = PATCH_BN / (g.Q / 2);
+        if (th2 > 2 * g.P) th2 = 2 * g.P;
+        while (th2 >= 1 && a.cblks * (((th2 / 2 + 1 + g.R - 1) * a.PW + 31) / 32 * 32) > PATCH_CAP) --th2;
+        if (th2 >= 1 && (2 * g.P + th2 - 1) / th2 < a.tiles_per_img) {
+            a.TH = th2; a.QS = g.Q / 2; a.sh = 1; a.segs = 2 * g.P;
+            a.tiles_per_img = (2 * g.P + th2 - 1) / th2;
+            patch_rows = th2 / 2 + 1 + g.R - 1;
+        }
+    }
+    a.THQ = a.TH * a.QS;
+    a.tiles = g.N * a.tiles_per_img;
+    a.PPN = patch_rows * a.PW;
     a.PPB = (a.PPN + 31) / 32;
     a.magic_pw = (unsigned)((0x100000000ull + a.PW - 1) / a.PW);
-    a.magic_q = (unsigned)((0x100000000ull + g.Q - 1) / g.Q);
+    a.magic_qs = (unsigned)((0x100000000ull + a.QS - 1) / a.QS);
     // 96 filters per workgroup when that wastes fewer padded filter rows than 64
     const int pad96 = (g.K + 95) / 96 * 96, pad64 = (g.K + 63) / 64 * 64;
     if (tm == 0) tm = pad96 <= pad64 ? 3 : 2;
