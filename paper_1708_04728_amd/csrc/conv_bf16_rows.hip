@@ -20,6 +20,7 @@
 // offset of each k-step comes from three counters on the scalar unit.
 //
 // Pipeline, ring of filter slices, stores and waits are the patch kernel's (conv_bf16_patch.hip).
+#include <atomic>
 #include "dr_internal.h"
 #include "dr_store.h"
 #include "conv_bf16_dev.h"
@@ -340,11 +341,15 @@ int launch_rows(RArgs a, int patch_bytes, hipStream_t st)
     int gn = device_cus() * OCC / a.grid_m;
     if (gn < 1) gn = 1;
     if (gn > a.tiles) gn = a.tiles;
-    static bool sized = false;                           // (benign race: every thread sets the same value)
-    if (!sized) {
+    // the kernel's dynamic LDS limit, once per device (benign race: every thread stores the same value)
+    constexpr int MAX_DEV = 64;
+    static std::atomic<bool> sized[MAX_DEV];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return fail(DR_ERR_HIP, "conv_bf16_rows: no current device");
+    if (!sized[dev].load(std::memory_order_relaxed)) {
         if (hipFuncSetAttribute((const void*)conv_bf16_rows_kernel<TM, OCC, TAIL>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_PER_CU / 2) != hipSuccess)
             return fail(DR_ERR_HIP, "conv_bf16_rows: cannot size the patch");
-        sized = true;
+        sized[dev].store(true, std::memory_order_relaxed);
     }
     a.wk = make_walk(a.grid_m, gn, a.tiles);
     hipLaunchKernelGGL((conv_bf16_rows_kernel<TM, OCC, TAIL>), dim3((unsigned)(gn * a.grid_m)), dim3(256), (size_t)patch_bytes, st, a);
