@@ -320,7 +320,7 @@ int dr_net_workspace_bytes(const dr_net* net, const dr_tensor* xd, size_t* bytes
  * a 1x1 convolution with at most 64 filters right behind it run as ONE kernel when the first
  * layer's kernel takes the pair; the tensor between them (rounded to bf16 as it would be stored)
  * stays in registers and is never written.  Per-layer timing then books the kernel under the
- * first of the two layers and gives the second 0. */
+ * first of the two layers; the second shows only the gap between two event records. */
 int dr_net_fwd(dr_net* net, const dr_tensor* xd, const void* x, const void* const* params,
                const dr_tensor* yd, void* y, void* ws, size_t ws_bytes, void* stream);
 

@@ -209,3 +209,47 @@ def test_first_layer_and_1x1_in_one_kernel(case, relus):
     two = run_net_bf16(second, params[1:], mid_gpu, fuse_relu=True)
     # (the same matrix instruction on the same operands in the same order of k-steps: the values are the same bits)
     assert np.array_equal(got, two), "%d of %d values differ from the two layers run one after the other" % (int((got != two).sum()), got.size)
+
+
+def test_first_layer_pair_under_layer_timing_and_as_a_graph():
+    """The one-kernel pair with per-layer timing on (the kernel's time is booked under the first layer, the 1x1 gets the gap
+    between two event records)
+    and recorded into a HIP graph: the same bits as the plain call."""
+    from paper_1708_04728_amd import graph as G
+    case = (40, 3, 81, 77, 24, 7, 4, 3, 40)
+    N, C, H, W, K, R, stride, pad, K2 = case
+    assert tail_takes(*case) > 0
+    rng = np.random.default_rng(case_seed(case, 1))
+    x = workloads.round_to_bf16(rng.standard_normal((N, C, H, W)).astype(np.float32))
+    params = [{"w": workloads.round_to_bf16(rng.standard_normal((K, C, R, R)).astype(np.float32) * np.float32(0.1)),
+               "b": (rng.standard_normal(K) * 0.1).astype(np.float32)},
+              {"w": workloads.round_to_bf16(rng.standard_normal((K2, K, 1, 1)).astype(np.float32) * np.float32(0.2)),
+               "b": (rng.standard_normal(K2) * 0.1).astype(np.float32)}]
+    layers = [workloads.conv(K, R, stride, pad), workloads.relu(), workloads.conv(K2, 1, 1, 0), workloads.relu()]
+    xg = G.to_device(x, "bf16", nhwc=True)
+    net = B.Net(G.net_descs(layers, C, fuse_relu=True, pack="bf16"))
+    assert net.n_layers == 2
+    flat = G.flat_params(params, "bf16", pack=True)
+    ws = torch.empty(max(net.workspace_bytes(B.desc(xg)), 256), dtype=torch.uint8, device="cuda")
+    outs = []
+    for mode in ("plain", "timed", "graph"):
+        y = G.empty_like_desc(net.output_desc(B.desc(xg)))
+        if mode == "timed":
+            net.set_timing(True)
+            net.fwd(xg, flat, y, ws)
+            times = net.layer_times()
+            net.set_timing(False)
+            assert len(times) == 2 and times[0] > 0.0 and 0.0 <= times[1] < 0.01, times
+        elif mode == "graph":
+            side = torch.cuda.Stream()
+            g = net.capture(xg, flat, y, ws, side)
+            for _ in range(3):
+                g.launch(torch.cuda.current_stream())
+                torch.cuda.synchronize()
+        else:
+            net.fwd(xg, flat, y, ws)
+        torch.cuda.synchronize()
+        outs.append(G.to_host(y))
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    mid = oracle.round_bf16(oracle.forward(layers[:2], params[:1], x)).astype(np.float32)
+    assert close(outs[0], oracle.forward(layers[2:], params[1:], mid), TOL_BF16)
