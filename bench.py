@@ -128,6 +128,8 @@ def ceilings():
     lib.drc_mfma_bf16.argtypes = lib.drc_mfma_f32.argtypes = lib.drc_mfma_bf16_data.argtypes = [vp, i, i, vp]
     lib.drc_copy16.argtypes = [vp, vp, z, i, vp]
     lib.drc_read16.argtypes = [vp, vp, z, i, i, vp]
+    lib.drc_fill16.argtypes = [vp, z, i, vp]
+    lib.drc_kstep.argtypes = [i, vp, i, i, vp, vp]
     st = torch.cuda.current_stream()
     sp = vp(st.cuda_stream)
     out = torch.zeros(1024, dtype=torch.float32, device="cuda")
@@ -145,7 +147,7 @@ def ceilings():
             ts.append(e0.elapsed_time(e1))
         return min(ts)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    res = {"compute_units": cus, "mfma": {}, "copy": {}, "cache_read": {}}
+    res = {"compute_units": cus, "mfma": {}, "copy": {}, "fill": {}, "cache_read": {}, "kstep_cycles": {}}
     iters = 20000
     for wg_per_cu in (1, 2):
         blocks = cus * wg_per_cu
@@ -164,6 +166,24 @@ def ceilings():
         ms = best_ms(lambda: lib.drc_copy16(vp(src.data_ptr()), vp(dst.data_ptr()), n, cus * 8, sp))
         res["copy"]["%d_MiB_read_plus_write_GBs" % mib] = round(2.0 * n / (ms * 1e-3) / 1e9, 1)
         del src, dst
+    for mib in (64, 256, 1024):
+        n = mib << 20
+        dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+        ms = best_ms(lambda: lib.drc_fill16(vp(dst.data_ptr()), n, cus * 8, sp))
+        res["fill"]["%d_MiB_write_GBs" % mib] = round(float(n) / (ms * 1e-3) / 1e9, 1)
+        del dst
+    # one k-step of the bf16 convolutions' inner loop in isolation (6 matrix instructions = 192 cycles of matrix work on 5 LDS
+    # reads), shader-clock cycles per k-step and wave: one workgroup of four waves per compute unit, then two
+    filt = torch.ones(96 * 1152 + 4096, dtype=torch.uint8, device="cuda")
+    names = ("matrix_instructions_only", "with_lds_reads_one_step_ahead", "with_drain_and_barrier_every_4_steps", "with_next_filter_slice_by_dma")
+    for wg_per_cu in (1, 2):
+        blocks = cus * wg_per_cu
+        ticks = torch.zeros(4 * blocks, dtype=torch.float32, device="cuda")
+        for mode, name in enumerate(names):
+            assert lib.drc_kstep(mode, vp(ticks.data_ptr()), 2000, blocks, vp(filt.data_ptr()), sp) == 0
+            torch.cuda.synchronize()
+            t = ticks.cpu()
+            res["kstep_cycles"]["%s_%dwg_per_cu" % (name, wg_per_cu)] = {"mean": round(float(t.mean()), 1), "min": round(float(t.min()), 1), "max": round(float(t.max()), 1)}
     for kib in (64, 1024):
         n = kib << 10
         src = torch.ones(n, dtype=torch.uint8, device="cuda")
